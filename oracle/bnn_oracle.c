@@ -1,0 +1,205 @@
+/*
+ * CPU oracle for the forward pass of a feedforward acoustic model with binary
+ * (+1/-1) weights and, optionally, binary activations.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+ * GPU library must compute.  It shares no code, header, table or helper with the
+ * HIP path, and the product never calls it: only the tests, the smoke check and
+ * the benchmark's CPU-baseline leg may build or load it.
+ *
+ * Every function states the passage of the paper it follows (arXiv 1706.09453):
+ *   Eq. 1-2   layer:  h^_l = w_l h_{l-1} + r_l ,  h_l = f_l(h^_l)
+ *   Eq. 3     Sign(w) = +1 if w > 0, -1 otherwise (so Sign(0) = -1)
+ *   Alg. 1    forward with binary weights  w^b_l = Sign(w_l)
+ *   Alg. 2    forward with binary activations: Sign for l < L, Softmax for l = L
+ *   Sec. 2.3  with both binarised the products reduce to XOR operations
+ *
+ * Readings taken where the paper is silent (also listed in the design notes):
+ *   - bit encoding: bit 1 <=> +1; element k of a row lives in word k / wb, bit
+ *     k % wb counted from the least significant bit; pad bits are 0;
+ *   - per-layer scale alpha = mean|w| multiplies the product only:
+ *     h^ = alpha * (w^b h) + r, evaluated as ONE fused multiply-add in fp32;
+ *   - a real-input product is accumulated in fp32 in ascending k with one
+ *     accumulator per output (the order any output-stationary kernel can keep),
+ *     with an fp64 shadow sum for tolerance checks;
+ *   - the output layer returns log-Softmax, evaluated in fp64, rounded to fp32.
+ *
+ * Parity pins (tests/test_oracle_*.py): brute force against numpy's matmul on
+ * +-1 floats, the XOR/popcount identity and its closed forms, sign symmetry,
+ * numpy's sequential fp32 cumsum, exact rational arithmetic for the fused
+ * multiply-add, scipy's fp64 log-softmax, and hand-worked examples under
+ * tests/golden/.  The paper prints no worked numeric example, so no pin comes
+ * from printed values.
+ *
+ * Loops over frames carry an OpenMP pragma: frames are independent, the
+ * arithmetic inside one frame is untouched.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+#define ORC_API __attribute__((visibility("default")))
+
+/* Eq. 3: +1 if v > 0, -1 otherwise.  0, -0 and NaN all fail "v > 0" and give -1. */
+static inline int sign_pm1(float v) { return (v > 0.0f) ? 1 : -1; }
+
+/* Words per packed row: ceil(K / word_bits). */
+ORC_API int64_t orc_words_per_row(int64_t K, int word_bits) { return (K + word_bits - 1) / word_bits; }
+
+/*
+ * Eq. 3 applied elementwise, then the storage reading: element k -> word k/wb,
+ * bit k%wb (LSB first), bit = 1 for +1.  rows x K floats -> rows x Kw words.
+ */
+ORC_API void orc_pack_sign(const float* x, int64_t rows, int64_t K, int word_bits, void* out) {
+    const int64_t Kw = orc_words_per_row(K, word_bits);
+    if (word_bits == 32) {
+        uint32_t* o = (uint32_t*)out;
+        memset(o, 0, (size_t)(rows * Kw) * sizeof(uint32_t));
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t k = 0; k < K; ++k)
+                if (sign_pm1(x[r * K + k]) == 1) o[r * Kw + k / 32] |= (uint32_t)1 << (k % 32);
+    } else {
+        uint64_t* o = (uint64_t*)out;
+        memset(o, 0, (size_t)(rows * Kw) * sizeof(uint64_t));
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t k = 0; k < K; ++k)
+                if (sign_pm1(x[r * K + k]) == 1) o[r * Kw + k / 64] |= (uint64_t)1 << (k % 64);
+    }
+}
+
+/* Inverse of the storage reading: packed rows -> +1/-1 as int8, rows x K. */
+ORC_API void orc_unpack_pm1(const void* words, int64_t rows, int64_t K, int word_bits, int8_t* out) {
+    const int64_t Kw = orc_words_per_row(K, word_bits);
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < K; ++k) {
+            int bit;
+            if (word_bits == 32) bit = (int)((((const uint32_t*)words)[r * Kw + k / 32] >> (k % 32)) & 1u);
+            else                 bit = (int)((((const uint64_t*)words)[r * Kw + k / 64] >> (k % 64)) & 1u);
+            out[r * K + k] = bit ? 1 : -1;
+        }
+}
+
+/* Per-layer scale: mean of |w| over the real-valued weights, fp64 running sum in index order. */
+ORC_API float orc_mean_abs(const float* w, int64_t count) {
+    double s = 0.0;
+    for (int64_t i = 0; i < count; ++i) s += fabs((double)w[i]);
+    return (float)(s / (double)count);
+}
+
+/*
+ * Eq. 1 with both operands in {-1,+1}: dot[m][n] = sum_k a[m][k] * b[n][k].
+ * The plain definition, exact in int32.
+ */
+ORC_API void orc_dot_pm1(const int8_t* a, const int8_t* b, int64_t M, int64_t N, int64_t K, int32_t* dot) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int32_t s = 0;
+            for (int64_t k = 0; k < K; ++k) s += (int32_t)a[m * K + k] * (int32_t)b[n * K + k];
+            dot[m * N + n] = s;
+        }
+}
+
+/*
+ * Sec. 2.3: the same product on packed rows.  Equal bits multiply to +1 and
+ * differing bits to -1, so dot = (K - d) - d with d = popcount(a XOR b);
+ * zero pad bits are equal in both operands and add nothing to d.
+ */
+ORC_API void orc_dot_xor(const void* a, const void* b, int64_t M, int64_t N, int64_t K, int word_bits,
+                         int32_t* dot) {
+    const int64_t Kw = orc_words_per_row(K, word_bits);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t d = 0;
+            if (word_bits == 32) {
+                const uint32_t* ar = (const uint32_t*)a + m * Kw;
+                const uint32_t* br = (const uint32_t*)b + n * Kw;
+                for (int64_t w = 0; w < Kw; ++w) d += __builtin_popcount(ar[w] ^ br[w]);
+            } else {
+                const uint64_t* ar = (const uint64_t*)a + m * Kw;
+                const uint64_t* br = (const uint64_t*)b + n * Kw;
+                for (int64_t w = 0; w < Kw; ++w) d += __builtin_popcountll(ar[w] ^ br[w]);
+            }
+            dot[m * N + n] = (int32_t)(K - 2 * d);
+        }
+}
+
+/*
+ * Alg. 1 forward, product term with real input: acc[m][n] = sum_k w^b[n][k] * x[m][k],
+ * which is an add where w^b = +1 and a subtract where w^b = -1 (no multiplications).
+ * acc32: fp32, k ascending, one accumulator, every add/sub rounded to nearest.
+ * acc64: the same sum carried in fp64 (reference for tolerance checks).
+ */
+ORC_API void orc_realx_acc(const float* x, const int8_t* wpm1, int64_t M, int64_t N, int64_t K,
+                           float* acc32, double* acc64) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            float s32 = 0.0f; /* built without fast-math or contraction: the order below is the order executed */
+            double s64 = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                const float v = x[m * K + k];
+                if (wpm1[n * K + k] > 0) { s32 = s32 + v; s64 += (double)v; }
+                else                     { s32 = s32 - v; s64 -= (double)v; }
+            }
+            if (acc32) acc32[m * N + n] = s32;
+            if (acc64) acc64[m * N + n] = s64;
+        }
+}
+
+/*
+ * Eq. 1 with the per-layer scale: h^[m][n] = scale[n] * v[m][n] + bias[n] as one
+ * fp32 fused multiply-add (single rounding).  scale == NULL means 1, bias == NULL means 0.
+ */
+ORC_API void orc_affine_f32(const float* v, const float* scale, const float* bias, int64_t M, int64_t N,
+                            float* hhat) {
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n)
+            hhat[m * N + n] = fmaf(scale ? scale[n] : 1.0f, v[m * N + n], bias ? bias[n] : 0.0f);
+}
+
+/* The same affine map carried in fp64 from an fp64 product (tolerance reference, not a parity definition). */
+ORC_API void orc_affine_f64(const double* v, const float* scale, const float* bias, int64_t M, int64_t N,
+                            double* hhat) {
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n)
+            hhat[m * N + n] = (double)(scale ? scale[n] : 1.0f) * v[m * N + n] + (double)(bias ? bias[n] : 0.0f);
+}
+
+/* int32 -> fp32, exact for |dot| < 2^24. */
+ORC_API void orc_i32_to_f32(const int32_t* dot, int64_t count, float* out) {
+    for (int64_t i = 0; i < count; ++i) out[i] = (float)dot[i];
+}
+
+/* Real hidden nonlinearity of the real-activation configuration: clip to [-1, 1]. */
+ORC_API void orc_hardtanh(const float* hhat, int64_t count, float* out) {
+    for (int64_t i = 0; i < count; ++i) {
+        float v = hhat[i];
+        if (v > 1.0f) v = 1.0f;
+        if (v < -1.0f) v = -1.0f;
+        out[i] = v;
+    }
+}
+
+/*
+ * Alg. 2, last layer: Softmax over the N outputs of each frame, returned as
+ * log-posteriors: logp[n] = z[n] - max_j z[j] - log sum_j exp(z[j] - max_j z[j]).
+ * Evaluated in fp64 from the fp32 pre-activations; result kept in fp64 and also rounded to fp32.
+ */
+ORC_API void orc_log_softmax(const float* z, int64_t M, int64_t N, float* out32, double* out64) {
+    for (int64_t m = 0; m < M; ++m) {
+        const float* zr = z + m * N;
+        double mx = (double)zr[0];
+        for (int64_t n = 1; n < N; ++n) if ((double)zr[n] > mx) mx = (double)zr[n];
+        double s = 0.0;
+        for (int64_t n = 0; n < N; ++n) s += exp((double)zr[n] - mx);
+        const double lse = log(s);
+        for (int64_t n = 0; n < N; ++n) {
+            const double v = (double)zr[n] - mx - lse;
+            if (out64) out64[m * N + n] = v;
+            if (out32) out32[m * N + n] = (float)v;
+        }
+    }
+}

@@ -1,0 +1,144 @@
+"""Counter-based synthetic tensors with the shapes of hybrid DNN acoustic-model workloads.
+
+The paper's networks (Section 3: 40-dim filterbank features spliced over 11
+frames, six hidden layers of 1024 or 2048 units, a Softmax layer over a few
+thousand tied triphone states) are trained on speech corpora that are not
+available here, so every tensor is synthetic: features ~ N(0,1), real-valued
+"shadow" weights ~ U(-1,1) (to be binarised by whoever consumes them),
+biases ~ N(0, 0.1^2), and fair random bits for the isolated GEMM sweep.
+
+Every element is a pure function of (seed, tensor id, flat index) through a
+SplitMix64-style hash, so any slice of any tensor can be regenerated anywhere
+and both the CPU oracle and the GPU path are fed the very same bytes.
+Nothing in this module belongs to the method itself.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Tuple
+
+import numpy as np
+
+_U64 = np.uint64
+_GOLDEN = _U64(0x9E3779B97F4A7C15)
+_M1 = _U64(0xBF58476D1CE4E5B9)
+_M2 = _U64(0x94D049BB133111EB)
+
+TENSOR_W, TENSOR_BIAS, TENSOR_INPUT, TENSOR_ABITS, TENSOR_BBITS = 0, 1, 2, 3, 4
+
+
+def _mix(z: np.ndarray) -> np.ndarray:
+    """SplitMix64 finaliser on uint64 arrays (wrapping arithmetic)."""
+    z = (z ^ (z >> _U64(30))) * _M1
+    z = (z ^ (z >> _U64(27))) * _M2
+    return z ^ (z >> _U64(31))
+
+
+def _stream(seed: int, tensor_id: int, start: int, count: int, lane: int = 0) -> np.ndarray:
+    """uint64 hash of the counters (seed, tensor_id, lane, start..start+count-1)."""
+    with np.errstate(over="ignore"):
+        key = _mix(np.array([(seed * 0x1000003 + tensor_id * 0x10001 + lane * 0x101 + 1) & 0xFFFFFFFFFFFFFFFF],
+                            dtype=_U64) * _GOLDEN)[0]
+        idx = np.arange(start, start + count, dtype=_U64)
+        return _mix(key + (idx + _U64(1)) * _GOLDEN)
+
+
+def uniform_pm1(seed: int, tensor_id: int, count: int, start: int = 0) -> np.ndarray:
+    """fp32 samples on the grid (2i+1)/2^24 - 1, i in [0, 2^24): uniform on (-1, 1), never 0."""
+    i = (_stream(seed, tensor_id, start, count) >> _U64(40)).astype(np.int64)
+    return ((2 * i + 1 - (1 << 24)).astype(np.float64) / float(1 << 24)).astype(np.float32)
+
+
+def normal(seed: int, tensor_id: int, count: int, std: float = 1.0, start: int = 0) -> np.ndarray:
+    """fp32 N(0, std^2) samples: Box-Muller in fp64 from two hashed uniforms, rounded to fp32."""
+    a = _stream(seed, tensor_id, start, count, lane=0)
+    b = _stream(seed, tensor_id, start, count, lane=1)
+    u1 = ((a >> _U64(11)).astype(np.float64) + 1.0) / float(1 << 53)      # (0, 1]
+    u2 = (b >> _U64(11)).astype(np.float64) / float(1 << 53)              # [0, 1)
+    z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    return (z * std).astype(np.float32)
+
+
+def random_words(seed: int, tensor_id: int, rows: int, words_per_row: int, start_row: int = 0) -> np.ndarray:
+    """[rows, words_per_row] uint32 of fair random bits (every bit position is used)."""
+    n = rows * words_per_row
+    h = _stream(seed, tensor_id, start_row * words_per_row, n)
+    return (h >> _U64(32)).astype(np.uint32).reshape(rows, words_per_row)
+
+
+@dataclass(frozen=True)
+class NetConfig:
+    """One feedforward acoustic-model workload.
+
+    dims = [K0, hidden..., N_out]; hidden_act is "sign" (binary activations) or
+    "hardtanh" (real activations); the last layer always ends in log-softmax.
+    """
+    cfg_id: int
+    name: str
+    dims: Tuple[int, ...]
+    M: int
+    hidden_act: str
+    word_bits: int
+    seed: int = 0
+
+    @property
+    def n_layers(self) -> int:
+        return len(self.dims) - 1
+
+    def layer_shape(self, l: int) -> Tuple[int, int]:
+        """(K, N) of layer l (0-based)."""
+        return self.dims[l], self.dims[l + 1]
+
+    def macs_per_frame(self) -> int:
+        return sum(self.dims[l] * self.dims[l + 1] for l in range(self.n_layers))
+
+    def binbin_macs_per_frame(self) -> int:
+        if self.hidden_act != "sign":
+            return 0
+        return sum(self.dims[l] * self.dims[l + 1] for l in range(1, self.n_layers))
+
+
+@dataclass(frozen=True)
+class GemmShape:
+    M: int
+    K: int
+    N: int
+
+
+CONFIGS = {
+    1: NetConfig(1, "C1 tiny 440-3x512-1000 sign M=64", (440, 512, 512, 512, 1000), 64, "sign", 32),
+    2: NetConfig(2, "C2 binW/realX 440-6x2048-3400 hardtanh M=4096",
+                 (440,) + (2048,) * 6 + (3400,), 4096, "hardtanh", 32),
+    3: NetConfig(3, "C3 binW/binX 440-6x2048-3400 sign M=4096",
+                 (440,) + (2048,) * 6 + (3400,), 4096, "sign", 32),
+    4: NetConfig(4, "C4 binW/binX 440-6x4096-4000 sign M=16384 w64",
+                 (440,) + (4096,) * 6 + (4000,), 16384, "sign", 64),
+}
+
+GEMM_SWEEP: List[GemmShape] = [GemmShape(M, K, N)
+                               for M in (4096, 65536) for K in (2048, 8192) for N in (2048, 8192)]
+
+
+def get_config(cfg_id: int) -> NetConfig:
+    return CONFIGS[cfg_id]
+
+
+def _tid(cfg_id: int, layer: int, kind: int) -> int:
+    return 100 * cfg_id + 10 * layer + kind
+
+
+def make_net_params(cfg: NetConfig):
+    """Real-valued weights [N,K] ~ U(-1,1) and biases [N] ~ N(0, 0.1^2) for every layer."""
+    Ws, bs = [], []
+    for l in range(cfg.n_layers):
+        K, N = cfg.layer_shape(l)
+        Ws.append(uniform_pm1(cfg.seed, _tid(cfg.cfg_id, l + 1, TENSOR_W), N * K).reshape(N, K))
+        bs.append(normal(cfg.seed, _tid(cfg.cfg_id, l + 1, TENSOR_BIAS), N, std=0.1))
+    return Ws, bs
+
+
+def make_frames(cfg: NetConfig, M: int | None = None, start: int = 0) -> np.ndarray:
+    """Input frames [M, K0] ~ N(0,1); frames start..start+M-1 of the config's stream."""
+    M = cfg.M if M is None else M
+    K0 = cfg.dims[0]
+    return normal(cfg.seed, _tid(cfg.cfg_id, 0, TENSOR_INPUT), M * K0, start=start * K0).reshape(M, K0)
