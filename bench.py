@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Throughput of the binary-network forward pass on one MI355X.
+
+A step is one bnn_forward over one batch: Config 3 of the benchmark set (440 -> 6 x 2048 -> 3400, binary
+weights and binary activations, 4096 synthetic frames, 32-bit packed words), all seven layers, inputs and
+the packed model already resident in HBM.  Prints ONE JSON line with frames/s, binary TOPS, the roofline
+of the dominant kernel (timed live with HIP events on the launch stream) and the CPU oracle timed on the
+host cores on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--arm mfma|valu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+# Published MI355X peaks used as roofline denominators.
+PEAK_MFMA_FP4_TFLOPS = 10100.0          # dense fp4/fp6 MFMA
+PEAK_VALU_LANE_OPS = 256 * 4 * 16 * 2.4e9   # 256 CUs x 4 SIMD16 x 2.4 GHz = 39.3 T lane-ops/s
+PEAK_FP32_VALU_TFLOPS = 2 * PEAK_VALU_LANE_OPS / 1e12      # one v_fma_f32 per lane-op, unpacked: 78.6 TFLOP/s
+PEAK_XOR_POPC_TOPS = 2 * 32 * PEAK_VALU_LANE_OPS / 2 / 1e12  # xor + bcnt per 32 binary MACs: 1258 binary TOP/s
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--arm", choices=["mfma", "valu"], default="mfma")
+    ap.add_argument("--cpu-sample-frames", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (frames are independent; a multi-GPU run would just split "
+              "the batch with no communication). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_1706_09453_amd as bnn
+    import workloads
+    import gpu_util as G
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = workloads.CONFIGS[3]
+    M = cfg.M
+    Ws, bs = workloads.make_net_params(cfg)
+    X_host = workloads.make_frames(cfg)
+    model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
+    X = G.to_dev(X_host)
+    out = torch.empty((M, model.N_out), dtype=torch.float32, device=G.DEV)
+    arm = bnn.BNN_ARM_MFMA if args.arm == "mfma" else bnn.BNN_ARM_VALU_XOR
+    bnn.bnn_set_option(bnn.BNN_OPT_BINX_ARM, arm)
+
+    # ---- whole forward pass: W warm-up steps, then exactly K timed steps
+    for _ in range(args.warmup):
+        model.forward(X, out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        model.forward(X, out)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    dev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall_ms / args.steps
+    frames_per_s = M / (ms_per_step * 1e-3)
+
+    macs_all = cfg.macs_per_frame() * M
+    macs_bin = cfg.binbin_macs_per_frame() * M
+
+    # ---- per-layer kernels, same launch configuration, timed one layer at a time with HIP events
+    acts = [X]
+    ws_bits = [torch.empty((M, bnn.bnn_packed_words(d["N"], cfg.word_bits)), dtype=torch.int32, device=G.DEV)
+               for d in model.descs[:-1]]
+    layer_us = []
+    reps = max(20, min(args.steps, 200))
+    for l, d in enumerate(model.descs):
+        src = X if l == 0 else ws_bits[l - 1]
+        dst = out if l == model.n_layers - 1 else ws_bits[l]
+        fn = bnn.bnn_layer_binw_binx if d["x_is_binary"] else bnn.bnn_layer_binw_realx
+
+        def call():
+            fn(src.data_ptr(), d["Wp"], d["scale"], d["bias"], M, d["K"], d["N"], d["act"], d["word_bits"],
+               dst.data_ptr(), G.stream())
+        for _ in range(3):
+            call()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            call()
+        b.record()
+        torch.cuda.synchronize()
+        layer_us.append(a.elapsed_time(b) * 1e3 / reps)
+
+    # kernel groups: layer 1 (real input), hidden binary layers (one kernel, launched 5x per step), output layer
+    hidden_us = layer_us[1:-1]
+    groups = {
+        "realx_valu_kernel (layer 1, fp32 add/sub)": (layer_us[0], 1, 2.0 * M * cfg.dims[0] * cfg.dims[1]),
+        "binx hidden kernel (2048x2048, sign+repack)": (sum(hidden_us), len(hidden_us),
+                                                        2.0 * M * cfg.dims[1] * cfg.dims[2]),
+        "binx output kernel + log-softmax": (layer_us[-1], 1, 2.0 * M * cfg.dims[-2] * cfg.dims[-1]),
+    }
+    dominant = max(groups, key=lambda k: groups[k][0])
+    tot_us, launches, flops_per_launch = groups[dominant]
+    avg_us = tot_us / launches
+    achieved_tflops = flops_per_launch / (avg_us * 1e-6) / 1e12
+    if dominant.startswith("realx"):
+        bound, peak = "alu", PEAK_FP32_VALU_TFLOPS
+    elif args.arm == "mfma":
+        bound, peak = "mfma", PEAK_MFMA_FP4_TFLOPS
+    else:
+        bound, peak = "alu", PEAK_XOR_POPC_TOPS
+    roofline = {"bound": bound, "achieved": round(achieved_tflops, 3), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved_tflops / peak, 4), "traffic": None, "kernel": dominant,
+                "avg_launch_us": round(avg_us, 2), "launches_per_step": launches}
+
+    bin_us = sum(layer_us[1:])
+    result = {
+        "metric": "frames/sec, 6x2048 binarized DNN (binary weights and activations), batch 4096, 1xMI355X",
+        "value": round(frames_per_s, 1), "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "b1 (+-1 as fp4-e2m1 MFMA operands, exact fp32 accumulate) + f32" if args.arm == "mfma" else "b1 (xor+popcount u32) + f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "dims": list(cfg.dims), "batch_frames": M, "word_bits": cfg.word_bits,
+                   "binx_arm": args.arm},
+        "device_ms_per_step": round(dev_ms / args.steps, 5),
+        "binary_tops_all_layers": round(2.0 * macs_all / (ms_per_step * 1e-3) / 1e12, 2),
+        "binary_tops_binbin_kernels": round(2.0 * macs_bin / (bin_us * 1e-6) / 1e12, 2),
+        "layer_us": [round(v, 2) for v in layer_us],
+        "roofline": roofline,
+    }
+
+    # ---- the CPU oracle on the host cores, on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        S = min(args.cpu_sample_frames, M)
+        layers = orc.make_layers(Ws, bs, cfg.hidden_act, cfg.word_bits)
+        orc.forward(layers, X_host[:8], form="xor")                       # warm-up (loads the library)
+        t0 = time.perf_counter()
+        ref = orc.forward(layers, X_host[:S], form="xor")
+        dt = time.perf_counter() - t0
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        got = out[:S].cpu().numpy()
+        err = float(np.max(np.abs(got.astype(np.float64) - ref)))
+        result["cpu_baseline"] = {"value": round(S / dt, 1), "unit": "frames/s", "cores": cores, "kind": "oracle",
+                                  "sample": f"first {S} of the {M} frames, all 7 layers, XOR/popcount form, "
+                                            f"{dt:.2f} s wall",
+                                  "gpu_vs_oracle_max_abs_err": err,
+                                  "oracle_output_scale": float(np.max(np.abs(ref)))}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

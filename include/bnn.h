@@ -1,0 +1,167 @@
+/*
+ * bnn.h - C ABI of the MI355X (gfx950) forward pass for feedforward acoustic
+ * models with binary weights and, optionally, binary activations
+ * (arXiv 1706.09453, "Toward Computation and Memory Efficient Neural Network
+ * Acoustic Models with Binary Weights and Activations").
+ *
+ * What the library computes, per layer l (paper Eq. 1-2):
+ *     h^_l = scale_l * (w^b_l h_{l-1}) + r_l ,   h_l = f_l(h^_l)
+ * with w^b_l = Sign(w_l) (Eq. 3: +1 if w > 0, -1 otherwise, so Sign(0) = -1),
+ * f_l = Sign for binary hidden activations (Alg. 2 forward), hard-tanh for real
+ * hidden activations, and log-Softmax at the last layer (Alg. 2: Softmax at l = L).
+ * scale_l = 1 is the paper's layer; a per-layer scale mean|w_l| is what
+ * bnn_pack_weights reports.
+ *
+ * Conventions common to every call
+ *   - Every pointer is a DEVICE pointer unless marked HOST.  The caller owns all
+ *     memory; the library never allocates, frees or keeps a caller pointer.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work; they never synchronise.  Results are valid once the
+ *     stream has reached the end of the call's work.
+ *   - Matrices are row-major and dense.  Weights are [N][K] (N outputs, K inputs),
+ *     activations [M][K] (M frames), outputs [M][N].
+ *   - Packed rows: element k of a row is bit (k % word_bits) of word (k / word_bits),
+ *     least significant bit first, bit 1 <=> +1, words little-endian; a row holds
+ *     bnn_packed_words(K, word_bits) words and its pad bits are 0.  Every producer
+ *     here writes pad bits as 0 and every consumer assumes they are 0.  A 64-bit
+ *     packed row is byte-identical to the 32-bit packed row padded to a multiple of 8 bytes.
+ *   - word_bits is 32 or 64.  Packed pointers must be aligned to word_bits/8 bytes, fp32 pointers to 4.
+ *   - M, K and N are at most 2^30 (K < 2^24 for a binary input).
+ *   - Output buffers must not overlap input buffers.
+ *   - Return value: BNN_OK (0) or a negative bnn_status.  On error nothing has been
+ *     enqueued.  M == 0 is valid and does nothing.
+ */
+#ifndef BNN_H_
+#define BNN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum bnn_status {
+    BNN_OK = 0,
+    BNN_EINVAL = -1,     /* null pointer, unknown act / arm, act not allowed for this call, overlapping buffers */
+    BNN_ESHAPE = -2,     /* M < 0, K <= 0, N <= 0, word_bits not in {32, 64}, inconsistent layer chain */
+    BNN_EALIGN = -3,     /* a packed or fp32 pointer is not aligned as required */
+    BNN_EWORKSPACE = -4, /* workspace missing or smaller than bnn_forward_workspace_bytes() */
+    BNN_EDEVICE = -5     /* a HIP call failed (launch error) */
+} bnn_status;
+
+typedef enum bnn_act {
+    BNN_ACT_RAW_I32 = 0,   /* bnn_layer_binw_binx only: int32 product, scale and bias ignored            */
+    BNN_ACT_LINEAR = 1,    /* fp32 h^                                                                     */
+    BNN_ACT_HARDTANH = 2,  /* fp32 min(1, max(-1, h^))                                                    */
+    BNN_ACT_SIGN = 3,      /* packed bits of Sign(h^): bit = (h^ > 0), packed along n                     */
+    BNN_ACT_LOGSOFTMAX = 4 /* fp32 log-posteriors: h^ - max_n h^ - log sum_n exp(h^ - max_n h^)           */
+} bnn_act;
+
+/* Which arithmetic unit carries the binary x binary product (same results, different speed). */
+typedef enum bnn_binx_arm {
+    BNN_ARM_AUTO = 0,      /* the arm measurement showed to be faster for the shape */
+    BNN_ARM_VALU_XOR = 1,  /* v_xor + accumulating v_bcnt on packed words (Sec. 2.3 of the paper, literally) */
+    BNN_ARM_MFMA = 2       /* +-1 expanded in registers to a matrix-core operand format, MFMA accumulate    */
+} bnn_binx_arm;
+
+/* Kernel-selection knobs for bnn_set_option (measurement and tuning; results never change). */
+typedef enum bnn_option {
+    BNN_OPT_BINX_ARM = 1,      /* arm used for BNN_ARM_AUTO: BNN_ARM_VALU_XOR or BNN_ARM_MFMA                    */
+    BNN_OPT_REALX_TM = 2,      /* frames per wavefront of the real-input kernel: 8, 16 or 32                    */
+    BNN_OPT_BINX_VALU_TM = 3,  /* frames per wavefront of the XOR/popcount kernel: 8, 16 or 32                  */
+    BNN_OPT_MFMA_WM = 4        /* 16-row accumulator fragments per wavefront of the matrix-core kernel: 2 or 4  */
+} bnn_option;
+
+/* One layer of a network for bnn_forward.  HOST struct; the three pointers are DEVICE pointers. */
+typedef struct bnn_layer_desc {
+    int64_t K;            /* inputs                                                        */
+    int64_t N;            /* outputs                                                       */
+    int32_t act;          /* bnn_act of this layer (not BNN_ACT_RAW_I32)                   */
+    int32_t word_bits;    /* 32 or 64: packing of Wp, of a binary input and of a SIGN output */
+    int32_t x_is_binary;  /* 1: input is packed bits [M][Kw]; 0: input is fp32 [M][K]      */
+    int32_t reserved;     /* must be 0                                                      */
+    const void* Wp;       /* packed weights [N][Kw]                                         */
+    const float* scale;   /* [N] or NULL (= 1)                                              */
+    const float* bias;    /* [N] or NULL (= 0)                                              */
+} bnn_layer_desc;
+
+/* ceil(K / word_bits); 0 if K <= 0 or word_bits is not 32 or 64.  HOST helper. */
+size_t bnn_packed_words(int64_t K, int word_bits);
+
+/* Static, never-freed description of a status code.  HOST helper. */
+const char* bnn_status_string(int status);
+
+/* Set a kernel-selection knob (bnn_option) process-wide; BNN_EINVAL for an unknown option or value.  HOST helper. */
+int bnn_set_option(int option, int value);
+
+/*
+ * Binarise real-valued weights (Eq. 3; Alg. 1 forward, first step): Wp[n][k-bit] = (W[n][k] > 0).
+ *   W         fp32 [N][K]
+ *   Wp        out, words [N][bnn_packed_words(K, word_bits)]
+ *   scale_out out, nullable: ONE float = mean over all N*K elements of |W| (fp64 accumulation in a
+ *             fixed order, rounded once to fp32; deterministic)
+ */
+int bnn_pack_weights(const float* W, int64_t N, int64_t K, int word_bits, void* Wp, float* scale_out,
+                     void* stream);
+
+/*
+ * Binarise activations with the same Sign (Sec. 2.2): Xp[m][k-bit] = (X[m][k] > 0).
+ *   X  fp32 [M][K];  Xp out, words [M][bnn_packed_words(K, word_bits)]
+ * Inside bnn_forward this step is fused into the producing layer; this call is for standalone use.
+ */
+int bnn_pack_activations(const float* X, int64_t M, int64_t K, int word_bits, void* Xp, void* stream);
+
+/*
+ * One layer with binary weights and REAL input (Alg. 1 forward): the product is a sign-selected
+ * add/subtract, acc[m][n] = sum_k (Wp bit ? +X[m][k] : -X[m][k]), accumulated in fp32 in ascending k
+ * with one accumulator per output; then h^ = fmaf(scale[n], acc, bias[n]) and the activation.
+ *   X [M][K] fp32; Wp [N][Kw]; scale, bias [N] or NULL
+ *   act: LINEAR, HARDTANH, LOGSOFTMAX -> Y fp32 [M][N];  SIGN -> Y words [M][bnn_packed_words(N, word_bits)]
+ */
+int bnn_layer_binw_realx(const float* X, const void* Wp, const float* scale, const float* bias,
+                         int64_t M, int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream);
+
+/*
+ * One layer with binary weights and BINARY input (Sec. 2.3): dot[m][n] = sum_k x[m][k] w[n][k] over +-1
+ * values = K - 2 * popcount(Xp[m] XOR Wp[n]), exact in int32; then h^ = fmaf(scale[n], (float)dot, bias[n])
+ * and the activation.
+ *   Xp [M][Kw]; Wp [N][Kw]; K < 2^24
+ *   act: RAW_I32 -> Y int32 [M][N] (scale, bias ignored); LINEAR, HARDTANH, LOGSOFTMAX -> Y fp32 [M][N];
+ *        SIGN -> Y words [M][bnn_packed_words(N, word_bits)]
+ */
+int bnn_layer_binw_binx(const void* Xp, const void* Wp, const float* scale, const float* bias,
+                        int64_t M, int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream);
+
+/* As bnn_layer_binw_binx, with the arithmetic unit chosen by the caller (bnn_binx_arm); same results. */
+int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, const float* bias,
+                            int64_t M, int64_t K, int64_t N, int act, int word_bits, void* Y, int arm,
+                            void* stream);
+
+/*
+ * Bytes of scratch bnn_forward needs for M frames: two ping-pong buffers, each large enough for the
+ * largest inter-layer activation (packed bits or fp32), each 256-byte aligned.  0 for a one-layer net
+ * or on invalid arguments.  HOST helper; layers is a HOST array.
+ */
+size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M);
+
+/*
+ * Whole forward pass (Alg. 2 forward with Alg. 1's binary weights): layer 0 reads X, every layer reads the
+ * previous layer's output, the last layer writes `out`.
+ *   layers    HOST array of n_layers descriptors.  layers[0].x_is_binary says whether X is fp32 [M][K0] or
+ *             packed bits; for l > 0, x_is_binary must equal (layers[l-1].act == BNN_ACT_SIGN),
+ *             K must equal layers[l-1].N and word_bits must match across a binary link.
+ *   X         input of layer 0
+ *   out       output of the last layer: fp32 [M][N_last] (log-posteriors when its act is LOGSOFTMAX),
+ *             or packed bits when its act is SIGN
+ *   workspace DEVICE scratch of at least bnn_forward_workspace_bytes() bytes, 256-byte aligned
+ *             (may be NULL for a one-layer network)
+ * Enqueues one kernel per layer (two for a LOGSOFTMAX layer) on `stream`, no host synchronisation.
+ */
+int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BNN_H_ */

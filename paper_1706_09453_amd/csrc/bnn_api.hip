@@ -1,0 +1,339 @@
+// C ABI of the gfx950 binary-network forward pass: argument checks, kernel selection, launches.
+// See include/bnn.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdint>
+#include <cstring>
+
+#include "../../include/bnn.h"
+#include "mfma_kernels.hpp"
+#include "pack_kernels.hpp"
+#include "softmax_kernels.hpp"
+#include "valu_kernels.hpp"
+
+#define BNN_EXPORT extern "C" __attribute__((visibility("default")))
+
+namespace {
+
+using namespace bnn;
+
+// Tuning knobs (bnn_set_option).  Plain atomics: set from the host thread that benchmarks.
+std::atomic<int> g_default_arm{BNN_ARM_MFMA};
+std::atomic<int> g_realx_tm{16};
+std::atomic<int> g_binx_valu_tm{16};
+std::atomic<int> g_mfma_wm{4};
+
+inline bool word_bits_ok(int wb) { return wb == 32 || wb == 64; }
+inline int64_t words_per_row(int64_t K, int wb) { return (K + wb - 1) / wb; }
+// Row length in 32-bit words (a 64-bit word is two little-endian 32-bit words).
+inline int64_t row_w32(int64_t K, int wb) { return words_per_row(K, wb) * (wb / 32); }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline bool overlap(const void* a, size_t na, const void* b, size_t nb) {
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return na && nb && a0 < b0 + nb && b0 < a0 + na;
+}
+inline int launch_status() { return hipGetLastError() == hipSuccess ? BNN_OK : BNN_EDEVICE; }
+
+constexpr int64_t kMaxDim = (int64_t)1 << 30;
+
+size_t out_bytes(int64_t M, int64_t N, int act, int wb) {
+    if (act == BNN_ACT_SIGN) return (size_t)M * (size_t)row_w32(N, wb) * 4;
+    return (size_t)M * (size_t)N * 4;
+}
+
+int check_layer_args(const void* X, const void* Wp, int64_t M, int64_t K, int64_t N, int act, int wb, const void* Y,
+                     bool binx) {
+    if (!word_bits_ok(wb) || M < 0 || K <= 0 || N <= 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim) return BNN_ESHAPE;
+    if (binx && K >= ((int64_t)1 << 24)) return BNN_ESHAPE;
+    if (act < BNN_ACT_RAW_I32 || act > BNN_ACT_LOGSOFTMAX) return BNN_EINVAL;
+    if (!binx && act == BNN_ACT_RAW_I32) return BNN_EINVAL;
+    if (M == 0) return BNN_OK;
+    if (!X || !Wp || !Y) return BNN_EINVAL;
+    if (!aligned(Wp, wb / 8)) return BNN_EALIGN;
+    if (!aligned(X, binx ? wb / 8 : 4)) return BNN_EALIGN;
+    if (!aligned(Y, act == BNN_ACT_SIGN ? wb / 8 : 4)) return BNN_EALIGN;
+    const size_t xb = binx ? (size_t)M * row_w32(K, wb) * 4 : (size_t)M * K * 4;
+    const size_t wbytes = (size_t)N * row_w32(K, wb) * 4;
+    const size_t yb = out_bytes(M, N, act, wb);
+    if (overlap(X, xb, Y, yb) || overlap(Wp, wbytes, Y, yb)) return BNN_EINVAL;
+    return BNN_OK;
+}
+
+// ---------------------------------------------------------------- launches (arguments already checked)
+
+template <int TM>
+void launch_realx_tm(const float* X, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
+                     int w32, int act, void* Y, int yw32, hipStream_t st) {
+    const dim3 grid((M + TM - 1) / TM, (N + 255) / 256), block(256);
+    switch (act) {
+        case BNN_ACT_SIGN:
+            realx_valu_kernel<TM, ACT_SIGN><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_HARDTANH:
+            realx_valu_kernel<TM, ACT_HARDTANH><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        default:
+            realx_valu_kernel<TM, ACT_LINEAR><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+    }
+}
+
+void launch_log_softmax(float* Z, int M, int N, hipStream_t st) {
+    log_softmax_rows_kernel<<<dim3(M < 65536 ? M : 65536), dim3(256), 0, st>>>(Z, M, N);
+}
+
+int run_realx(const float* X, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K, int64_t N,
+              int act, int wb, void* Y, hipStream_t st) {
+    if (M == 0) return BNN_OK;
+    const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
+    const uint32_t* W = static_cast<const uint32_t*>(Wp);
+    switch (g_realx_tm.load()) {
+        case 8: launch_realx_tm<8>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
+        case 32: launch_realx_tm<32>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
+        default: launch_realx_tm<16>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
+    }
+    if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(static_cast<float*>(Y), (int)M, (int)N, st);
+    return launch_status();
+}
+
+template <int TM, bool VEC4>
+void launch_binx_valu_tm(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K,
+                         int N, int w32, int act, void* Y, int yw32, hipStream_t st) {
+    const dim3 grid((M + TM - 1) / TM, (N + 255) / 256), block(256);
+    switch (act) {
+        case BNN_ACT_RAW_I32:
+            binx_valu_kernel<TM, ACT_RAW_I32, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_SIGN:
+            binx_valu_kernel<TM, ACT_SIGN, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_HARDTANH:
+            binx_valu_kernel<TM, ACT_HARDTANH, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        default:
+            binx_valu_kernel<TM, ACT_LINEAR, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+    }
+}
+
+template <int WM, bool AL>
+void launch_binx_mfma_wm(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K,
+                         int N, int w32, int act, void* Y, int yw32, hipStream_t st) {
+    constexpr int WN = 4;
+    const dim3 grid((M + 32 * WM - 1) / (32 * WM), (N + 32 * WN - 1) / (32 * WN)), block(256);
+    switch (act) {
+        case BNN_ACT_RAW_I32:
+            binx_mfma_kernel<WM, WN, ACT_RAW_I32, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_SIGN:
+            binx_mfma_kernel<WM, WN, ACT_SIGN, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_HARDTANH:
+            binx_mfma_kernel<WM, WN, ACT_HARDTANH, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        default:
+            binx_mfma_kernel<WM, WN, ACT_LINEAR, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+    }
+}
+
+int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K, int64_t N,
+             int act, int wb, void* Y, int arm, hipStream_t st) {
+    if (M == 0) return BNN_OK;
+    if (arm == BNN_ARM_AUTO) arm = g_default_arm.load();
+    const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
+    const uint32_t* A = static_cast<const uint32_t*>(Xp);
+    const uint32_t* B = static_cast<const uint32_t*>(Wp);
+    const bool rows16 = (w32 % 4 == 0) && aligned(Xp, 16) && aligned(Wp, 16);
+    const int Mi = (int)M, Ki = (int)K, Ni = (int)N;
+    if (arm == BNN_ARM_VALU_XOR) {
+        const int tm = g_binx_valu_tm.load();
+        if (rows16) {
+            if (tm == 8) launch_binx_valu_tm<8, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else if (tm == 32) launch_binx_valu_tm<32, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_valu_tm<16, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        } else {
+            if (tm == 8) launch_binx_valu_tm<8, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else if (tm == 32) launch_binx_valu_tm<32, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_valu_tm<16, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        }
+    } else {
+        const bool al = rows16 && (K % 512 == 0);
+        const int wm = g_mfma_wm.load();
+        if (al) {
+            if (wm == 2) launch_binx_mfma_wm<2, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_mfma_wm<4, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        } else {
+            if (wm == 2) launch_binx_mfma_wm<2, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_mfma_wm<4, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        }
+    }
+    if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(static_cast<float*>(Y), Mi, Ni, st);
+    return launch_status();
+}
+
+int run_pack(const float* X, int64_t rows, int64_t K, int wb, void* out, hipStream_t st) {
+    if (rows == 0) return BNN_OK;
+    const int64_t chunks = (K + 63) / 64;
+    const int64_t tasks = rows * chunks;
+    int64_t blocks = (tasks + 3) / 4;
+    if (blocks > 65536 * 4) blocks = 65536 * 4;
+    pack_sign_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(X, rows, K, row_w32(K, wb),
+                                                                    static_cast<uint32_t*>(out));
+    return launch_status();
+}
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
+    if (!L || n_layers <= 0) return BNN_EINVAL;
+    if (M < 0 || M > kMaxDim) return BNN_ESHAPE;
+    for (int l = 0; l < n_layers; ++l) {
+        const bnn_layer_desc& d = L[l];
+        if (!word_bits_ok(d.word_bits) || d.K <= 0 || d.N <= 0 || d.K > kMaxDim || d.N > kMaxDim) return BNN_ESHAPE;
+        if (d.act < BNN_ACT_LINEAR || d.act > BNN_ACT_LOGSOFTMAX || d.reserved != 0) return BNN_EINVAL;
+        if (d.x_is_binary != 0 && d.x_is_binary != 1) return BNN_EINVAL;
+        if (!d.Wp) return BNN_EINVAL;
+        if (l > 0) {
+            const bnn_layer_desc& p = L[l - 1];
+            if (d.K != p.N) return BNN_ESHAPE;
+            if (d.x_is_binary != (p.act == BNN_ACT_SIGN ? 1 : 0)) return BNN_ESHAPE;
+            if (d.x_is_binary && d.word_bits != p.word_bits) return BNN_ESHAPE;
+            if (p.act == BNN_ACT_LOGSOFTMAX) return BNN_ESHAPE;   // Softmax only closes a network (Alg. 2)
+        }
+    }
+    return BNN_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------ C ABI
+
+BNN_EXPORT size_t bnn_packed_words(int64_t K, int word_bits) {
+    if (K <= 0 || !word_bits_ok(word_bits)) return 0;
+    return (size_t)words_per_row(K, word_bits);
+}
+
+BNN_EXPORT const char* bnn_status_string(int status) {
+    switch (status) {
+        case BNN_OK: return "ok";
+        case BNN_EINVAL: return "invalid argument (null pointer, unknown activation or arm, overlapping buffers)";
+        case BNN_ESHAPE: return "invalid shape (M < 0, K or N <= 0, word_bits not 32/64, or inconsistent layer chain)";
+        case BNN_EALIGN: return "misaligned pointer";
+        case BNN_EWORKSPACE: return "workspace missing or too small";
+        case BNN_EDEVICE: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+BNN_EXPORT int bnn_set_option(int option, int value) {
+    switch (option) {
+        case BNN_OPT_BINX_ARM:
+            if (value != BNN_ARM_VALU_XOR && value != BNN_ARM_MFMA) return BNN_EINVAL;
+            g_default_arm.store(value);
+            return BNN_OK;
+        case BNN_OPT_REALX_TM:
+            if (value != 8 && value != 16 && value != 32) return BNN_EINVAL;
+            g_realx_tm.store(value);
+            return BNN_OK;
+        case BNN_OPT_BINX_VALU_TM:
+            if (value != 8 && value != 16 && value != 32) return BNN_EINVAL;
+            g_binx_valu_tm.store(value);
+            return BNN_OK;
+        case BNN_OPT_MFMA_WM:
+            if (value != 2 && value != 4) return BNN_EINVAL;
+            g_mfma_wm.store(value);
+            return BNN_OK;
+        default: return BNN_EINVAL;
+    }
+}
+
+BNN_EXPORT int bnn_pack_weights(const float* W, int64_t N, int64_t K, int word_bits, void* Wp, float* scale_out,
+                                void* stream) {
+    if (!word_bits_ok(word_bits) || N <= 0 || K <= 0 || N > kMaxDim || K > kMaxDim) return BNN_ESHAPE;
+    if (!W || !Wp) return BNN_EINVAL;
+    if (!aligned(W, 4) || !aligned(Wp, word_bits / 8) || (scale_out && !aligned(scale_out, 4))) return BNN_EALIGN;
+    const size_t wb = (size_t)N * K * 4, pb = (size_t)N * row_w32(K, word_bits) * 4;
+    if (overlap(W, wb, Wp, pb) || (scale_out && (overlap(W, wb, scale_out, 4) || overlap(Wp, pb, scale_out, 4))))
+        return BNN_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int rc = run_pack(W, N, K, word_bits, Wp, st);
+    if (rc != BNN_OK) return rc;
+    if (scale_out) {
+        mean_abs_kernel<<<dim3(1), dim3(1024), 0, st>>>(W, N * K, scale_out);
+        return launch_status();
+    }
+    return BNN_OK;
+}
+
+BNN_EXPORT int bnn_pack_activations(const float* X, int64_t M, int64_t K, int word_bits, void* Xp, void* stream) {
+    if (!word_bits_ok(word_bits) || M < 0 || K <= 0 || M > kMaxDim || K > kMaxDim) return BNN_ESHAPE;
+    if (M == 0) return BNN_OK;
+    if (!X || !Xp) return BNN_EINVAL;
+    if (!aligned(X, 4) || !aligned(Xp, word_bits / 8)) return BNN_EALIGN;
+    if (overlap(X, (size_t)M * K * 4, Xp, (size_t)M * row_w32(K, word_bits) * 4)) return BNN_EINVAL;
+    return run_pack(X, M, K, word_bits, Xp, static_cast<hipStream_t>(stream));
+}
+
+BNN_EXPORT int bnn_layer_binw_realx(const float* X, const void* Wp, const float* scale, const float* bias, int64_t M,
+                                    int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream) {
+    const int rc = check_layer_args(X, Wp, M, K, N, act, word_bits, Y, false);
+    if (rc != BNN_OK) return rc;
+    return run_realx(X, Wp, scale, bias, M, K, N, act, word_bits, Y, static_cast<hipStream_t>(stream));
+}
+
+BNN_EXPORT int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M,
+                                       int64_t K, int64_t N, int act, int word_bits, void* Y, int arm, void* stream) {
+    if (arm != BNN_ARM_AUTO && arm != BNN_ARM_VALU_XOR && arm != BNN_ARM_MFMA) return BNN_EINVAL;
+    const int rc = check_layer_args(Xp, Wp, M, K, N, act, word_bits, Y, true);
+    if (rc != BNN_OK) return rc;
+    return run_binx(Xp, Wp, scale, bias, M, K, N, act, word_bits, Y, arm, static_cast<hipStream_t>(stream));
+}
+
+BNN_EXPORT int bnn_layer_binw_binx(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M,
+                                   int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream) {
+    return bnn_layer_binw_binx_arm(Xp, Wp, scale, bias, M, K, N, act, word_bits, Y, BNN_ARM_AUTO, stream);
+}
+
+BNN_EXPORT size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M) {
+    if (check_chain(layers, n_layers, M) != BNN_OK || n_layers < 2) return 0;
+    size_t biggest = 0;
+    for (int l = 0; l + 1 < n_layers; ++l) {
+        const size_t b = out_bytes(M, layers[l].N, layers[l].act, layers[l].word_bits);
+        if (b > biggest) biggest = b;
+    }
+    return 2 * round_up(biggest, 256);
+}
+
+BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_chain(layers, n_layers, M);
+    if (rc != BNN_OK) return rc;
+    if (M == 0) return BNN_OK;
+    if (!X || !out) return BNN_EINVAL;
+    const size_t need = bnn_forward_workspace_bytes(layers, n_layers, M);
+    if (need && (!workspace || workspace_bytes < need)) return BNN_EWORKSPACE;
+    if (need && !aligned(workspace, 256)) return BNN_EALIGN;
+    // Check every layer's arguments before anything is enqueued.
+    char* buf[2] = {static_cast<char*>(workspace), static_cast<char*>(workspace) + need / 2};
+    for (int pass = 0; pass < 2; ++pass) {
+        const void* in = X;
+        for (int l = 0; l < n_layers; ++l) {
+            const bnn_layer_desc& d = layers[l];
+            void* o = (l == n_layers - 1) ? out : static_cast<void*>(buf[l & 1]);
+            if (pass == 0) {
+                rc = check_layer_args(in, d.Wp, M, d.K, d.N, d.act, d.word_bits, o, d.x_is_binary != 0);
+            } else if (d.x_is_binary) {
+                rc = run_binx(in, d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o, BNN_ARM_AUTO,
+                              static_cast<hipStream_t>(stream));
+            } else {
+                rc = run_realx(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o,
+                               static_cast<hipStream_t>(stream));
+            }
+            if (rc != BNN_OK) return rc;
+            in = o;
+        }
+    }
+    return BNN_OK;
+}

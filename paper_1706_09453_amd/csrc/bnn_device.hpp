@@ -1,0 +1,36 @@
+// Device-side helpers shared by the gfx950 kernels of the binary-network forward pass.
+// Written for CDNA4 only: 64-wide wavefronts, no portability layer.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bnn {
+
+constexpr int kWave = 64;
+
+// Activation selectors; numerically identical to bnn_act in include/bnn.h.
+enum : int { ACT_RAW_I32 = 0, ACT_LINEAR = 1, ACT_HARDTANH = 2, ACT_SIGN = 3, ACT_LOGSOFTMAX = 4 };
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+
+// Eq. 3 of the paper: +1 exactly when v > 0 (0, -0 and NaN give -1, i.e. bit 0).
+__device__ __forceinline__ bool sign_bit(float v) { return v > 0.0f; }
+
+// Eq. 1 with the per-layer scale: one fused multiply-add, a single rounding.
+__device__ __forceinline__ float affine(float scale, float v, float bias) { return __builtin_fmaf(scale, v, bias); }
+
+__device__ __forceinline__ float hardtanh(float v) {
+    v = v > 1.0f ? 1.0f : v;
+    v = v < -1.0f ? -1.0f : v;
+    return v;
+}
+
+// +1.0f or -1.0f from bit `pos` of `inv` where inv holds the COMPLEMENT of the weight bits
+// (weight bit 1 <=> +1 <=> float sign bit clear).
+__device__ __forceinline__ float pm1_from_inverted_bit(uint32_t inv, int pos) {
+    const uint32_t s = (inv << (31 - pos)) & 0x80000000u;
+    return __uint_as_float(s | 0x3f800000u);
+}
+
+}  // namespace bnn

@@ -1,0 +1,161 @@
+// Vector-ALU kernels: lanes <-> outputs n, frames streamed through scalar registers.
+//
+//   realx_valu_kernel  binary weights x real input   (paper Alg. 1 forward: add/subtract product)
+//   binx_valu_kernel   binary weights x binary input (paper Sec. 2.3: XOR + popcount)
+//
+// Both are output-stationary: one wavefront owns 64 outputs n (one per lane) for TM frames, so every
+// output has exactly one accumulator and one writer.  What a lane needs of the weights is its own
+// packed row (vector loads); what it needs of the frames is the same for all 64 lanes, so the frame
+// operands are wave-uniform and arrive through the scalar cache as SGPR operands of the VALU
+// instruction: no LDS traffic and no cross-lane exchange in the inner loop.
+#pragma once
+
+#include "bnn_device.hpp"
+
+namespace bnn {
+
+// Epilogue for the lanes<->n layout.  v[i] is the product term of frame m0+i and output n (this lane).
+//   ACT_RAW_I32            Y int32 [M][N]          (vi[i], no affine step)
+//   ACT_LINEAR / HARDTANH  Y fp32  [M][N]
+//   ACT_SIGN               Y words [M][yw32]       one ballot per frame packs the 64 outputs of the wave
+template <int TM, int ACT>
+__device__ __forceinline__ void epilogue_lanes_n(const float (&v)[TM], const int (&vi)[TM], const float* __restrict__ scale,
+                                                 const float* __restrict__ bias, int m0, int M, int n0, int n, int N,
+                                                 void* __restrict__ Y, int yw32) {
+    const bool nvalid = n < N;
+    const int lane = lane_id();
+    if constexpr (ACT == ACT_RAW_I32) {
+        int* Yi = (int*)Y;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            if (nvalid && m0 + i < M) Yi[(size_t)(m0 + i) * N + n] = vi[i];
+    } else {
+        const float sc = (scale && nvalid) ? scale[n] : 1.0f;
+        const float bi = (bias && nvalid) ? bias[n] : 0.0f;
+        if constexpr (ACT == ACT_SIGN) {
+            unsigned long long mine = 0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const bool p = nvalid && sign_bit(affine(sc, v[i], bi));
+                const unsigned long long mask = __ballot(p);
+                if (lane == i) mine = mask;
+            }
+            if (lane < TM && m0 + lane < M) {
+                uint32_t* yr = (uint32_t*)Y + (size_t)(m0 + lane) * yw32;
+                const int w = n0 >> 5;
+                yr[w] = (uint32_t)mine;
+                if (w + 1 < yw32) yr[w + 1] = (uint32_t)(mine >> 32);
+            }
+        } else {
+            float* Yf = (float*)Y;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                float h = affine(sc, v[i], bi);
+                if constexpr (ACT == ACT_HARDTANH) h = hardtanh(h);
+                if (nvalid && m0 + i < M) Yf[(size_t)(m0 + i) * N + n] = h;
+            }
+        }
+    }
+}
+
+// acc[m][n] = sum_k (w[n][k] ? +x[m][k] : -x[m][k]) in fp32, k ascending, one accumulator per output:
+// each step is fma(+-1.0f, x, acc), which rounds exactly like acc +- x.  The +-1.0f is built per lane
+// from the lane's weight bit (2 VALU ops per k, shared by the TM frames), x[m][k] is an SGPR operand.
+// Grid: x = ceil(M / TM), y = ceil(N / 256) (4 waves x 64 outputs).
+template <int TM, int ACT>
+__global__ __launch_bounds__(256) void realx_valu_kernel(const float* __restrict__ X, const uint32_t* __restrict__ Wp,
+                                                         const float* __restrict__ scale, const float* __restrict__ bias,
+                                                         int M, int K, int N, int w32, void* __restrict__ Y, int yw32) {
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = lane_id();
+    const int n0 = ((int)blockIdx.y * 4 + wave) * kWave;
+    if (n0 >= N) return;
+    const int n = n0 + lane;
+    const int m0 = (int)blockIdx.x * TM;
+    const uint32_t* wrow = Wp + (size_t)(n < N ? n : N - 1) * w32;
+
+    const float* xr[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) xr[i] = X + (size_t)(m0 + i < M ? m0 + i : M - 1) * K;
+
+    float acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) acc[i] = 0.0f;
+
+    const int kfull = K >> 5;
+    for (int kw = 0; kw < kfull; ++kw) {
+        const uint32_t inv = ~wrow[kw];
+        const int kb = kw << 5;
+#pragma unroll
+        for (int kk = 0; kk < 32; ++kk) {
+            const float w = pm1_from_inverted_bit(inv, kk);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) acc[i] = __builtin_fmaf(w, xr[i][kb + kk], acc[i]);
+        }
+    }
+    if (K & 31) {
+        const uint32_t inv = ~wrow[kfull];
+        const int kb = kfull << 5;
+        for (int kk = 0; kb + kk < K; ++kk) {
+            const float w = pm1_from_inverted_bit(inv, kk);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) acc[i] = __builtin_fmaf(w, xr[i][kb + kk], acc[i]);
+        }
+    }
+    int dummy[TM];
+    epilogue_lanes_n<TM, ACT>(acc, dummy, scale, bias, m0, M, n0, n, N, Y, yw32);
+}
+
+// dot[m][n] = K - 2 * sum_w popcount(x[m][w] XOR w[n][w]): v_xor_b32 with the frame word as SGPR
+// operand, then v_bcnt_u32_b32, whose second operand is the running count (the add is free).
+// VEC4: rows are 16-byte aligned and a multiple of 4 words long, so a lane fetches 4 words per load.
+template <int TM, int ACT, bool VEC4>
+__global__ __launch_bounds__(256) void binx_valu_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
+                                                        const float* __restrict__ scale, const float* __restrict__ bias,
+                                                        int M, int K, int N, int w32, void* __restrict__ Y, int yw32) {
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = lane_id();
+    const int n0 = ((int)blockIdx.y * 4 + wave) * kWave;
+    if (n0 >= N) return;
+    const int n = n0 + lane;
+    const int m0 = (int)blockIdx.x * TM;
+    const uint32_t* wrow = Wp + (size_t)(n < N ? n : N - 1) * w32;
+
+    const uint32_t* xr[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) xr[i] = Xp + (size_t)(m0 + i < M ? m0 + i : M - 1) * w32;
+
+    uint32_t cnt[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) cnt[i] = 0;
+
+    if constexpr (VEC4) {
+        for (int kw = 0; kw < w32; kw += 4) {
+            const uint4 b = *reinterpret_cast<const uint4*>(wrow + kw);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                cnt[i] += __builtin_popcount(b.x ^ xr[i][kw + 0]);
+                cnt[i] += __builtin_popcount(b.y ^ xr[i][kw + 1]);
+                cnt[i] += __builtin_popcount(b.z ^ xr[i][kw + 2]);
+                cnt[i] += __builtin_popcount(b.w ^ xr[i][kw + 3]);
+            }
+        }
+    } else {
+        for (int kw = 0; kw < w32; ++kw) {
+            const uint32_t b = wrow[kw];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) cnt[i] += __builtin_popcount(b ^ xr[i][kw]);
+        }
+    }
+
+    float v[TM];
+    int vi[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        vi[i] = K - 2 * (int)cnt[i];
+        v[i] = (float)vi[i];
+    }
+    epilogue_lanes_n<TM, ACT>(v, vi, scale, bias, m0, M, n0, n, N, Y, yw32);
+}
+
+}  // namespace bnn

@@ -1,0 +1,309 @@
+"""GPU parity: the HIP path behind the C ABI against the CPU oracle, element by element.
+
+Bars: bit-exact for packed bits and int32 products (also for the real-input layer, whose fp32 order
+of additions is fixed on both sides: ascending k, one accumulator); fp32 outputs within
+max|gpu - oracle| <= 1e-4 * max|oracle| ("layer output scale" = L-infinity norm of the oracle tensor).
+"""
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+@pytest.fixture(scope="module")
+def bnn():
+    import paper_1706_09453_amd as b
+    return b
+
+
+def _close(got: np.ndarray, want: np.ndarray, what=""):
+    scale = float(np.max(np.abs(want)))
+    err = float(np.max(np.abs(got.astype(np.float64) - want.astype(np.float64))))
+    assert np.isfinite(got).all(), what
+    assert err <= TOL * scale, f"{what}: max abs err {err:g} > {TOL:g} * {scale:g}"
+
+
+def _rand_layer(seed, M, K, N):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    W = rng.uniform(-1, 1, size=(N, K)).astype(np.float32)
+    scale = rng.uniform(0.3, 0.7, N).astype(np.float32)
+    scale[::7] *= -1.0                                   # negative scales reverse the threshold direction
+    bias = (rng.standard_normal(N) * 0.5).astype(np.float32)
+    return X, W, scale, bias
+
+
+# ----------------------------------------------------------------------------- pack
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("rows,K", [(1, 1), (3, 31), (5, 32), (7, 33), (4, 63), (4, 64), (9, 65), (64, 440),
+                                    (33, 2048), (2, 3307), (130, 1000)])
+def test_pack_activations_bit_exact(G, oracle, rows, K, wb):
+    rng = np.random.default_rng(rows * 1000 + K)
+    X = rng.standard_normal((rows, K)).astype(np.float32)
+    X.ravel()[:: 5] = 0.0
+    X.ravel()[1:: 11] = -0.0
+    if X.size > 8:
+        X.ravel()[3] = np.nan; X.ravel()[4] = np.inf; X.ravel()[5] = -np.inf
+        X.ravel()[6] = np.float32(1e-45); X.ravel()[7] = -np.float32(1e-45)
+    got = G.words_to_host(G.pack_activations(G.to_dev(X), wb), wb)
+    assert np.array_equal(got, oracle.pack_sign(X, wb))
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("N,K", [(1, 1), (5, 440), (64, 100), (512, 512), (1000, 513), (3400, 2048)])
+def test_pack_weights_bits_and_scale(G, oracle, N, K, wb):
+    W = workloads.uniform_pm1(3, 7000 + N, N * K).reshape(N, K)
+    Wp, sc = G.pack_weights(G.to_dev(W), wb)
+    assert np.array_equal(G.words_to_host(Wp, wb), oracle.pack_sign(W, wb))
+    # weights on the 2^-24 grid: every partial sum of |w| is exact in fp64, so the mean is order-independent
+    assert sc.cpu().numpy()[0] == oracle.mean_abs(W)
+    # arbitrary floats: equal up to the last fp32 bit
+    W2 = np.random.default_rng(N + K).standard_normal((N, K)).astype(np.float32)
+    _, sc2 = G.pack_weights(G.to_dev(W2), wb)
+    want = oracle.mean_abs(W2)
+    assert abs(float(sc2.cpu().numpy()[0]) - float(want)) <= float(np.spacing(want))
+
+
+# ----------------------------------------------------------------------------- binary x binary
+
+BIN_SHAPES = [(1, 1, 1), (3, 31, 5), (70, 33, 65), (16, 64, 64), (130, 440, 200), (257, 512, 129), (64, 1000, 1000),
+              (300, 2048, 512), (129, 1536, 3307), (65, 4096, 70), (128, 8192, 128)]
+
+
+def _bin_operands(oracle, seed, M, K, N, wb):
+    rng = np.random.default_rng(seed)
+    a = (rng.integers(0, 2, (M, K)) * 2 - 1).astype(np.float32)
+    b = (rng.integers(0, 2, (N, K)) * 2 - 1).astype(np.float32)
+    return oracle.pack_sign(a, wb), oracle.pack_sign(b, wb)
+
+
+@pytest.mark.parametrize("arm", ["valu", "mfma"])
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("M,K,N", BIN_SHAPES)
+def test_binx_raw_dot_bit_exact(G, bnn, oracle, M, K, N, wb, arm):
+    aw, bw = _bin_operands(oracle, M + K + N, M, K, N, wb)
+    armv = bnn.BNN_ARM_VALU_XOR if arm == "valu" else bnn.BNN_ARM_MFMA
+    got = G.layer_binx(G.to_dev(aw), G.to_dev(bw), None, None, K, N, bnn.BNN_ACT_RAW_I32, wb, armv).cpu().numpy()
+    want = oracle.dot_xor(aw, bw, K, wb)
+    if M * K * N <= 40_000_000:
+        assert np.array_equal(want, oracle.dot_pm1(oracle.unpack_pm1(aw, K, wb), oracle.unpack_pm1(bw, K, wb)))
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("arm", ["valu", "mfma"])
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax"])
+@pytest.mark.parametrize("M,K,N", [(3, 31, 5), (70, 33, 65), (130, 440, 200), (257, 512, 129), (200, 2048, 1000),
+                                   (96, 1024, 3307)])
+def test_binx_layer_acts(G, bnn, oracle, M, K, N, act, wb, arm):
+    aw, bw = _bin_operands(oracle, 5 * M + K + N, M, K, N, wb)
+    _, _, scale, bias = _rand_layer(M + N, 1, 1, N)
+    if act == "hardtanh":
+        scale = scale / np.float32(np.sqrt(K))            # keep a good share of outputs inside (-1, 1)
+    armv = bnn.BNN_ARM_VALU_XOR if arm == "valu" else bnn.BNN_ARM_MFMA
+    Y = G.layer_binx(G.to_dev(aw), G.to_dev(bw), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb, armv)
+    want = oracle.layer_binw_binx(aw, bw, K, scale, bias, act, wb, form="xor")
+    if act == "sign":
+        assert np.array_equal(G.words_to_host(Y, wb), want)
+    elif act == "logsoftmax":
+        _close(Y.cpu().numpy(), want, "logsoftmax")
+    else:
+        assert np.array_equal(Y.cpu().numpy(), want)       # one fma on an exact integer: identical bits
+        if act == "hardtanh":
+            inside = np.mean(np.abs(want) < 1.0)
+            assert 0.05 < inside < 0.999
+
+
+def test_binx_null_scale_bias(G, bnn, oracle):
+    M, K, N, wb = 40, 96, 70, 32
+    aw, bw = _bin_operands(oracle, 9, M, K, N, wb)
+    for arm in (bnn.BNN_ARM_VALU_XOR, bnn.BNN_ARM_MFMA):
+        Y = G.layer_binx(G.to_dev(aw), G.to_dev(bw), None, None, K, N, bnn.BNN_ACT_SIGN, wb, arm)
+        assert np.array_equal(G.words_to_host(Y, wb), oracle.layer_binw_binx(aw, bw, K, None, None, "sign", wb))
+
+
+# ----------------------------------------------------------------------------- real x binary
+
+@pytest.mark.parametrize("tm", [8, 16, 32])
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax"])
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (64, 440, 512), (130, 440, 200),
+                                   (37, 2048, 300), (50, 100, 3307)])
+def test_realx_layer(G, bnn, oracle, M, K, N, act, wb, tm):
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, tm)
+    try:
+        X, W, scale, bias = _rand_layer(M * 3 + K + N, M, K, N)
+        if act == "hardtanh":
+            scale = scale / np.float32(np.sqrt(K))
+        Wp = oracle.pack_sign(W, wb)
+        Y = G.layer_realx(G.to_dev(X), G.to_dev(Wp), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb)
+        want = oracle.layer_binw_realx(X, Wp, K, scale, bias, act, wb)
+        if act == "sign":
+            assert np.array_equal(G.words_to_host(Y, wb), want)
+        elif act == "logsoftmax":
+            _close(Y.cpu().numpy(), want, "logsoftmax")
+        else:
+            got = Y.cpu().numpy()
+            _close(got, want, act)
+            assert np.array_equal(got, want), "same order of fp32 additions on both sides: identical bits"
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, 16)
+
+
+def test_realx_against_fp64_shadow(G, bnn, oracle):
+    """The fp32 product also stays within the tolerance of the fp64 value of the same sum."""
+    M, K, N, wb = 64, 440, 256, 32
+    X, W, scale, bias = _rand_layer(77, M, K, N)
+    Wp = oracle.pack_sign(W, wb)
+    Y = G.layer_realx(G.to_dev(X), G.to_dev(Wp), G.to_dev(scale), G.to_dev(bias), K, N, bnn.BNN_ACT_LINEAR, wb)
+    _, acc64 = oracle.realx_acc(X, oracle.unpack_pm1(Wp, K, wb))
+    _close(Y.cpu().numpy(), oracle.affine_f64(acc64, scale, bias), "fp64 shadow")
+
+
+# ----------------------------------------------------------------------------- whole network
+
+def _net_parity(G, bnn, oracle, cfg, M, frames=None, form="xor", arm=None):
+    """GPU forward on M frames of cfg; oracle on `frames` (indices) or on all of them."""
+    Ws, bs = workloads.make_net_params(cfg)
+    X = workloads.make_frames(cfg, M)
+    model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
+    layers = oracle.make_layers(Ws, bs, cfg.hidden_act, cfg.word_bits)
+    for ly, sc in zip(layers, model.scales):
+        assert sc.cpu().numpy()[0] == ly.scale[0]
+    if arm is not None:
+        bnn.bnn_set_option(bnn.BNN_OPT_BINX_ARM, arm)
+    try:
+        got = model.forward(G.to_dev(X))
+        torch.cuda.synchronize()
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_BINX_ARM, bnn.BNN_ARM_MFMA)
+    idx = np.arange(M) if frames is None else np.asarray(frames)
+    want, keep = oracle.forward(layers, X[idx], form=form, keep=True)
+    got_h = got[torch.from_numpy(idx).to(G.DEV)].cpu().numpy()
+    _close(got_h, want, cfg.name)
+    assert np.array_equal(got_h.argmax(1), want.argmax(1)) or np.mean(got_h.argmax(1) == want.argmax(1)) > 0.999
+    assert np.allclose(np.exp(got_h.astype(np.float64)).sum(1), 1.0, atol=1e-4)
+    return model, layers, X, keep
+
+
+@pytest.mark.parametrize("arm", ["valu", "mfma"])
+def test_forward_config1_full(G, bnn, oracle, arm):
+    cfg = workloads.CONFIGS[1]
+    armv = bnn.BNN_ARM_VALU_XOR if arm == "valu" else bnn.BNN_ARM_MFMA
+    _net_parity(G, bnn, oracle, cfg, cfg.M, form="definition", arm=armv)
+
+
+def test_forward_config1_layer_by_layer_bits(G, bnn, oracle):
+    """Every hidden layer's packed output equals the oracle's, fed with the oracle's own previous bits."""
+    cfg = workloads.CONFIGS[1]
+    Ws, bs = workloads.make_net_params(cfg)
+    X = workloads.make_frames(cfg)
+    layers = oracle.make_layers(Ws, bs, "sign", 32)
+    _, keep = oracle.forward(layers, X, form="definition", keep=True)
+    h = G.to_dev(X)
+    for l, ly in enumerate(layers[:-1]):
+        args = (G.to_dev(ly.w_words), G.to_dev(ly.scale), G.to_dev(ly.bias), ly.K, ly.N, bnn.BNN_ACT_SIGN, 32)
+        Y = G.layer_realx(h, *args) if l == 0 else G.layer_binx(h, *args)
+        assert np.array_equal(G.words_to_host(Y, 32), keep[l]), f"layer {l + 1}"
+        h = Y
+
+
+@pytest.mark.parametrize("cfg_id,M", [(2, 96), (3, 300), (4, 200)])
+def test_forward_configs_reduced_batch_full_compare(G, bnn, oracle, cfg_id, M):
+    cfg = workloads.CONFIGS[cfg_id]
+    _net_parity(G, bnn, oracle, cfg, M)
+
+
+def test_forward_config3_full_batch_sampled_frames(G, bnn, oracle):
+    """Config 3 at its full size (M = 4096, the launch configuration the benchmark times)."""
+    cfg = workloads.CONFIGS[3]
+    rng = np.random.default_rng(0)
+    frames = np.unique(np.concatenate([np.arange(0, 16), np.arange(cfg.M - 16, cfg.M), rng.integers(0, cfg.M, 96)]))
+    model, layers, X, keep = _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
+    # and the hidden bits of the first binary layers, full batch, bit for bit (popcount form of the oracle)
+    Xd = G.to_dev(X)
+    ly = layers[0]
+    h1 = G.layer_realx(Xd, G.to_dev(ly.w_words), G.to_dev(ly.scale), G.to_dev(ly.bias), ly.K, ly.N, bnn.BNN_ACT_SIGN, 32)
+    want1 = oracle.layer_binw_realx(X, ly.w_words, ly.K, ly.scale, ly.bias, "sign", 32)
+    assert np.array_equal(G.words_to_host(h1, 32), want1)
+    ly = layers[1]
+    h2 = G.layer_binx(h1, G.to_dev(ly.w_words), G.to_dev(ly.scale), G.to_dev(ly.bias), ly.K, ly.N, bnn.BNN_ACT_SIGN, 32)
+    want2 = oracle.layer_binw_binx(want1, ly.w_words, ly.K, ly.scale, ly.bias, "sign", 32, form="xor")
+    assert np.array_equal(G.words_to_host(h2, 32), want2)
+
+
+def test_forward_config2_full_batch_sampled_frames(G, bnn, oracle):
+    cfg = workloads.CONFIGS[2]
+    frames = np.unique(np.concatenate([np.arange(0, 8), np.arange(cfg.M - 8, cfg.M),
+                                       np.random.default_rng(1).integers(0, cfg.M, 16)]))
+    _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
+
+
+def test_forward_config4_full_batch_sampled_frames(G, bnn, oracle):
+    cfg = workloads.CONFIGS[4]
+    frames = np.unique(np.concatenate([np.arange(0, 8), np.arange(cfg.M - 8, cfg.M),
+                                       np.random.default_rng(2).integers(0, cfg.M, 32)]))
+    _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
+
+
+# ----------------------------------------------------------------------------- isolated GEMM sweep (Config 5)
+
+@pytest.mark.parametrize("arm", ["valu", "mfma"])
+@pytest.mark.parametrize("shape", workloads.GEMM_SWEEP, ids=lambda s: f"M{s.M}_K{s.K}_N{s.N}")
+def test_gemm_sweep_int32(G, bnn, oracle, shape, arm):
+    M, K, N = shape.M, shape.K, shape.N
+    A = workloads.random_words(0, 500 + workloads.TENSOR_ABITS, M, K // 32)
+    B = workloads.random_words(0, 500 + workloads.TENSOR_BBITS, N, K // 32)
+    armv = bnn.BNN_ARM_VALU_XOR if arm == "valu" else bnn.BNN_ARM_MFMA
+    Y = G.layer_binx(G.to_dev(A), G.to_dev(B), None, None, K, N, bnn.BNN_ACT_RAW_I32, 32, armv)
+    torch.cuda.synchronize()
+    if M <= 4096:
+        rows = np.arange(M)
+    else:   # the oracle computes sampled rows one by one: first and last tiles plus random rows
+        rows = np.unique(np.concatenate([np.arange(0, 160), np.arange(M - 160, M),
+                                         np.random.default_rng(M + K + N).integers(0, M, 700)]))
+    got = Y[torch.from_numpy(rows).to(G.DEV)].cpu().numpy()
+    want = oracle.dot_xor(A[rows], B, K, 32)
+    assert np.array_equal(got, want)
+    # properties that hold at any size, on the whole output, evaluated on the GPU tensor
+    assert int(Y.abs().max()) <= K
+    assert int((Y & 1).max()) == (K & 1) and int((Y & 1).min()) == (K & 1)
+    del Y
+    torch.cuda.empty_cache()
+
+
+# ----------------------------------------------------------------------------- edges
+
+def test_zero_frames_is_a_noop(G, bnn):
+    assert bnn.bnn_layer_binw_binx(0, 0, 0, 0, 0, 64, 64, bnn.BNN_ACT_SIGN, 32, 0, G.stream()) == 0
+    assert bnn.bnn_layer_binw_realx(0, 0, 0, 0, 0, 64, 64, bnn.BNN_ACT_SIGN, 32, 0, G.stream()) == 0
+    assert bnn.bnn_pack_activations(0, 0, 64, 32, 0, G.stream()) == 0
+
+
+def test_forward_twice_same_result_and_other_stream(G, bnn, oracle):
+    cfg = workloads.CONFIGS[1]
+    Ws, bs = workloads.make_net_params(cfg)
+    X = G.to_dev(workloads.make_frames(cfg))
+    model = G.GpuModel(Ws, bs, "sign", 32)
+    a = model.forward(X).clone()
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        b = model.forward(X)
+    s.synchronize()
+    assert torch.equal(a, b)
