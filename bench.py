@@ -23,6 +23,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 # Published MI355X peaks used as roofline denominators.
 PEAK_MFMA_FP4_TFLOPS = 10100.0          # dense fp4/fp6 MFMA
+PEAK_MFMA_INT8_TOPS = 5000.0            # dense int8 MFMA
 PEAK_VALU_LANE_OPS = 256 * 4 * 16 * 2.4e9   # 256 CUs x 4 SIMD16 x 2.4 GHz = 39.3 T lane-ops/s
 PEAK_FP32_VALU_TFLOPS = 2 * PEAK_VALU_LANE_OPS / 1e12      # one v_fma_f32 per lane-op, unpacked: 78.6 TFLOP/s
 PEAK_XOR_POPC_TOPS = 2 * 32 * PEAK_VALU_LANE_OPS / 2 / 1e12  # xor + bcnt per 32 binary MACs: 1258 binary TOP/s
@@ -85,14 +86,22 @@ def main() -> int:
                for d in model.descs[:-1]]
     layer_us = []
     reps = max(20, min(args.steps, 200))
+    # layer 1 exactly as bnn_forward runs it: a one-layer network (real input -> Sign bits)
+    first = bnn.make_layer_array(model.descs[:1])
+    first_ws_bytes = bnn.bnn_forward_workspace_bytes(first, 1, M)
+    first_ws = torch.empty(max(first_ws_bytes, 256), dtype=torch.uint8, device=G.DEV)
     for l, d in enumerate(model.descs):
         src = X if l == 0 else ws_bits[l - 1]
         dst = out if l == model.n_layers - 1 else ws_bits[l]
         fn = bnn.bnn_layer_binw_binx if d["x_is_binary"] else bnn.bnn_layer_binw_realx
 
         def call():
-            fn(src.data_ptr(), d["Wp"], d["scale"], d["bias"], M, d["K"], d["N"], d["act"], d["word_bits"],
-               dst.data_ptr(), G.stream())
+            if l == 0:
+                bnn.bnn_forward(first, 1, src.data_ptr(), M, dst.data_ptr(), first_ws.data_ptr(), first_ws_bytes,
+                                G.stream())
+            else:
+                fn(src.data_ptr(), d["Wp"], d["scale"], d["bias"], M, d["K"], d["N"], d["act"], d["word_bits"],
+                   dst.data_ptr(), G.stream())
         for _ in range(3):
             call()
         torch.cuda.synchronize()
@@ -107,7 +116,7 @@ def main() -> int:
     # kernel groups: layer 1 (real input), hidden binary layers (one kernel, launched 5x per step), output layer
     hidden_us = layer_us[1:-1]
     groups = {
-        "realx_valu_kernel (layer 1, fp32 add/sub)": (layer_us[0], 1, 2.0 * M * cfg.dims[0] * cfg.dims[1]),
+        "realx layer 1 (quantize + int8 MFMA filter + exact resolution)": (layer_us[0], 1, 2.0 * M * cfg.dims[0] * cfg.dims[1]),
         "binx hidden kernel (2048x2048, sign+repack)": (sum(hidden_us), len(hidden_us),
                                                         2.0 * M * cfg.dims[1] * cfg.dims[2]),
         "binx output kernel + log-softmax": (layer_us[-1], 1, 2.0 * M * cfg.dims[-2] * cfg.dims[-1]),
@@ -117,7 +126,7 @@ def main() -> int:
     avg_us = tot_us / launches
     achieved_tflops = flops_per_launch / (avg_us * 1e-6) / 1e12
     if dominant.startswith("realx"):
-        bound, peak = "alu", PEAK_FP32_VALU_TFLOPS
+        bound, peak = "mfma", PEAK_MFMA_INT8_TOPS / 3.0   # three int8 digit products per fp32 multiply-add
     elif args.arm == "mfma":
         bound, peak = "mfma", PEAK_MFMA_FP4_TFLOPS
     else:

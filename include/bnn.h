@@ -70,7 +70,9 @@ typedef enum bnn_option {
     BNN_OPT_BINX_ARM = 1,      /* arm used for BNN_ARM_AUTO: BNN_ARM_VALU_XOR or BNN_ARM_MFMA                    */
     BNN_OPT_REALX_TM = 2,      /* frames per wavefront of the real-input kernel: 8, 16 or 32                    */
     BNN_OPT_BINX_VALU_TM = 3,  /* frames per wavefront of the XOR/popcount kernel: 8, 16 or 32                  */
-    BNN_OPT_MFMA_WM = 4        /* 16-row accumulator fragments per wavefront of the matrix-core kernel: 2 or 4  */
+    BNN_OPT_MFMA_WM = 4,       /* 16-row accumulator fragments per wavefront of the matrix-core kernel: 2 or 4  */
+    BNN_OPT_REALX_SIGN_MFMA = 5 /* bnn_forward, first layer real input -> Sign: 1 = matrix-core filter with exact
+                                   fix-up of uncertain outputs (default), 0 = vector-ALU kernel; same bits      */
 } bnn_option;
 
 /* One layer of a network for bnn_forward.  HOST struct; the three pointers are DEVICE pointers. */
@@ -140,8 +142,10 @@ int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, 
 
 /*
  * Bytes of scratch bnn_forward needs for M frames: two ping-pong buffers, each large enough for the
- * largest inter-layer activation (packed bits or fp32), each 256-byte aligned.  0 for a one-layer net
- * or on invalid arguments.  HOST helper; layers is a HOST array.
+ * largest inter-layer activation (packed bits or fp32), each 256-byte aligned, plus, when the first
+ * layer maps real input to Sign bits with K <= 1023, the scratch of its matrix-core path (three int8 digit
+ * planes of the frames, 64*ceil(K/64) bytes per frame each, and 16 bytes of bounds per frame).  0 on invalid
+ * arguments.  HOST helper; layers is a HOST array.
  */
 size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M);
 

@@ -9,6 +9,7 @@
 #include "../../include/bnn.h"
 #include "mfma_kernels.hpp"
 #include "pack_kernels.hpp"
+#include "realx_mfma_kernels.hpp"
 #include "softmax_kernels.hpp"
 #include "valu_kernels.hpp"
 
@@ -23,6 +24,7 @@ std::atomic<int> g_default_arm{BNN_ARM_MFMA};
 std::atomic<int> g_realx_tm{16};
 std::atomic<int> g_binx_valu_tm{16};
 std::atomic<int> g_mfma_wm{4};
+std::atomic<int> g_realx_sign_mfma{1};
 
 inline bool word_bits_ok(int wb) { return wb == 32 || wb == 64; }
 inline int64_t words_per_row(int64_t K, int wb) { return (K + wb - 1) / wb; }
@@ -186,6 +188,51 @@ int run_pack(const float* X, int64_t rows, int64_t K, int wb, void* out, hipStre
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Scratch of the matrix-core path of a real-input Sign layer (first layer of a binary-activation network):
+// three digit planes of the frames and 16 bytes of bounds per frame.
+struct RealxScratch {
+    size_t planes, meta, total;   // byte offsets from the start of the scratch, and its size
+    int kpad;
+};
+
+bool realx_sign_mfma_applies(const bnn_layer_desc& d) {
+    return !d.x_is_binary && d.act == BNN_ACT_SIGN && d.K <= kRealxMfmaMaxK;
+}
+
+RealxScratch realx_scratch_layout(int64_t M, int64_t K) {
+    RealxScratch s;
+    s.kpad = (int)((K + 63) / 64 * 64);
+    s.planes = 0;
+    s.meta = round_up(s.planes + (size_t)kDigits * M * s.kpad, 256);
+    s.total = round_up(s.meta + (size_t)M * sizeof(RowMeta), 256);
+    return s;
+}
+
+int run_realx_sign_mfma(const float* X, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K,
+                        int64_t N, int wb, void* Y, char* scratch, hipStream_t st) {
+    const RealxScratch L = realx_scratch_layout(M, K);
+    int8_t* planes = reinterpret_cast<int8_t*>(scratch + L.planes);
+    RowMeta* meta = reinterpret_cast<RowMeta*>(scratch + L.meta);
+    const int Mi = (int)M, Ki = (int)K, Ni = (int)N;
+    const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
+    quantize_rows_kernel<<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, L.kpad, planes, meta);
+    const size_t lds_main = realx_lds_bytes(L.kpad, w32);
+    // More than 64 KB of LDS per workgroup has to be requested explicitly (gfx950 has 160 KB per CU).
+    static std::atomic<size_t> lds_granted{48 * 1024};
+    if (lds_main > lds_granted.load()) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(realx_mfma_sign_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_main) != hipSuccess) {
+            (void)hipGetLastError();
+            return BNN_EDEVICE;
+        }
+        lds_granted.store(lds_main);
+    }
+    realx_mfma_sign_kernel<<<dim3((Mi + kRealxBM - 1) / kRealxBM, (Ni + kRealxBN - 1) / kRealxBN), dim3(256), lds_main, st>>>(
+        X, planes, meta, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki, L.kpad, Ni, w32,
+        static_cast<uint32_t*>(Y), yw32);
+    return launch_status();
+}
+
 int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
     if (!L || n_layers <= 0) return BNN_EINVAL;
     if (M < 0 || M > kMaxDim) return BNN_ESHAPE;
@@ -245,6 +292,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
             if (value != 2 && value != 4) return BNN_EINVAL;
             g_mfma_wm.store(value);
             return BNN_OK;
+        case BNN_OPT_REALX_SIGN_MFMA:
+            if (value != 0 && value != 1) return BNN_EINVAL;
+            g_realx_sign_mfma.store(value);
+            return BNN_OK;
         default: return BNN_EINVAL;
     }
 }
@@ -297,13 +348,15 @@ BNN_EXPORT int bnn_layer_binw_binx(const void* Xp, const void* Wp, const float* 
 }
 
 BNN_EXPORT size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M) {
-    if (check_chain(layers, n_layers, M) != BNN_OK || n_layers < 2) return 0;
+    if (check_chain(layers, n_layers, M) != BNN_OK) return 0;
     size_t biggest = 0;
     for (int l = 0; l + 1 < n_layers; ++l) {
         const size_t b = out_bytes(M, layers[l].N, layers[l].act, layers[l].word_bits);
         if (b > biggest) biggest = b;
     }
-    return 2 * round_up(biggest, 256);
+    size_t total = 2 * round_up(biggest, 256);
+    if (realx_sign_mfma_applies(layers[0])) total += realx_scratch_layout(M, layers[0].K).total;
+    return total;
 }
 
 BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
@@ -316,7 +369,14 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
     if (need && (!workspace || workspace_bytes < need)) return BNN_EWORKSPACE;
     if (need && !aligned(workspace, 256)) return BNN_EALIGN;
     // Check every layer's arguments before anything is enqueued.
-    char* buf[2] = {static_cast<char*>(workspace), static_cast<char*>(workspace) + need / 2};
+    size_t biggest = 0;
+    for (int l = 0; l + 1 < n_layers; ++l) {
+        const size_t b = out_bytes(M, layers[l].N, layers[l].act, layers[l].word_bits);
+        if (b > biggest) biggest = b;
+    }
+    const size_t half = round_up(biggest, 256);
+    char* buf[2] = {static_cast<char*>(workspace), static_cast<char*>(workspace) + half};
+    char* realx_scratch = static_cast<char*>(workspace) + 2 * half;
     for (int pass = 0; pass < 2; ++pass) {
         const void* in = X;
         for (int l = 0; l < n_layers; ++l) {
@@ -327,6 +387,9 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
             } else if (d.x_is_binary) {
                 rc = run_binx(in, d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o, BNN_ARM_AUTO,
                               static_cast<hipStream_t>(stream));
+            } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load()) {
+                rc = run_realx_sign_mfma(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
+                                         o, realx_scratch, static_cast<hipStream_t>(stream));
             } else {
                 rc = run_realx(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o,
                                static_cast<hipStream_t>(stream));

@@ -175,6 +175,80 @@ def test_realx_against_fp64_shadow(G, bnn, oracle):
     _close(Y.cpu().numpy(), oracle.affine_f64(acc64, scale, bias), "fp64 shadow")
 
 
+# ----------------------------------------------------------------------------- first layer on the matrix cores
+
+def _first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, use_mfma):
+    """Real input -> Sign bits through bnn_forward with a one-layer network (the path bnn_forward takes for layer 1)."""
+    keep = [G.to_dev(Wp), None if scale is None else G.to_dev(scale), None if bias is None else G.to_dev(bias)]
+    d = [dict(K=K, N=N, act=bnn.BNN_ACT_SIGN, word_bits=wb, x_is_binary=False, Wp=G.ptr(keep[0]),
+              scale=G.ptr(keep[1]), bias=G.ptr(keep[2]))]
+    arr = bnn.make_layer_array(d)
+    M = X.shape[0]
+    nbytes = bnn.bnn_forward_workspace_bytes(arr, 1, M)
+    ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=G.DEV)
+    out = G.word_tensor(M, N, wb)
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_SIGN_MFMA, 1 if use_mfma else 0)
+    try:
+        bnn.bnn_forward(arr, 1, G.ptr(G.to_dev(X)), M, G.ptr(out), G.ptr(ws), nbytes, G.stream())
+        torch.cuda.synchronize()
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_SIGN_MFMA, 1)
+    return G.words_to_host(out, wb)
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (64, 440, 512), (300, 440, 2048), (130, 64, 200),
+                                   (37, 1023, 300), (50, 100, 3307), (257, 129, 129)])
+def test_first_layer_mfma_filter_bit_exact(G, bnn, oracle, M, K, N, wb):
+    X, W, scale, bias = _rand_layer(M * 7 + K + N, M, K, N)
+    Wp = oracle.pack_sign(W, wb)
+    want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "sign", wb)
+    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, True), want)
+    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, False), want)
+
+
+def test_first_layer_mfma_filter_all_outputs_near_tie(G, bnn, oracle):
+    """Every pre-activation within rounding of 0: all outputs go through the exact fix-up (queue and its overflow)."""
+    M, K, N, wb = 300, 440, 200, 32
+    rng = np.random.default_rng(5)
+    x0 = rng.standard_normal((1, K)).astype(np.float32)
+    X = np.repeat(x0, M, axis=0)
+    X[1::2] *= np.float32(1.0 + 2.0 ** -20)                       # a second, slightly different frame
+    W = rng.uniform(-1, 1, (N, K)).astype(np.float32)
+    Wp = oracle.pack_sign(W, wb)
+    scale = np.full(N, 0.5, np.float32)
+    acc32, _ = oracle.realx_acc(x0, oracle.unpack_pm1(Wp, K, wb))
+    bias = (-0.5 * acc32[0]).astype(np.float32)                     # h^ = 0.5 * acc - 0.5 * acc(frame 0): ties and near-ties
+    bias[::3] = np.nextafter(bias[::3], np.float32(np.inf))
+    bias[1::3] = np.nextafter(bias[1::3], np.float32(-np.inf))
+    want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "sign", wb)
+    frac = np.unpackbits(want.view(np.uint8), bitorder="little").mean()
+    assert 0.05 < frac < 0.95
+    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, True), want)
+
+
+def test_first_layer_mfma_filter_special_rows(G, bnn, oracle):
+    M, K, N, wb = 70, 440, 130, 32
+    X, W, scale, bias = _rand_layer(123, M, K, N)
+    X[0] = 0.0
+    X[1] *= np.float32(1e-41)          # subnormal row
+    X[2] *= np.float32(1e-30)
+    X[3] *= np.float32(1e30)
+    X[4] *= np.float32(3e36)           # too large to quantise: goes to the exact path
+    X[5, 17] = np.inf
+    X[6, 100] = np.nan
+    X[7, 3] = -np.inf
+    X[8] = np.float32(1.0)
+    X[9, :] = 0.0; X[9, 5] = np.float32(1e-45)
+    X[10, ::2] *= np.float32(1e-20)    # wide dynamic range inside a row
+    scale[5] = 0.0
+    Wp = oracle.pack_sign(W, wb)
+    with np.errstate(all="ignore"):
+        want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "sign", wb)
+    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, True), want)
+    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, False), want)
+
+
 # ----------------------------------------------------------------------------- whole network
 
 def _net_parity(G, bnn, oracle, cfg, M, frames=None, form="xor", arm=None):
