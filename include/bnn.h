@@ -71,8 +71,13 @@ typedef enum bnn_option {
     BNN_OPT_REALX_TM = 2,      /* frames per wavefront of the real-input kernel: 8, 16 or 32                    */
     BNN_OPT_BINX_VALU_TM = 3,  /* frames per wavefront of the XOR/popcount kernel: 8, 16 or 32                  */
     BNN_OPT_MFMA_WM = 4,       /* 16-row accumulator fragments per wavefront of the matrix-core kernel: 2 or 4  */
-    BNN_OPT_REALX_SIGN_MFMA = 5 /* bnn_forward, first layer real input -> Sign: 1 = matrix-core filter with exact
-                                   fix-up of uncertain outputs (default), 0 = vector-ALU kernel; same bits      */
+    BNN_OPT_REALX_SIGN_MFMA = 5, /* bnn_forward, first layer real input -> Sign: 1 = matrix-core filter with exact
+                                   resolution of uncertain outputs (default), 0 = vector-ALU kernel; same bits  */
+    BNN_OPT_FUSED_LOGSOFTMAX = 6, /* binary-input LOGSOFTMAX layer on the matrix-core arm: 1 = product and
+                                   log-Softmax in one kernel (needs K % 256 == 0 and N <= 4096),
+                                   0 = product kernel followed by a row kernel (default: measured faster)        */
+    BNN_OPT_MFMA_SHAPE = 7       /* matrix-core arm: 16 = 16x16x128 MFMA (64 x 64 wave tiles), 32 = 32x32x64 MFMA
+                                   (128 x 64 wave tiles), 0 = by batch size (32 from 1024 frames; default)       */
 } bnn_option;
 
 /* One layer of a network for bnn_forward.  HOST struct; the three pointers are DEVICE pointers. */

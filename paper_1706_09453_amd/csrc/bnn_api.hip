@@ -7,6 +7,7 @@
 #include <cstring>
 
 #include "../../include/bnn.h"
+#include "mfma32_kernels.hpp"
 #include "mfma_kernels.hpp"
 #include "pack_kernels.hpp"
 #include "realx_mfma_kernels.hpp"
@@ -25,6 +26,8 @@ std::atomic<int> g_realx_tm{16};
 std::atomic<int> g_binx_valu_tm{16};
 std::atomic<int> g_mfma_wm{4};
 std::atomic<int> g_realx_sign_mfma{1};
+std::atomic<int> g_fused_softmax{0};
+std::atomic<int> g_mfma_shape{0};
 
 inline bool word_bits_ok(int wb) { return wb == 32 || wb == 64; }
 inline int64_t words_per_row(int64_t K, int wb) { return (K + wb - 1) / wb; }
@@ -82,7 +85,13 @@ void launch_realx_tm(const float* X, const uint32_t* Wp, const float* scale, con
 }
 
 void launch_log_softmax(float* Z, int M, int N, hipStream_t st) {
-    log_softmax_rows_kernel<<<dim3(M < 65536 ? M : 65536), dim3(256), 0, st>>>(Z, M, N);
+    const dim3 grid(M < 65536 ? M : 65536), block(256);
+    const bool al = aligned(Z, 16);
+    if (al && N <= 1024) log_softmax_rows_reg_kernel<4><<<grid, block, 0, st>>>(Z, M, N);
+    else if (al && N <= 2048) log_softmax_rows_reg_kernel<8><<<grid, block, 0, st>>>(Z, M, N);
+    else if (al && N <= 4096) log_softmax_rows_reg_kernel<16><<<grid, block, 0, st>>>(Z, M, N);
+    else if (al && N <= 8192) log_softmax_rows_reg_kernel<32><<<grid, block, 0, st>>>(Z, M, N);
+    else log_softmax_rows_kernel<<<grid, block, 0, st>>>(Z, M, N);
 }
 
 int run_realx(const float* X, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K, int64_t N,
@@ -140,6 +149,27 @@ void launch_binx_mfma_wm(const uint32_t* Xp, const uint32_t* Wp, const float* sc
     }
 }
 
+template <bool AL>
+void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
+                        int w32, int act, void* Y, int yw32, hipStream_t st) {
+    constexpr int WM = 4, WN = 2;
+    const dim3 grid((M + 64 * WM - 1) / (64 * WM), (N + 64 * WN - 1) / (64 * WN)), block(256);
+    switch (act) {
+        case BNN_ACT_RAW_I32:
+            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_SIGN:
+            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_HARDTANH:
+            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        default:
+            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+    }
+}
+
 int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K, int64_t N,
              int act, int wb, void* Y, int arm, hipStream_t st) {
     if (M == 0) return BNN_OK;
@@ -160,6 +190,27 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
             else if (tm == 32) launch_binx_valu_tm<32, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
             else launch_binx_valu_tm<16, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         }
+    } else if (act == BNN_ACT_LOGSOFTMAX && g_fused_softmax.load() && rows16 &&
+               ((K % 512 == 0 && N <= 16 * 8 * 16) || (K % 256 == 0 && N <= 16 * 8 * 32)) &&
+               (size_t)(M + 16) * w32 * 4 < 0x7fffffffu && (size_t)(N + 512) * w32 * 4 < 0x7fffffffu) {
+        // output layer: product, affine step and log-Softmax fused, one workgroup per 16 frames
+        const int nf = (int)((N + 127) / 128);
+        const dim3 grid((Mi + 15) / 16), block(512);
+        float* Yf = static_cast<float*>(Y);
+        const unsigned int ab = (unsigned int)((size_t)M * w32 * 4), bb = (unsigned int)((size_t)N * w32 * 4);
+        if (K % 512 == 0 && nf <= 8)
+            binx_mfma_logsoftmax_kernel<8, 4><<<grid, block, 0, st>>>(A, B, scale, bias, Mi, Ki, Ni, w32, Yf, ab, bb);
+        else if (K % 512 == 0 && nf <= 16)
+            binx_mfma_logsoftmax_kernel<16, 4><<<grid, block, 0, st>>>(A, B, scale, bias, Mi, Ki, Ni, w32, Yf, ab, bb);
+        else if (nf <= 28)
+            binx_mfma_logsoftmax_kernel<28, 2><<<grid, block, 0, st>>>(A, B, scale, bias, Mi, Ki, Ni, w32, Yf, ab, bb);
+        else
+            binx_mfma_logsoftmax_kernel<32, 2><<<grid, block, 0, st>>>(A, B, scale, bias, Mi, Ki, Ni, w32, Yf, ab, bb);
+        return launch_status();
+    } else if (g_mfma_shape.load() == 32 || (g_mfma_shape.load() == 0 && M >= 1024)) {
+        // large batch: 32x32x64 MFMA, 128 x 64 wave tiles
+        if (rows16 && (K % 512 == 0)) launch_binx_mfma32<true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        else launch_binx_mfma32<false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
     } else {
         const bool al = rows16 && (K % 512 == 0);
         const int wm = g_mfma_wm.load();
@@ -291,6 +342,14 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_MFMA_WM:
             if (value != 2 && value != 4) return BNN_EINVAL;
             g_mfma_wm.store(value);
+            return BNN_OK;
+        case BNN_OPT_MFMA_SHAPE:
+            if (value != 0 && value != 16 && value != 32) return BNN_EINVAL;
+            g_mfma_shape.store(value);
+            return BNN_OK;
+        case BNN_OPT_FUSED_LOGSOFTMAX:
+            if (value != 0 && value != 1) return BNN_EINVAL;
+            g_fused_softmax.store(value);
             return BNN_OK;
         case BNN_OPT_REALX_SIGN_MFMA:
             if (value != 0 && value != 1) return BNN_EINVAL;

@@ -1,0 +1,188 @@
+// Matrix-core arm of the binary x binary product (paper Sec. 2.3), large-batch version:
+// V_MFMA_F32_32X32X64_F8F6F4 with both operands in the 4-bit float format (+-1.0 exactly, see
+// mfma_kernels.hpp for the encoding and for why the result is the exact integer dot product).
+//
+// Why this shape: every operand word a lane holds (32 elements of one row) has to be expanded from bits to
+// nibbles by the vector ALU (7 instructions), and the SIMD issues either a VALU instruction or an MFMA per
+// 4 clocks.  What counts is therefore expansions per multiply-accumulate: a wave that owns a 128 x 64 tile of
+// [M][N] as 4 x 2 accumulator fragments of 32 x 32 expands 6 words for 8 MFMAs of 65536 MACs each, about
+// half the expansion work per MAC of the 16 x 16 x 128 kernel with 64 x 64 wave tiles.
+//
+// K advances in super-steps of 512 bits: lane (r = lane%32, g = lane/32) fetches 32 contiguous bytes (words
+// 8g..8g+7 of the super-step) of row r of every fragment in two 16-byte loads; word j feeds MFMA step j.
+// Inside a fragment the order of k is therefore permuted, identically for both operands.  The next
+// super-step is fetched while the current one is expanded and multiplied.
+// A workgroup is 2 x 2 waves: a (64 WM) x (64 WN) tile; at M = 4096, N = 2048 with WM = 4, WN = 2 that is
+// 256 workgroups, one wave per SIMD of the chip.
+#pragma once
+
+#include "mfma_kernels.hpp"
+
+namespace bnn {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+struct Raw8 {
+    uint4 lo, hi;   // words 0..3 and 4..7 of a lane's share of a super-step
+};
+
+// Fetch words [16*S + 8*g, +8) of a packed row.  ALIGNED: rows are 16-byte aligned and whole super-steps
+// long.  Otherwise each word is bounds-checked against the row length and reads as 0.
+template <bool ALIGNED>
+__device__ __forceinline__ Raw8 load_raw8(const uint32_t* __restrict__ row, int S, int g, int w32) {
+    const int base = S * 16 + g * 8;
+    Raw8 v;
+    if constexpr (ALIGNED) {
+        v.lo = *reinterpret_cast<const uint4*>(row + base);
+        v.hi = *reinterpret_cast<const uint4*>(row + base + 4);
+    } else {
+        v.lo.x = (base + 0 < w32) ? row[base + 0] : 0u;
+        v.lo.y = (base + 1 < w32) ? row[base + 1] : 0u;
+        v.lo.z = (base + 2 < w32) ? row[base + 2] : 0u;
+        v.lo.w = (base + 3 < w32) ? row[base + 3] : 0u;
+        v.hi.x = (base + 4 < w32) ? row[base + 4] : 0u;
+        v.hi.y = (base + 5 < w32) ? row[base + 5] : 0u;
+        v.hi.z = (base + 6 < w32) ? row[base + 6] : 0u;
+        v.hi.w = (base + 7 < w32) ? row[base + 7] : 0u;
+    }
+    return v;
+}
+
+// words[lane `lane`] = value (a wave-uniform value; `lane` must be a compile-time constant after unrolling).
+__device__ __forceinline__ void write_lane(int& words, uint32_t value, int lane) {
+    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(words) : "s"(value), "n"(lane));
+}
+
+__device__ __forceinline__ uint32_t word_of(const Raw8& v, int j) {
+    return j < 4 ? word_of(v.lo, j) : word_of(v.hi, j - 4);
+}
+
+// Grid: x = ceil(M / (64*WM)), y = ceil(N / (64*WN)); block = 256 threads.
+template <int WM, int WN, int ACT, bool ALIGNED>
+__global__ __launch_bounds__(256) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
+                                                          const float* __restrict__ scale, const float* __restrict__ bias,
+                                                          int M, int K, int N, int w32, void* __restrict__ Y, int yw32) {
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = lane_id();
+    const int r = lane & 31;   // row of the operand fragment / column of the accumulator fragment
+    const int g = lane >> 5;   // k-group of the operand fragment / row-group of the accumulator fragment
+    const int m_base = ((int)blockIdx.x * 2 + (wave >> 1)) * (WM * 32);
+    const int n_base = ((int)blockIdx.y * 2 + (wave & 1)) * (WN * 32);
+    if (m_base >= M || n_base >= N) return;   // wave-uniform
+
+    const uint32_t* arow[WM];
+    const uint32_t* brow[WN];
+#pragma unroll
+    for (int f = 0; f < WM; ++f) {
+        const int m = m_base + f * 32 + r;
+        arow[f] = Xp + (size_t)(m < M ? m : M - 1) * w32;
+    }
+#pragma unroll
+    for (int f = 0; f < WN; ++f) {
+        const int n = n_base + f * 32 + r;
+        brow[f] = Wp + (size_t)(n < N ? n : N - 1) * w32;
+    }
+
+    v16f acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const ExpandConsts ec = expand_consts();
+    const int nS = (K + 511) >> 9;
+    Raw8 araw[WM], braw[WN];
+#pragma unroll
+    for (int f = 0; f < WM; ++f) araw[f] = load_raw8<ALIGNED>(arow[f], 0, g, w32);
+#pragma unroll
+    for (int f = 0; f < WN; ++f) braw[f] = load_raw8<ALIGNED>(brow[f], 0, g, w32);
+
+    for (int S = 0; S < nS; ++S) {
+        Raw8 anext[WM], bnext[WN];
+        const int Sn = (S + 1 < nS) ? S + 1 : S;   // the last prefetch re-reads the last step (in bounds, unused)
+#pragma unroll
+        for (int f = 0; f < WM; ++f) anext[f] = load_raw8<ALIGNED>(arow[f], Sn, g, w32);
+#pragma unroll
+        for (int f = 0; f < WN; ++f) bnext[f] = load_raw8<ALIGNED>(brow[f], Sn, g, w32);
+
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            v8i bx[WN];
+#pragma unroll
+            for (int f = 0; f < WN; ++f) bx[f] = expand_pm1_fp4(word_of(braw[f], j), ec);
+#pragma unroll
+            for (int fm = 0; fm < WM; ++fm) {
+                const v8i ax = expand_pm1_fp4(word_of(araw[fm], j), ec);
+#pragma unroll
+                for (int fn = 0; fn < WN; ++fn)
+                    acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bx[fn], acc[fm][fn], 4, 4, 0, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int f = 0; f < WM; ++f) araw[f] = anext[f];
+#pragma unroll
+        for (int f = 0; f < WN; ++f) braw[f] = bnext[f];
+    }
+
+    // ---- epilogue.  Accumulator fragment (fm, fn), register v of lane (r, g) is
+    //      dot[m_base + 32 fm + 8 (v/4) + 4 g + v%4][n_base + 32 fn + r] + pad.
+    const float pad = (float)(nS * 512 - K);
+    if constexpr (ACT == ACT_SIGN) {
+        uint32_t* Yw = (uint32_t*)Y;
+#pragma unroll
+        for (int fn = 0; fn < WN; ++fn) {
+            const int n = n_base + fn * 32 + r;
+            const bool nvalid = n < N;
+            const float sc = (scale && nvalid) ? scale[n] : 1.0f;
+            const float bi = (bias && nvalid) ? bias[n] : 0.0f;
+            const int wcol = (n_base >> 5) + fn;
+#pragma unroll
+            for (int fm = 0; fm < WM; ++fm) {
+                // One ballot is two output words: lanes 0..31 are the 32 outputs of frame row 8(v/4)+v%4,
+                // lanes 32..63 the same outputs of the frame 4 rows below.  Word v is parked in lane v
+                // (and 32+v) of one register, so the whole fragment leaves with a single store.
+                int words = 0;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float h = affine(sc, acc[fm][fn][v] - pad, bi);
+                    const unsigned long long b = __ballot(nvalid && sign_bit(h));
+                    write_lane(words, (uint32_t)b, v);
+                    write_lane(words, (uint32_t)(b >> 32), 32 + v);
+                }
+                if (r < 16) {
+                    const int m = m_base + fm * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (m < M && wcol < yw32) Yw[(size_t)m * yw32 + wcol] = (uint32_t)words;
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int fn = 0; fn < WN; ++fn) {
+            const int n = n_base + fn * 32 + r;
+            const bool nvalid = n < N;
+            const float sc = (scale && nvalid) ? scale[n] : 1.0f;
+            const float bi = (bias && nvalid) ? bias[n] : 0.0f;
+#pragma unroll
+            for (int fm = 0; fm < WM; ++fm) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m_base + fm * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                    const float dot = acc[fm][fn][v] - pad;
+                    if (m < M && nvalid) {
+                        if constexpr (ACT == ACT_RAW_I32) {
+                            ((int*)Y)[(size_t)m * N + n] = (int)dot;
+                        } else {
+                            float h = affine(sc, dot, bi);
+                            if constexpr (ACT == ACT_HARDTANH) h = hardtanh(h);
+                            ((float*)Y)[(size_t)m * N + n] = h;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace bnn

@@ -42,4 +42,59 @@ __global__ __launch_bounds__(256) void log_softmax_rows_kernel(float* __restrict
     }
 }
 
+// The same with the whole row held in registers (N <= 256 * PER): one read and one write of the tensor.
+// Thread t owns elements 4 t .. 4 t + 3 of every 1024-element chunk (16-byte accesses when N % 4 == 0).
+template <int PER>
+__global__ __launch_bounds__(256) void log_softmax_rows_reg_kernel(float* __restrict__ Z, int M, int N) {
+    __shared__ float red[4];
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const bool vec = (N & 3) == 0;
+    for (int m = blockIdx.x; m < M; m += gridDim.x) {
+        float* z = Z + (size_t)m * N;
+        float v[PER];
+        const float neg_inf = -__builtin_inff();
+#pragma unroll
+        for (int c = 0; c < PER / 4; ++c) {
+            const int n = c * 1024 + 4 * (int)threadIdx.x;
+            if (vec && n + 3 < N) {
+                const float4 q = *reinterpret_cast<const float4*>(z + n);
+                v[4 * c] = q.x; v[4 * c + 1] = q.y; v[4 * c + 2] = q.z; v[4 * c + 3] = q.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[4 * c + i] = (n + i < N) ? z[n + i] : neg_inf;
+            }
+        }
+        float mx = neg_inf;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) mx = fmaxf(mx, v[i]);
+        mx = wave_max(mx);
+        if (lane == 0) red[wave] = mx;
+        __syncthreads();
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        __syncthreads();
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) s += __expf(v[i] - mx);
+        s = wave_sum(s);
+        if (lane == 0) red[wave] = s;
+        __syncthreads();
+        s = (red[0] + red[1]) + (red[2] + red[3]);
+        __syncthreads();
+        const float shift = mx + __logf(s);
+#pragma unroll
+        for (int c = 0; c < PER / 4; ++c) {
+            const int n = c * 1024 + 4 * (int)threadIdx.x;
+            if (vec && n + 3 < N) {
+                float4 q;
+                q.x = v[4 * c] - shift; q.y = v[4 * c + 1] - shift; q.z = v[4 * c + 2] - shift; q.w = v[4 * c + 3] - shift;
+                *reinterpret_cast<float4*>(z + n) = q;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (n + i < N) z[n + i] = v[4 * c + i] - shift;
+            }
+        }
+    }
+}
+
 }  // namespace bnn

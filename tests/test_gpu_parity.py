@@ -37,6 +37,26 @@ def _close(got: np.ndarray, want: np.ndarray, what=""):
     assert err <= TOL * scale, f"{what}: max abs err {err:g} > {TOL:g} * {scale:g}"
 
 
+ARMS = ["valu", "mfma16", "mfma32"]
+
+
+class _arm:
+    """Select the arithmetic arm (and the MFMA shape) of the binary product for the duration of a test."""
+
+    def __init__(self, bnn, name):
+        self.bnn, self.name = bnn, name
+
+    def __enter__(self):
+        b = self.bnn
+        if self.name != "valu":
+            b.bnn_set_option(b.BNN_OPT_MFMA_SHAPE, 16 if self.name == "mfma16" else 32)
+        return b.BNN_ARM_VALU_XOR if self.name == "valu" else b.BNN_ARM_MFMA
+
+    def __exit__(self, *exc):
+        self.bnn.bnn_set_option(self.bnn.BNN_OPT_MFMA_SHAPE, 0)
+        return False
+
+
 def _rand_layer(seed, M, K, N):
     rng = np.random.default_rng(seed)
     X = rng.standard_normal((M, K)).astype(np.float32)
@@ -92,20 +112,20 @@ def _bin_operands(oracle, seed, M, K, N, wb):
     return oracle.pack_sign(a, wb), oracle.pack_sign(b, wb)
 
 
-@pytest.mark.parametrize("arm", ["valu", "mfma"])
+@pytest.mark.parametrize("arm", ARMS)
 @pytest.mark.parametrize("wb", [32, 64])
 @pytest.mark.parametrize("M,K,N", BIN_SHAPES)
 def test_binx_raw_dot_bit_exact(G, bnn, oracle, M, K, N, wb, arm):
     aw, bw = _bin_operands(oracle, M + K + N, M, K, N, wb)
-    armv = bnn.BNN_ARM_VALU_XOR if arm == "valu" else bnn.BNN_ARM_MFMA
-    got = G.layer_binx(G.to_dev(aw), G.to_dev(bw), None, None, K, N, bnn.BNN_ACT_RAW_I32, wb, armv).cpu().numpy()
+    with _arm(bnn, arm) as armv:
+        got = G.layer_binx(G.to_dev(aw), G.to_dev(bw), None, None, K, N, bnn.BNN_ACT_RAW_I32, wb, armv).cpu().numpy()
     want = oracle.dot_xor(aw, bw, K, wb)
     if M * K * N <= 40_000_000:
         assert np.array_equal(want, oracle.dot_pm1(oracle.unpack_pm1(aw, K, wb), oracle.unpack_pm1(bw, K, wb)))
     assert np.array_equal(got, want)
 
 
-@pytest.mark.parametrize("arm", ["valu", "mfma"])
+@pytest.mark.parametrize("arm", ARMS)
 @pytest.mark.parametrize("wb", [32, 64])
 @pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax"])
 @pytest.mark.parametrize("M,K,N", [(3, 31, 5), (70, 33, 65), (130, 440, 200), (257, 512, 129), (200, 2048, 1000),
@@ -115,8 +135,8 @@ def test_binx_layer_acts(G, bnn, oracle, M, K, N, act, wb, arm):
     _, _, scale, bias = _rand_layer(M + N, 1, 1, N)
     if act == "hardtanh":
         scale = scale / np.float32(np.sqrt(K))            # keep a good share of outputs inside (-1, 1)
-    armv = bnn.BNN_ARM_VALU_XOR if arm == "valu" else bnn.BNN_ARM_MFMA
-    Y = G.layer_binx(G.to_dev(aw), G.to_dev(bw), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb, armv)
+    with _arm(bnn, arm) as armv:
+        Y = G.layer_binx(G.to_dev(aw), G.to_dev(bw), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb, armv)
     want = oracle.layer_binw_binx(aw, bw, K, scale, bias, act, wb, form="xor")
     if act == "sign":
         assert np.array_equal(G.words_to_host(Y, wb), want)
@@ -132,8 +152,9 @@ def test_binx_layer_acts(G, bnn, oracle, M, K, N, act, wb, arm):
 def test_binx_null_scale_bias(G, bnn, oracle):
     M, K, N, wb = 40, 96, 70, 32
     aw, bw = _bin_operands(oracle, 9, M, K, N, wb)
-    for arm in (bnn.BNN_ARM_VALU_XOR, bnn.BNN_ARM_MFMA):
-        Y = G.layer_binx(G.to_dev(aw), G.to_dev(bw), None, None, K, N, bnn.BNN_ACT_SIGN, wb, arm)
+    for arm in ARMS:
+        with _arm(bnn, arm) as armv:
+            Y = G.layer_binx(G.to_dev(aw), G.to_dev(bw), None, None, K, N, bnn.BNN_ACT_SIGN, wb, armv)
         assert np.array_equal(G.words_to_host(Y, wb), oracle.layer_binw_binx(aw, bw, K, None, None, "sign", wb))
 
 
@@ -275,11 +296,11 @@ def _net_parity(G, bnn, oracle, cfg, M, frames=None, form="xor", arm=None):
     return model, layers, X, keep
 
 
-@pytest.mark.parametrize("arm", ["valu", "mfma"])
+@pytest.mark.parametrize("arm", ARMS)
 def test_forward_config1_full(G, bnn, oracle, arm):
     cfg = workloads.CONFIGS[1]
-    armv = bnn.BNN_ARM_VALU_XOR if arm == "valu" else bnn.BNN_ARM_MFMA
-    _net_parity(G, bnn, oracle, cfg, cfg.M, form="definition", arm=armv)
+    with _arm(bnn, arm) as armv:
+        _net_parity(G, bnn, oracle, cfg, cfg.M, form="definition", arm=armv)
 
 
 def test_forward_config1_layer_by_layer_bits(G, bnn, oracle):
@@ -337,14 +358,14 @@ def test_forward_config4_full_batch_sampled_frames(G, bnn, oracle):
 
 # ----------------------------------------------------------------------------- isolated GEMM sweep (Config 5)
 
-@pytest.mark.parametrize("arm", ["valu", "mfma"])
+@pytest.mark.parametrize("arm", ARMS)
 @pytest.mark.parametrize("shape", workloads.GEMM_SWEEP, ids=lambda s: f"M{s.M}_K{s.K}_N{s.N}")
 def test_gemm_sweep_int32(G, bnn, oracle, shape, arm):
     M, K, N = shape.M, shape.K, shape.N
     A = workloads.random_words(0, 500 + workloads.TENSOR_ABITS, M, K // 32)
     B = workloads.random_words(0, 500 + workloads.TENSOR_BBITS, N, K // 32)
-    armv = bnn.BNN_ARM_VALU_XOR if arm == "valu" else bnn.BNN_ARM_MFMA
-    Y = G.layer_binx(G.to_dev(A), G.to_dev(B), None, None, K, N, bnn.BNN_ACT_RAW_I32, 32, armv)
+    with _arm(bnn, arm) as armv:
+        Y = G.layer_binx(G.to_dev(A), G.to_dev(B), None, None, K, N, bnn.BNN_ACT_RAW_I32, 32, armv)
     torch.cuda.synchronize()
     if M <= 4096:
         rows = np.arange(M)
