@@ -158,29 +158,61 @@ __global__ __launch_bounds__(256) void binx_mfma32_kernel(const uint32_t* __rest
             }
         }
     } else {
+        // 32-bit outputs: the accumulator layout gives a lane one column and 16 scattered rows, which would
+        // store 128-byte pieces.  Each wave turns 32 rows x (32 WN) columns at a time through its own slice
+        // of LDS so that 16 lanes write 256 contiguous bytes of a row (16 bytes per lane).
+        static_assert(WN == 2, "the transposing epilogue is written for 64-column wave tiles");
+        constexpr int LDW = 32 * WN + 4;                       // padded row length in words
+        __shared__ __attribute__((aligned(16))) uint32_t stage[4][32 * LDW];
+        uint32_t* st = stage[wave];
+        float sc[WN], bi[WN];
+        bool nvalid[WN];
 #pragma unroll
         for (int fn = 0; fn < WN; ++fn) {
             const int n = n_base + fn * 32 + r;
-            const bool nvalid = n < N;
-            const float sc = (scale && nvalid) ? scale[n] : 1.0f;
-            const float bi = (bias && nvalid) ? bias[n] : 0.0f;
+            nvalid[fn] = n < N;
+            sc[fn] = (scale && nvalid[fn]) ? scale[n] : 1.0f;
+            bi[fn] = (bias && nvalid[fn]) ? bias[n] : 0.0f;
+        }
+        const bool rows_vec = ((N & 3) == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
+        const int c4 = (lane & 15) * 4;                        // this lane's 4 columns of the 64
 #pragma unroll
-            for (int fm = 0; fm < WM; ++fm) {
+        for (int fm = 0; fm < WM; ++fm) {
+#pragma unroll
+            for (int fn = 0; fn < WN; ++fn)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int m = m_base + fm * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
                     const float dot = acc[fm][fn][v] - pad;
-                    if (m < M && nvalid) {
-                        if constexpr (ACT == ACT_RAW_I32) {
-                            ((int*)Y)[(size_t)m * N + n] = (int)dot;
-                        } else {
-                            float h = affine(sc, dot, bi);
-                            if constexpr (ACT == ACT_HARDTANH) h = hardtanh(h);
-                            ((float*)Y)[(size_t)m * N + n] = h;
-                        }
+                    uint32_t bits;
+                    if constexpr (ACT == ACT_RAW_I32) {
+                        bits = (uint32_t)(int)dot;
+                    } else {
+                        float h = affine(sc[fn], dot, bi[fn]);
+                        if constexpr (ACT == ACT_HARDTANH) h = hardtanh(h);
+                        bits = __float_as_uint(h);
+                    }
+                    st[(8 * (v >> 2) + 4 * g + (v & 3)) * LDW + fn * 32 + r] = bits;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // this wave's LDS writes are done before it reads them back
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int row = it * 4 + (lane >> 4);
+                const int m = m_base + fm * 32 + row;
+                const int n = n_base + c4;
+                const uint4 q = *reinterpret_cast<const uint4*>(st + row * LDW + c4);
+                if (m < M) {
+                    uint32_t* y = (uint32_t*)Y + (size_t)m * N + n;
+                    if (rows_vec && n + 3 < N) {
+                        *reinterpret_cast<uint4*>(y) = q;
+                    } else {
+                        if (n + 0 < N) y[0] = q.x;
+                        if (n + 1 < N) y[1] = q.y;
+                        if (n + 2 < N) y[2] = q.z;
+                        if (n + 3 < N) y[3] = q.w;
                     }
                 }
             }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // reads done before the next fragment row overwrites the slice
         }
     }
 }
