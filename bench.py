@@ -36,7 +36,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--arm", choices=["mfma", "valu"], default="mfma")
-    ap.add_argument("--cpu-sample-frames", type=int, default=1024)
+    ap.add_argument("--cpu-sample-frames", type=int, default=4096)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (frames are independent; a multi-GPU run would just split "

@@ -147,10 +147,8 @@ int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, 
 
 /*
  * Bytes of scratch bnn_forward needs for M frames: two ping-pong buffers, each large enough for the
- * largest inter-layer activation (packed bits or fp32), each 256-byte aligned, plus, when the first
- * layer maps real input to Sign bits with K <= 1023, the scratch of its matrix-core path (three int8 digit
- * planes of the frames, 64*ceil(K/64) bytes per frame each, and 16 bytes of bounds per frame).  0 on invalid
- * arguments.  HOST helper; layers is a HOST array.
+ * largest inter-layer activation (packed bits or fp32), each 256-byte aligned.  0 for a one-layer network
+ * and on invalid arguments.  HOST helper; layers is a HOST array.
  */
 size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M);
 

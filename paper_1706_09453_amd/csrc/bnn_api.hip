@@ -10,7 +10,7 @@
 #include "mfma32_kernels.hpp"
 #include "mfma_kernels.hpp"
 #include "pack_kernels.hpp"
-#include "realx_mfma_kernels.hpp"
+#include "realx_fused_kernel.hpp"
 #include "softmax_kernels.hpp"
 #include "valu_kernels.hpp"
 
@@ -239,48 +239,41 @@ int run_pack(const float* X, int64_t rows, int64_t K, int wb, void* out, hipStre
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Scratch of the matrix-core path of a real-input Sign layer (first layer of a binary-activation network):
-// three digit planes of the frames and 16 bytes of bounds per frame.
-struct RealxScratch {
-    size_t planes, meta, total;   // byte offsets from the start of the scratch, and its size
-    int kpad;
-};
-
+// The matrix-core path of a real-input Sign layer (first layer of a binary-activation network) applies when
+// K is small enough for its integer arithmetic; it needs no scratch in global memory.
 bool realx_sign_mfma_applies(const bnn_layer_desc& d) {
     return !d.x_is_binary && d.act == BNN_ACT_SIGN && d.K <= kRealxMfmaMaxK;
 }
 
-RealxScratch realx_scratch_layout(int64_t M, int64_t K) {
-    RealxScratch s;
-    s.kpad = (int)((K + 63) / 64 * 64);
-    s.planes = 0;
-    s.meta = round_up(s.planes + (size_t)kDigits * M * s.kpad, 256);
-    s.total = round_up(s.meta + (size_t)M * sizeof(RowMeta), 256);
-    return s;
-}
-
 int run_realx_sign_mfma(const float* X, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K,
-                        int64_t N, int wb, void* Y, char* scratch, hipStream_t st) {
-    const RealxScratch L = realx_scratch_layout(M, K);
-    int8_t* planes = reinterpret_cast<int8_t*>(scratch + L.planes);
-    RowMeta* meta = reinterpret_cast<RowMeta*>(scratch + L.meta);
+                        int64_t N, int wb, void* Y, hipStream_t st) {
     const int Mi = (int)M, Ki = (int)K, Ni = (int)N;
     const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
-    quantize_rows_kernel<<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, L.kpad, planes, meta);
-    const size_t lds_main = realx_lds_bytes(L.kpad, w32);
+    const int kpad = (Ki + 63) / 64 * 64;
+    int nb = realx_outputs_per_block(kpad, w32);
+    const int n_round = (Ni + kRealxChunk - 1) / kRealxChunk * kRealxChunk;
+    if (nb > n_round) nb = n_round;
+    const size_t lds = realx_dynamic_lds(Ki, kpad, w32, nb);
+    const dim3 grid((Mi + kRealxBM - 1) / kRealxBM, (Ni + nb - 1) / nb), block(kRealxThreads);
     // More than 64 KB of LDS per workgroup has to be requested explicitly (gfx950 has 160 KB per CU).
-    static std::atomic<size_t> lds_granted{48 * 1024};
-    if (lds_main > lds_granted.load()) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(realx_mfma_sign_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_main) != hipSuccess) {
+    static std::atomic<size_t> granted_vec{48 * 1024}, granted_scalar{48 * 1024};
+    const bool vec16 = aligned(Wp, 16) && (((size_t)nb * w32) % 4 == 0);   // every block's run of rows starts 16-byte aligned
+    std::atomic<size_t>& granted = vec16 ? granted_vec : granted_scalar;
+    if (lds > granted.load()) {
+        const void* fn = vec16 ? reinterpret_cast<const void*>(realx_sign_fused_kernel<true>)
+                               : reinterpret_cast<const void*>(realx_sign_fused_kernel<false>);
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
             (void)hipGetLastError();
             return BNN_EDEVICE;
         }
-        lds_granted.store(lds_main);
+        granted.store(lds);
     }
-    realx_mfma_sign_kernel<<<dim3((Mi + kRealxBM - 1) / kRealxBM, (Ni + kRealxBN - 1) / kRealxBN), dim3(256), lds_main, st>>>(
-        X, planes, meta, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki, L.kpad, Ni, w32,
-        static_cast<uint32_t*>(Y), yw32);
+    if (vec16)
+        realx_sign_fused_kernel<true><<<grid, block, lds, st>>>(X, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki, kpad,
+                                                               Ni, nb, w32, static_cast<uint32_t*>(Y), yw32);
+    else
+        realx_sign_fused_kernel<false><<<grid, block, lds, st>>>(X, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki, kpad,
+                                                                Ni, nb, w32, static_cast<uint32_t*>(Y), yw32);
     return launch_status();
 }
 
@@ -414,7 +407,6 @@ BNN_EXPORT size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int 
         if (b > biggest) biggest = b;
     }
     size_t total = 2 * round_up(biggest, 256);
-    if (realx_sign_mfma_applies(layers[0])) total += realx_scratch_layout(M, layers[0].K).total;
     return total;
 }
 
@@ -435,7 +427,6 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
     }
     const size_t half = round_up(biggest, 256);
     char* buf[2] = {static_cast<char*>(workspace), static_cast<char*>(workspace) + half};
-    char* realx_scratch = static_cast<char*>(workspace) + 2 * half;
     for (int pass = 0; pass < 2; ++pass) {
         const void* in = X;
         for (int l = 0; l < n_layers; ++l) {
@@ -448,7 +439,7 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
                               static_cast<hipStream_t>(stream));
             } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load()) {
                 rc = run_realx_sign_mfma(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
-                                         o, realx_scratch, static_cast<hipStream_t>(stream));
+                                         o, static_cast<hipStream_t>(stream));
             } else {
                 rc = run_realx(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o,
                                static_cast<hipStream_t>(stream));
