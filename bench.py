@@ -29,6 +29,40 @@ PEAK_FP32_VALU_TFLOPS = 2 * PEAK_VALU_LANE_OPS / 1e12      # one v_fma_f32 per l
 PEAK_XOR_POPC_TOPS = 2 * 32 * PEAK_VALU_LANE_OPS / 2 / 1e12  # xor + bcnt per 32 binary MACs: 1258 binary TOP/s
 
 
+def gemm_sweep(args, bnn, workloads, G, torch) -> int:
+    """Isolated binary x binary GEMM (Config 5): int32 = K - 2 popcount(XOR), one JSON line per shape and arm."""
+    for kv in args.opt:
+        key, val = kv.split("=")
+        bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
+    for shape in workloads.GEMM_SWEEP:
+        M, K, N = shape.M, shape.K, shape.N
+        A = G.to_dev(workloads.random_words(0, 500 + workloads.TENSOR_ABITS, M, K // 32))
+        B = G.to_dev(workloads.random_words(0, 500 + workloads.TENSOR_BBITS, N, K // 32))
+        Y = torch.empty((M, N), dtype=torch.int32, device=G.DEV)
+        for arm_name, arm in (("mfma", bnn.BNN_ARM_MFMA), ("valu", bnn.BNN_ARM_VALU_XOR)):
+            def call():
+                bnn.bnn_layer_binw_binx_arm(A.data_ptr(), B.data_ptr(), 0, 0, M, K, N, bnn.BNN_ACT_RAW_I32, 32,
+                                            Y.data_ptr(), arm, G.stream())
+            for _ in range(2):
+                call()
+            torch.cuda.synchronize()
+            reps = 10 if M * K * N < 1e12 else 3
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                call()
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / reps
+            out_gb = 4.0 * M * N / 1e9
+            print(json.dumps({"workload": f"C5 binary GEMM M={M} K={K} N={N} int32 out", "arm": arm_name,
+                              "us": round(us, 1), "binary_tops": round(2.0 * M * K * N / us / 1e6, 1),
+                              "output_GBps": round(out_gb / (us * 1e-6), 1)}))
+        del A, B, Y
+        torch.cuda.empty_cache()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -37,6 +71,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--arm", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
+    ap.add_argument("--gemm-sweep", action="store_true", help="time the isolated binary GEMM sweep (Config 5) instead")
+    ap.add_argument("--opt", action="append", default=[], help="kernel option as KEY=VALUE with KEY a BNN_OPT_* name, e.g. MFMA_LDS=0")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (frames are independent; a multi-GPU run would just split "
@@ -51,6 +87,8 @@ def main() -> int:
     import gpu_util as G
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.gemm_sweep:
+        return gemm_sweep(args, bnn, workloads, G, torch)
     cfg = workloads.CONFIGS[3]
     M = cfg.M
     Ws, bs = workloads.make_net_params(cfg)
@@ -60,6 +98,9 @@ def main() -> int:
     out = torch.empty((M, model.N_out), dtype=torch.float32, device=G.DEV)
     arm = bnn.BNN_ARM_MFMA if args.arm == "mfma" else bnn.BNN_ARM_VALU_XOR
     bnn.bnn_set_option(bnn.BNN_OPT_BINX_ARM, arm)
+    for kv in args.opt:
+        key, val = kv.split("=")
+        bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
 
     # ---- whole forward pass: W warm-up steps, then exactly K timed steps
     for _ in range(args.warmup):

@@ -76,8 +76,10 @@ typedef enum bnn_option {
     BNN_OPT_FUSED_LOGSOFTMAX = 6, /* binary-input LOGSOFTMAX layer on the matrix-core arm: 1 = product and
                                    log-Softmax in one kernel (needs K % 256 == 0 and N <= 4096),
                                    0 = product kernel followed by a row kernel (default: measured faster)        */
-    BNN_OPT_MFMA_SHAPE = 7       /* matrix-core arm: 16 = 16x16x128 MFMA (64 x 64 wave tiles), 32 = 32x32x64 MFMA
+    BNN_OPT_MFMA_SHAPE = 7,      /* matrix-core arm: 16 = 16x16x128 MFMA (64 x 64 wave tiles), 32 = 32x32x64 MFMA
                                    (128 x 64 wave tiles), 0 = by batch size (32 from 1024 frames; default)       */
+    BNN_OPT_MFMA32_WM = 8        /* 32-row accumulator fragments per wavefront of the 32x32x64 kernel: 2, 4, or 0 =
+                                   by grid size (default)                                                        */
 } bnn_option;
 
 /* One layer of a network for bnn_forward.  HOST struct; the three pointers are DEVICE pointers. */

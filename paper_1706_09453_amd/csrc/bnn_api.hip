@@ -28,6 +28,7 @@ std::atomic<int> g_mfma_wm{4};
 std::atomic<int> g_realx_sign_mfma{1};
 std::atomic<int> g_fused_softmax{0};
 std::atomic<int> g_mfma_shape{0};
+std::atomic<int> g_mfma32_wm{0};
 
 inline bool word_bits_ok(int wb) { return wb == 32 || wb == 64; }
 inline int64_t words_per_row(int64_t K, int wb) { return (K + wb - 1) / wb; }
@@ -149,10 +150,10 @@ void launch_binx_mfma_wm(const uint32_t* Xp, const uint32_t* Wp, const float* sc
     }
 }
 
-template <bool AL>
+template <int WM, bool AL>
 void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
                         int w32, int act, void* Y, int yw32, hipStream_t st) {
-    constexpr int WM = 4, WN = 2;
+    constexpr int WN = 2;
     const dim3 grid((M + 64 * WM - 1) / (64 * WM), (N + 64 * WN - 1) / (64 * WN)), block(256);
     switch (act) {
         case BNN_ACT_RAW_I32:
@@ -208,9 +209,19 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
             binx_mfma_logsoftmax_kernel<32, 2><<<grid, block, 0, st>>>(A, B, scale, bias, Mi, Ki, Ni, w32, Yf, ab, bb);
         return launch_status();
     } else if (g_mfma_shape.load() == 32 || (g_mfma_shape.load() == 0 && M >= 1024)) {
-        // large batch: 32x32x64 MFMA, 128 x 64 wave tiles
-        if (rows16 && (K % 512 == 0)) launch_binx_mfma32<true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
-        else launch_binx_mfma32<false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        // large batch: 32x32x64 MFMA, 128 x 64 (or 64 x 64) wave tiles
+        const bool al = rows16 && (K % 512 == 0);
+        // 128-row wave tiles expand fewer operand words per MAC; 64-row ones give twice the workgroups, which
+        // matters more while the 128-row grid cannot put two workgroups on every CU (measured on MI355X)
+        const int64_t blocks4 = ((M + 255) / 256) * ((N + 127) / 128);
+        const int wm32 = g_mfma32_wm.load();
+        if (wm32 == 2 || (wm32 == 0 && blocks4 < 400)) {
+            if (al) launch_binx_mfma32<2, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_mfma32<2, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        } else {
+            if (al) launch_binx_mfma32<4, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_mfma32<4, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        }
     } else {
         const bool al = rows16 && (K % 512 == 0);
         const int wm = g_mfma_wm.load();
@@ -339,6 +350,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_MFMA_SHAPE:
             if (value != 0 && value != 16 && value != 32) return BNN_EINVAL;
             g_mfma_shape.store(value);
+            return BNN_OK;
+        case BNN_OPT_MFMA32_WM:
+            if (value != 0 && value != 2 && value != 4) return BNN_EINVAL;
+            g_mfma32_wm.store(value);
             return BNN_OK;
         case BNN_OPT_FUSED_LOGSOFTMAX:
             if (value != 0 && value != 1) return BNN_EINVAL;

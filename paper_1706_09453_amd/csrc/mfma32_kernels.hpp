@@ -59,7 +59,7 @@ __device__ __forceinline__ uint32_t word_of(const Raw8& v, int j) {
 
 // Grid: x = ceil(M / (64*WM)), y = ceil(N / (64*WN)); block = 256 threads.
 template <int WM, int WN, int ACT, bool ALIGNED>
-__global__ __launch_bounds__(256) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
+__global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
                                                           const float* __restrict__ scale, const float* __restrict__ bias,
                                                           int M, int K, int N, int w32, void* __restrict__ Y, int yw32) {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -146,8 +146,8 @@ __global__ __launch_bounds__(256) void binx_mfma32_kernel(const uint32_t* __rest
                 int words = 0;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float h = affine(sc, acc[fm][fn][v] - pad, bi);
-                    const unsigned long long b = __ballot(nvalid && sign_bit(h));
+                    const float dot = ALIGNED ? acc[fm][fn][v] : acc[fm][fn][v] - pad;   // whole super-steps: no pad
+                    const unsigned long long b = __builtin_amdgcn_ballot_w64(nvalid && sign_bit(affine(sc, dot, bi)));
                     write_lane(words, (uint32_t)b, v);
                     write_lane(words, (uint32_t)(b >> 32), 32 + v);
                 }

@@ -37,7 +37,7 @@ def _close(got: np.ndarray, want: np.ndarray, what=""):
     assert err <= TOL * scale, f"{what}: max abs err {err:g} > {TOL:g} * {scale:g}"
 
 
-ARMS = ["valu", "mfma16", "mfma32"]
+ARMS = ["valu", "mfma16", "mfma32", "mfma32wm2"]
 
 
 class _arm:
@@ -50,10 +50,12 @@ class _arm:
         b = self.bnn
         if self.name != "valu":
             b.bnn_set_option(b.BNN_OPT_MFMA_SHAPE, 16 if self.name == "mfma16" else 32)
+            b.bnn_set_option(b.BNN_OPT_MFMA32_WM, 2 if self.name == "mfma32wm2" else 4)
         return b.BNN_ARM_VALU_XOR if self.name == "valu" else b.BNN_ARM_MFMA
 
     def __exit__(self, *exc):
         self.bnn.bnn_set_option(self.bnn.BNN_OPT_MFMA_SHAPE, 0)
+        self.bnn.bnn_set_option(self.bnn.BNN_OPT_MFMA32_WM, 0)
         return False
 
 
