@@ -156,6 +156,9 @@ void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* sca
     constexpr int WN = 2;
     const dim3 grid((M + 64 * WM - 1) / (64 * WM), (N + 64 * WN - 1) / (64 * WN)), block(256);
     switch (act) {
+        case ACT_DOT_I16:
+            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
         case BNN_ACT_RAW_I32:
             binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
@@ -211,6 +214,11 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
     } else if (g_mfma_shape.load() == 32 || (g_mfma_shape.load() == 0 && M >= 1024)) {
         // large batch: 32x32x64 MFMA, 128 x 64 (or 64 x 64) wave tiles
         const bool al = rows16 && (K % 512 == 0);
+        // Output layer: the product goes to memory as int16 (half the bytes of fp32 pre-activations), and the row
+        // kernel forms fma(scale, dot, bias) itself before the log-Softmax.
+        const bool i16 = act == BNN_ACT_LOGSOFTMAX && K < 32768 && N % 4 == 0 && N <= 8192 && aligned(Y, 16) &&
+                         (!scale || aligned(scale, 16)) && (!bias || aligned(bias, 16));
+        if (i16) act = ACT_DOT_I16;
         // 128-row wave tiles expand fewer operand words per MAC; 64-row ones give twice the workgroups, which
         // matters more while the 128-row grid cannot put two workgroups on every CU (measured on MI355X)
         const int64_t blocks4 = ((M + 255) / 256) * ((N + 127) / 128);
@@ -234,6 +242,14 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
         }
     }
     if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(static_cast<float*>(Y), Mi, Ni, st);
+    if (act == ACT_DOT_I16) {
+        const dim3 grid(Mi < 65536 ? Mi : 65536), block(256);
+        float* Z = static_cast<float*>(Y);
+        if (Ni <= 1024) log_softmax_rows_i16_kernel<4><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
+        else if (Ni <= 2048) log_softmax_rows_i16_kernel<8><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
+        else if (Ni <= 4096) log_softmax_rows_i16_kernel<16><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
+        else log_softmax_rows_i16_kernel<32><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
+    }
     return launch_status();
 }
 

@@ -11,6 +11,9 @@ constexpr int kWave = 64;
 
 // Activation selectors; numerically identical to bnn_act in include/bnn.h.
 enum : int { ACT_RAW_I32 = 0, ACT_LINEAR = 1, ACT_HARDTANH = 2, ACT_SIGN = 3, ACT_LOGSOFTMAX = 4 };
+// Kernel-internal: the integer product as int16 in the first 2 N bytes of each fp32 output row (|dot| <= K < 2^15);
+// the log-Softmax row kernel turns the row into fp32 log-posteriors in place.
+enum : int { ACT_DOT_I16 = 5 };
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 

@@ -182,9 +182,9 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
             for (int fn = 0; fn < WN; ++fn)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float dot = acc[fm][fn][v] - pad;
+                    const float dot = ALIGNED ? acc[fm][fn][v] : acc[fm][fn][v] - pad;
                     uint32_t bits;
-                    if constexpr (ACT == ACT_RAW_I32) {
+                    if constexpr (ACT == ACT_RAW_I32 || ACT == ACT_DOT_I16) {
                         bits = (uint32_t)(int)dot;
                     } else {
                         float h = affine(sc[fn], dot, bi[fn]);
@@ -201,14 +201,24 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
                 const int n = n_base + c4;
                 const uint4 q = *reinterpret_cast<const uint4*>(st + row * LDW + c4);
                 if (m < M) {
-                    uint32_t* y = (uint32_t*)Y + (size_t)m * N + n;
-                    if (rows_vec && n + 3 < N) {
-                        *reinterpret_cast<uint4*>(y) = q;
+                    if constexpr (ACT == ACT_DOT_I16) {
+                        // caller guarantees N % 4 == 0 and a 16-byte aligned Y: four int16 = one 8-byte store
+                        if (n < N) {
+                            uint2 h;
+                            h.x = (q.x & 0xFFFFu) | (q.y << 16);
+                            h.y = (q.z & 0xFFFFu) | (q.w << 16);
+                            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(Y) + (size_t)m * 2 * N + n) = h;
+                        }
                     } else {
-                        if (n + 0 < N) y[0] = q.x;
-                        if (n + 1 < N) y[1] = q.y;
-                        if (n + 2 < N) y[2] = q.z;
-                        if (n + 3 < N) y[3] = q.w;
+                        uint32_t* y = (uint32_t*)Y + (size_t)m * N + n;
+                        if (rows_vec && n + 3 < N) {
+                            *reinterpret_cast<uint4*>(y) = q;
+                        } else {
+                            if (n + 0 < N) y[0] = q.x;
+                            if (n + 1 < N) y[1] = q.y;
+                            if (n + 2 < N) y[2] = q.z;
+                            if (n + 3 < N) y[3] = q.w;
+                        }
                     }
                 }
             }
