@@ -71,6 +71,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--arm", choices=["mfma", "valu"], default="mfma")
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
+    ap.add_argument("--copy-calibration", action="store_true", help="run 10 plain 256 MiB device copies (counter calibration)")
     ap.add_argument("--gemm-sweep", action="store_true", help="time the isolated binary GEMM sweep (Config 5) instead")
     ap.add_argument("--opt", action="append", default=[], help="kernel option as KEY=VALUE with KEY a BNN_OPT_* name, e.g. MFMA_LDS=0")
     args = ap.parse_args()
@@ -89,6 +90,16 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.gemm_sweep:
         return gemm_sweep(args, bnn, workloads, G, torch)
+    if args.copy_calibration:
+        # A plain device-to-device copy of known size: the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by.
+        nbytes = 256 << 20
+        src = torch.empty(nbytes, dtype=torch.uint8, device=G.DEV).fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": nbytes, "copies": 10}))
+        return 0
     cfg = workloads.CONFIGS[3]
     M = cfg.M
     Ws, bs = workloads.make_net_params(cfg)
@@ -172,8 +183,15 @@ def main() -> int:
         bound, peak = "mfma", PEAK_MFMA_FP4_TFLOPS
     else:
         bound, peak = "alu", PEAK_XOR_POPC_TOPS
+    # HBM bytes per launch of each kernel group from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
+    # (profiles/forward_c3_hbm_traffic.txt); measured for this workload with the matrix-core arm only
+    measured_traffic = {"realx": (8.43 + 1.00) * 2 ** 20, "binx hidden": (5.24 + 1.00) * 2 ** 20,
+                        "binx output": (7.81 + 26.82 + 27.27 + 53.13) * 2 ** 20}
+    traffic = None
+    if args.arm == "mfma" and not args.opt:
+        traffic = next(int(v) for k, v in measured_traffic.items() if dominant.startswith(k))
     roofline = {"bound": bound, "achieved": round(achieved_tflops, 3), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved_tflops / peak, 4), "traffic": None, "kernel": dominant,
+                "frac": round(achieved_tflops / peak, 4), "traffic": traffic, "kernel": dominant,
                 "avg_launch_us": round(avg_us, 2), "launches_per_step": launches}
 
     bin_us = sum(layer_us[1:])
