@@ -150,26 +150,26 @@ void launch_binx_mfma_wm(const uint32_t* Xp, const uint32_t* Wp, const float* sc
     }
 }
 
-template <int WM, bool AL>
+template <int WM, bool AL, bool PP = false>
 void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
                         int w32, int act, void* Y, int yw32, hipStream_t st) {
     constexpr int WN = 2;
     const dim3 grid((M + 64 * WM - 1) / (64 * WM), (N + 64 * WN - 1) / (64 * WN)), block(256);
     switch (act) {
         case ACT_DOT_I16:
-            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         case BNN_ACT_RAW_I32:
-            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         case BNN_ACT_SIGN:
-            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         case BNN_ACT_HARDTANH:
-            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         default:
-            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
     }
 }
@@ -223,7 +223,10 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
         // matters more while the 128-row grid cannot put two workgroups on every CU (measured on MI355X)
         const int64_t blocks4 = ((M + 255) / 256) * ((N + 127) / 128);
         const int wm32 = g_mfma32_wm.load();
-        if (wm32 == 2 || (wm32 == 0 && blocks4 < 400)) {
+        if (al && K >= 4096 && wm32 != 2) {
+            // long K: operand fetch and products explicitly overlapped (two register sets)
+            launch_binx_mfma32<4, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        } else if (wm32 == 2 || (wm32 == 0 && blocks4 < 400)) {
             if (al) launch_binx_mfma32<2, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
             else launch_binx_mfma32<2, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         } else {
@@ -243,12 +246,14 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
     }
     if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(static_cast<float*>(Y), Mi, Ni, st);
     if (act == ACT_DOT_I16) {
-        const dim3 grid(Mi < 65536 ? Mi : 65536), block(256);
+        constexpr int ROWS = 1;   // two rows per workgroup (shared scale/bias loads) measured slower
+        const int nblk = (Mi + ROWS - 1) / ROWS;
+        const dim3 grid(nblk < 65536 ? nblk : 65536), block(256);
         float* Z = static_cast<float*>(Y);
-        if (Ni <= 1024) log_softmax_rows_i16_kernel<4><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
-        else if (Ni <= 2048) log_softmax_rows_i16_kernel<8><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
-        else if (Ni <= 4096) log_softmax_rows_i16_kernel<16><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
-        else log_softmax_rows_i16_kernel<32><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
+        if (Ni <= 1024) log_softmax_rows_i16_kernel<4, ROWS><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
+        else if (Ni <= 2048) log_softmax_rows_i16_kernel<8, ROWS><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
+        else if (Ni <= 4096) log_softmax_rows_i16_kernel<16, ROWS><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
+        else log_softmax_rows_i16_kernel<32, ROWS><<<grid, block, 0, st>>>(Z, scale, bias, Mi, Ni);
     }
     return launch_status();
 }

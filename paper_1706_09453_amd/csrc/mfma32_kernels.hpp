@@ -57,8 +57,12 @@ __device__ __forceinline__ uint32_t word_of(const Raw8& v, int j) {
     return j < 4 ? word_of(v.lo, j) : word_of(v.hi, j - 4);
 }
 
+// PINGPONG: two operand register sets used in turn with the issue order pinned by scheduling barriers (fetch the
+// next super-step | multiply the current one).  The rotating form (current = next) lets the compiler merge the
+// two sets, which serialises fetch and multiply: fine for short K where two resident workgroups per CU cover each
+// other's stalls, 15-20 % slower from K = 4096 on (measured).
 // Grid: x = ceil(M / (64*WM)), y = ceil(N / (64*WN)); block = 256 threads.
-template <int WM, int WN, int ACT, bool ALIGNED>
+template <int WM, int WN, int ACT, bool ALIGNED, bool PINGPONG = false>
 __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
                                                           const float* __restrict__ scale, const float* __restrict__ bias,
                                                           int M, int K, int N, int w32, void* __restrict__ Y, int yw32) {
@@ -93,37 +97,74 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
 
     const ExpandConsts ec = expand_consts();
     const int nS = (K + 511) >> 9;
-    Raw8 araw[WM], braw[WN];
+    if constexpr (PINGPONG) {
+        Raw8 a0[WM], b0[WN], a1[WM], b1[WN];
+        auto fetch = [&](Raw8 (&a)[WM], Raw8 (&b)[WN], int S) {
+            const int Sc = S < nS ? S : nS - 1;   // past the end: re-read the last super-step (in bounds, unused)
 #pragma unroll
-    for (int f = 0; f < WM; ++f) araw[f] = load_raw8<ALIGNED>(arow[f], 0, g, w32);
+            for (int f = 0; f < WM; ++f) a[f] = load_raw8<ALIGNED>(arow[f], Sc, g, w32);
 #pragma unroll
-    for (int f = 0; f < WN; ++f) braw[f] = load_raw8<ALIGNED>(brow[f], 0, g, w32);
-
-    for (int S = 0; S < nS; ++S) {
-        Raw8 anext[WM], bnext[WN];
-        const int Sn = (S + 1 < nS) ? S + 1 : S;   // the last prefetch re-reads the last step (in bounds, unused)
+            for (int f = 0; f < WN; ++f) b[f] = load_raw8<ALIGNED>(brow[f], Sc, g, w32);
+        };
+        auto multiply = [&](const Raw8 (&a)[WM], const Raw8 (&b)[WN]) {
 #pragma unroll
-        for (int f = 0; f < WM; ++f) anext[f] = load_raw8<ALIGNED>(arow[f], Sn, g, w32);
+            for (int j = 0; j < 8; ++j) {
+                v8i bx[WN];
 #pragma unroll
-        for (int f = 0; f < WN; ++f) bnext[f] = load_raw8<ALIGNED>(brow[f], Sn, g, w32);
-
+                for (int f = 0; f < WN; ++f) bx[f] = expand_pm1_fp4(word_of(b[f], j), ec);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            v8i bx[WN];
+                for (int fm = 0; fm < WM; ++fm) {
+                    const v8i ax = expand_pm1_fp4(word_of(a[fm], j), ec);
 #pragma unroll
-            for (int f = 0; f < WN; ++f) bx[f] = expand_pm1_fp4(word_of(braw[f], j), ec);
-#pragma unroll
-            for (int fm = 0; fm < WM; ++fm) {
-                const v8i ax = expand_pm1_fp4(word_of(araw[fm], j), ec);
-#pragma unroll
-                for (int fn = 0; fn < WN; ++fn)
-                    acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bx[fn], acc[fm][fn], 4, 4, 0, 0, 0, 0);
+                    for (int fn = 0; fn < WN; ++fn)
+                        acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bx[fn], acc[fm][fn], 4, 4, 0, 0, 0, 0);
+                }
             }
+        };
+        fetch(a0, b0, 0);
+        for (int S = 0; S < nS; S += 2) {
+            fetch(a1, b1, S + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(a0, b0, S + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            if (S + 1 < nS) multiply(a1, b1);   // wave-uniform
+            __builtin_amdgcn_sched_barrier(0);
         }
+    } else {
+        Raw8 araw[WM], braw[WN];
 #pragma unroll
-        for (int f = 0; f < WM; ++f) araw[f] = anext[f];
+        for (int f = 0; f < WM; ++f) araw[f] = load_raw8<ALIGNED>(arow[f], 0, g, w32);
 #pragma unroll
-        for (int f = 0; f < WN; ++f) braw[f] = bnext[f];
+        for (int f = 0; f < WN; ++f) braw[f] = load_raw8<ALIGNED>(brow[f], 0, g, w32);
+
+        for (int S = 0; S < nS; ++S) {
+            Raw8 anext[WM], bnext[WN];
+            const int Sn = (S + 1 < nS) ? S + 1 : S;   // the last prefetch re-reads the last step (in bounds, unused)
+#pragma unroll
+            for (int f = 0; f < WM; ++f) anext[f] = load_raw8<ALIGNED>(arow[f], Sn, g, w32);
+#pragma unroll
+            for (int f = 0; f < WN; ++f) bnext[f] = load_raw8<ALIGNED>(brow[f], Sn, g, w32);
+
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                v8i bx[WN];
+#pragma unroll
+                for (int f = 0; f < WN; ++f) bx[f] = expand_pm1_fp4(word_of(braw[f], j), ec);
+#pragma unroll
+                for (int fm = 0; fm < WM; ++fm) {
+                    const v8i ax = expand_pm1_fp4(word_of(araw[fm], j), ec);
+#pragma unroll
+                    for (int fn = 0; fn < WN; ++fn)
+                        acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bx[fn], acc[fm][fn], 4, 4, 0, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int f = 0; f < WM; ++f) araw[f] = anext[f];
+#pragma unroll
+            for (int f = 0; f < WN; ++f) braw[f] = bnext[f];
+        }
     }
 
     // ---- epilogue.  Accumulator fragment (fm, fn), register v of lane (r, g) is

@@ -100,56 +100,85 @@ __global__ __launch_bounds__(256) void log_softmax_rows_reg_kernel(float* __rest
 // Output layer, second half: the row starts with N int16 integer products (written by the product kernel);
 // z[n] = fma(scale[n], dot[n], bias[n]) is formed here, then log-Softmax, and the fp32 log-posteriors replace
 // the row.  Every thread holds its elements in registers across the barriers of the two reductions, so all
-// reads of the row are complete before the first write.  Needs N % 4 == 0, N <= 256 * PER, 16-byte aligned rows.
-template <int PER>
+// reads of a row are complete before its first write.  A workgroup takes ROWS consecutive frames at a time and
+// fetches its scale/bias values once for all of them.
+// Needs N % 4 == 0, N <= 256 * PER, 16-byte aligned rows.
+template <int PER, int ROWS>
 __global__ __launch_bounds__(256) void log_softmax_rows_i16_kernel(float* __restrict__ Z, const float* __restrict__ scale,
                                                                    const float* __restrict__ bias, int M, int N) {
-    __shared__ float red[4];
+    __shared__ float red[ROWS][4];
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const float neg_inf = -__builtin_inff();
-    for (int m = blockIdx.x; m < M; m += gridDim.x) {
-        float* z = Z + (size_t)m * N;
-        const uint16_t* d16 = reinterpret_cast<const uint16_t*>(z);
-        float v[PER];
+    float sc[PER], bi[PER];
 #pragma unroll
-        for (int c = 0; c < PER / 4; ++c) {
-            const int n = c * 1024 + 4 * (int)threadIdx.x;
-            if (n < N) {
-                const uint2 h = *reinterpret_cast<const uint2*>(d16 + n);
-                const float4 sc = scale ? *reinterpret_cast<const float4*>(scale + n) : make_float4(1.f, 1.f, 1.f, 1.f);
-                const float4 bi = bias ? *reinterpret_cast<const float4*>(bias + n) : make_float4(0.f, 0.f, 0.f, 0.f);
-                v[4 * c + 0] = affine(sc.x, (float)(int)(int16_t)(h.x & 0xFFFFu), bi.x);
-                v[4 * c + 1] = affine(sc.y, (float)(int)(int16_t)(h.x >> 16), bi.y);
-                v[4 * c + 2] = affine(sc.z, (float)(int)(int16_t)(h.y & 0xFFFFu), bi.z);
-                v[4 * c + 3] = affine(sc.w, (float)(int)(int16_t)(h.y >> 16), bi.w);
-            } else {
-                v[4 * c] = v[4 * c + 1] = v[4 * c + 2] = v[4 * c + 3] = neg_inf;
+    for (int c = 0; c < PER / 4; ++c) {
+        const int n = c * 1024 + 4 * (int)threadIdx.x;
+        float4 s4 = make_float4(1.f, 1.f, 1.f, 1.f), b4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (n < N) {
+            if (scale) s4 = *reinterpret_cast<const float4*>(scale + n);
+            if (bias) b4 = *reinterpret_cast<const float4*>(bias + n);
+        }
+        sc[4 * c] = s4.x; sc[4 * c + 1] = s4.y; sc[4 * c + 2] = s4.z; sc[4 * c + 3] = s4.w;
+        bi[4 * c] = b4.x; bi[4 * c + 1] = b4.y; bi[4 * c + 2] = b4.z; bi[4 * c + 3] = b4.w;
+    }
+    for (int m0 = blockIdx.x * ROWS; m0 < M; m0 += gridDim.x * ROWS) {
+        float v[ROWS][PER];
+#pragma unroll
+        for (int t = 0; t < ROWS; ++t) {
+            const int m = m0 + t < M ? m0 + t : M - 1;     // a row past the end repeats the last one and is not written
+            const uint16_t* d16 = reinterpret_cast<const uint16_t*>(Z + (size_t)m * N);
+#pragma unroll
+            for (int c = 0; c < PER / 4; ++c) {
+                const int n = c * 1024 + 4 * (int)threadIdx.x;
+                if (n < N) {
+                    const uint2 h = *reinterpret_cast<const uint2*>(d16 + n);
+                    v[t][4 * c + 0] = affine(sc[4 * c + 0], (float)(int)(int16_t)(h.x & 0xFFFFu), bi[4 * c + 0]);
+                    v[t][4 * c + 1] = affine(sc[4 * c + 1], (float)(int)(int16_t)(h.x >> 16), bi[4 * c + 1]);
+                    v[t][4 * c + 2] = affine(sc[4 * c + 2], (float)(int)(int16_t)(h.y & 0xFFFFu), bi[4 * c + 2]);
+                    v[t][4 * c + 3] = affine(sc[4 * c + 3], (float)(int)(int16_t)(h.y >> 16), bi[4 * c + 3]);
+                } else {
+                    v[t][4 * c] = v[t][4 * c + 1] = v[t][4 * c + 2] = v[t][4 * c + 3] = neg_inf;
+                }
             }
         }
-        float mx = neg_inf;
+        float mx[ROWS], s[ROWS];
 #pragma unroll
-        for (int i = 0; i < PER; ++i) mx = fmaxf(mx, v[i]);
-        mx = wave_max(mx);
-        if (lane == 0) red[wave] = mx;
-        __syncthreads();
-        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        __syncthreads();
-        float s = 0.0f;
+        for (int t = 0; t < ROWS; ++t) {
+            mx[t] = neg_inf;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) s += __expf(v[i] - mx);
-        s = wave_sum(s);
-        if (lane == 0) red[wave] = s;
+            for (int i = 0; i < PER; ++i) mx[t] = fmaxf(mx[t], v[t][i]);
+            mx[t] = wave_max(mx[t]);
+            if (lane == 0) red[t][wave] = mx[t];
+        }
         __syncthreads();
-        s = (red[0] + red[1]) + (red[2] + red[3]);
-        __syncthreads();
-        const float shift = mx + __logf(s);
 #pragma unroll
-        for (int c = 0; c < PER / 4; ++c) {
-            const int n = c * 1024 + 4 * (int)threadIdx.x;
-            if (n < N) {
-                float4 q;
-                q.x = v[4 * c] - shift; q.y = v[4 * c + 1] - shift; q.z = v[4 * c + 2] - shift; q.w = v[4 * c + 3] - shift;
-                *reinterpret_cast<float4*>(z + n) = q;
+        for (int t = 0; t < ROWS; ++t) mx[t] = fmaxf(fmaxf(red[t][0], red[t][1]), fmaxf(red[t][2], red[t][3]));
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < ROWS; ++t) {
+            s[t] = 0.0f;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) s[t] += __expf(v[t][i] - mx[t]);
+            s[t] = wave_sum(s[t]);
+            if (lane == 0) red[t][wave] = s[t];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < ROWS; ++t) s[t] = (red[t][0] + red[t][1]) + (red[t][2] + red[t][3]);
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < ROWS; ++t) {
+            if (m0 + t >= M) break;
+            float* z = Z + (size_t)(m0 + t) * N;
+            const float shift = mx[t] + __logf(s[t]);
+#pragma unroll
+            for (int c = 0; c < PER / 4; ++c) {
+                const int n = c * 1024 + 4 * (int)threadIdx.x;
+                if (n < N) {
+                    float4 q;
+                    q.x = v[t][4 * c] - shift; q.y = v[t][4 * c + 1] - shift; q.z = v[t][4 * c + 2] - shift; q.w = v[t][4 * c + 3] - shift;
+                    *reinterpret_cast<float4*>(z + n) = q;
+                }
             }
         }
     }

@@ -104,7 +104,7 @@ def test_pack_weights_bits_and_scale(G, oracle, N, K, wb):
 # ----------------------------------------------------------------------------- binary x binary
 
 BIN_SHAPES = [(1, 1, 1), (3, 31, 5), (70, 33, 65), (16, 64, 64), (130, 440, 200), (257, 512, 129), (64, 1000, 1000),
-              (300, 2048, 512), (129, 1536, 3307), (65, 4096, 70), (128, 8192, 128)]
+              (300, 2048, 512), (129, 1536, 3307), (65, 4096, 70), (128, 8192, 128), (70, 4608, 96)]
 
 
 def _bin_operands(oracle, seed, M, K, N, wb):
