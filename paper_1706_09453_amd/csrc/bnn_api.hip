@@ -282,14 +282,13 @@ int run_realx_sign_mfma(const float* X, const void* Wp, const float* scale, cons
     const int Mi = (int)M, Ki = (int)K, Ni = (int)N;
     const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
     const int kpad = (Ki + 63) / 64 * 64;
-    int nb = realx_outputs_per_block(kpad, w32);
-    const int n_round = (Ni + kRealxChunk - 1) / kRealxChunk * kRealxChunk;
-    if (nb > n_round) nb = n_round;
+    int nb = (Ni + kRealxChunk - 1) / kRealxChunk * kRealxChunk;
+    if (nb > kRealxMaxNB) nb = kRealxMaxNB;
     const size_t lds = realx_dynamic_lds(Ki, kpad, w32, nb);
     const dim3 grid((Mi + kRealxBM - 1) / kRealxBM, (Ni + nb - 1) / nb), block(kRealxThreads);
     // More than 64 KB of LDS per workgroup has to be requested explicitly (gfx950 has 160 KB per CU).
     static std::atomic<size_t> granted_vec{48 * 1024}, granted_scalar{48 * 1024};
-    const bool vec16 = aligned(Wp, 16) && (((size_t)nb * w32) % 4 == 0);   // every block's run of rows starts 16-byte aligned
+    const bool vec16 = aligned(Wp, 16);   // chunks start at multiples of 512 rows: 16-byte aligned whenever the matrix is
     std::atomic<size_t>& granted = vec16 ? granted_vec : granted_scalar;
     if (lds > granted.load()) {
         const void* fn = vec16 ? reinterpret_cast<const void*>(realx_sign_fused_kernel<true>)

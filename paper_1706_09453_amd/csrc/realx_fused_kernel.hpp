@@ -16,12 +16,13 @@
 //              bit, that bit is the bit of acc32.  Otherwise the output is "uncertain" (a few in 10^4 on N(0,1)
 //              inputs) and goes to a list in LDS; if the list is full the lane takes the fp32 sum itself.
 //   resolve    for every listed (m, n) one lane takes the fp32 sum in ascending k exactly as the vector-ALU
-//              kernel does, and sets the bit in the LDS copy of the output tile.
+//              kernel does (frame from LDS, weight words from memory), and sets the bit in the LDS copy of
+//              the output tile.
 //
-// One workgroup (8 waves) owns 16 frames and up to NB outputs.  It first brings ALL it will ever read from
-// global memory into LDS with every load in flight at once - its frames (quantised on the way in) and the NB
-// packed weight rows - so the product loop over the outputs, 512 at a time, runs out of LDS with no global
-// latency to hide; with M = 4096 that is 256 workgroups, one per CU.
+// One workgroup (8 waves) owns 16 frames and all N outputs (up to 8192).  The frames are read once, kept in LDS
+// in fp32 (for the resolution) and as three digit planes (for the products).  The weight rows stream through
+// two LDS stages, 512 rows at a time: while one chunk is multiplied, the next one is in flight in registers
+// (issue order pinned by scheduling barriers).  With M = 4096 that is 256 workgroups, one per CU.
 //
 // Operand order inside a 64-wide k step is permuted so that a lane expands its 16 weight bytes with shift+mask
 // only: byte i of dword c' of lane group g is bit (4 (g & 1) + c' + 8 i) of packed word 2*step + (g >> 1).
@@ -37,12 +38,12 @@ typedef int v4i32 __attribute__((ext_vector_type(4)));
 constexpr int kDigits = 3;
 constexpr int kDigitBits = 7;
 constexpr int kQuantBits = 20;         // |xq| <= 2^20
-constexpr int kRealxMfmaMaxK = 1023;   // 2 * K * 2^20 must stay below 2^31
+constexpr int kRealxMfmaMaxK = 512;    // LDS budget (frames in two forms + two weight stages); also 2 K 2^20 < 2^31
 constexpr int kRealxBM = 16;           // frames per workgroup
 constexpr int kRealxThreads = 512;     // 8 waves: two per SIMD, so one wave's latencies hide behind the other's work
 constexpr int kRealxChunk = 512;       // outputs multiplied at a time (8 waves x 64)
+constexpr int kRealxMaxNB = 8192;      // outputs per workgroup, at most
 constexpr int kRealxListCap = 512;     // uncertain outputs a workgroup can list (expected: about a dozen)
-constexpr int kRealxLdsBudget = 150 * 1024;
 
 struct RowMeta {
     int R;             // sum_k xq[k]
@@ -59,25 +60,19 @@ __device__ __forceinline__ int permuted_byte_of_k(int kk) {
     return 16 * g + 4 * cp + i;
 }
 
-__host__ __device__ constexpr int realx_plane_row(int kpad) { return kpad + 16; }   // bytes; +16 spreads the 16 rows over the banks
+// LDS layout (bytes from the start of the dynamic LDS): digit planes | fp32 frames | two weight stages | output tile
+__host__ __device__ constexpr int realx_plane_row(int kpad) { return kpad + 16; }   // +16 spreads the 16 rows over the banks
 __host__ __device__ constexpr int realx_wrow(int w32) { return w32 | 1; }           // words; odd for the same reason
-__host__ __device__ constexpr size_t realx_fixed_lds(int kpad) {
-    return (size_t)kDigits * kRealxBM * realx_plane_row(kpad);
+__host__ __device__ constexpr size_t realx_off_xs(int kpad) { return (size_t)kDigits * kRealxBM * realx_plane_row(kpad); }
+__host__ __device__ constexpr size_t realx_off_w(int K, int kpad) {
+    return realx_off_xs(kpad) + ((size_t)kRealxBM * (K + 1) * 4 + 15) / 16 * 16;
 }
-// Outputs a workgroup can own for a given K (multiple of 256, at most 2048).
-inline int realx_outputs_per_block(int kpad, int w32) {
-    const size_t per_output = (size_t)realx_wrow(w32) * 4 + (size_t)kRealxBM / 8;   // weight row + its share of the output tile
-    size_t nb = (kRealxLdsBudget - realx_fixed_lds(kpad)) / per_output;
-    nb = nb / kRealxChunk * kRealxChunk;
-    return (int)(nb > 2048 ? 2048 : nb);
+__host__ __device__ constexpr size_t realx_stage_bytes(int w32) { return (size_t)kRealxChunk * realx_wrow(w32) * 4; }
+__host__ __device__ constexpr size_t realx_off_tile(int K, int kpad, int w32) {
+    return realx_off_w(K, kpad) + 2 * realx_stage_bytes(w32);
 }
-// Bytes of the region that holds the weight rows during the products and the fp32 frames during the resolution.
-__host__ __device__ constexpr size_t realx_w_region(int K, int w32, int nb) {
-    const size_t wbytes = (size_t)nb * realx_wrow(w32) * 4, xbytes = (size_t)kRealxBM * (K + 1) * 4;
-    return ((wbytes > xbytes ? wbytes : xbytes) + 15) / 16 * 16;
-}
-inline size_t realx_dynamic_lds(int K, int kpad, int w32, int nb) {
-    return realx_fixed_lds(kpad) + realx_w_region(K, w32, nb) + (size_t)kRealxBM * (nb / 32) * 4;
+__host__ __device__ constexpr size_t realx_dynamic_lds(int K, int kpad, int w32, int nb) {
+    return realx_off_tile(K, kpad, w32) + (size_t)kRealxBM * (nb / 32) * 4;
 }
 
 // The fp32 sum in ascending k for one output, operands in global memory (used only when the list overflows).
@@ -91,7 +86,7 @@ __device__ __noinline__ float canonical_acc_global(const float* __restrict__ x, 
 }
 
 // Grid: x = ceil(M / 16), y = ceil(N / NB); block = 512 threads; dynamic LDS = realx_dynamic_lds(K, kpad, w32, NB).
-// VEC16: the weight rows of the workgroup start at a 16-byte boundary (wide copy into LDS).
+// NB is a multiple of 512.  VEC16: Wp is 16-byte aligned (16-byte loads of the weight chunks).
 template <bool VEC16>
 __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const float* __restrict__ X, const uint32_t* __restrict__ Wp,
                                                                const float* __restrict__ scale, const float* __restrict__ bias,
@@ -110,16 +105,57 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
     const int nb = min(NB, N - n_block);             // outputs of this workgroup
     const int plrow = realx_plane_row(kpad);
     const int ldw = realx_wrow(w32);
-    int8_t* planes = lds_raw;                                                        // [3][16][plrow]
-    uint32_t* wl = reinterpret_cast<uint32_t*>(lds_raw + realx_fixed_lds(kpad));     // [NB][ldw]
-    uint32_t* tile = reinterpret_cast<uint32_t*>(lds_raw + realx_fixed_lds(kpad) + realx_w_region(K, w32, NB));   // [16][NB / 32] packed outputs
+    const int xstride = K + 1;
+    int8_t* planes = lds_raw;                                                            // [3][16][plrow]
+    float* xs = reinterpret_cast<float*>(lds_raw + realx_off_xs(kpad));                  // [16][K + 1]
+    uint32_t* wst = reinterpret_cast<uint32_t*>(lds_raw + realx_off_w(K, kpad));          // [2][512][ldw]
+    uint32_t* tile = reinterpret_cast<uint32_t*>(lds_raw + realx_off_tile(K, kpad, w32)); // [16][NB / 32] packed outputs
+    const int stage_words = kRealxChunk * ldw;
     const int tw = NB >> 5;
     if (threadIdx.x == 0) list_count = 0u;
 
-    // ---- frames first (their latency hides behind the weight copy): wave w takes frames 2w and 2w+1,
-    //      lane l elements l, l + 64, ...; every load of both rows is issued before the first is used
-    constexpr int KPL = (kRealxMfmaMaxK + 63) / 64;   // elements per lane and row, at most
-    constexpr int FPW = kRealxBM / (kRealxThreads / kWave);   // frames per wave
+    // ---- a chunk of weight rows: 512 rows = one contiguous run of words; a thread carries up to WPT 16-byte pieces
+    constexpr int WPT = (kRealxChunk * ((kRealxMfmaMaxK + 31) / 32) / 4 + kRealxThreads - 1) / kRealxThreads;
+    uint4 wreg[WPT];
+    auto fetch_chunk = [&](int c0) {
+        const int rows = min(kRealxChunk, nb - c0);
+        const int total = rows * w32;                                     // words
+        const uint32_t* src = Wp + (size_t)(n_block + c0) * w32;
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) {
+            const int f = (int)threadIdx.x + i * kRealxThreads;
+            wreg[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (VEC16 && 4 * f + 3 < total) {
+                wreg[i] = reinterpret_cast<const uint4*>(src)[f];
+            } else {                                                       // tail piece or unaligned matrix
+                if (4 * f + 0 < total) wreg[i].x = src[4 * f + 0];
+                if (4 * f + 1 < total) wreg[i].y = src[4 * f + 1];
+                if (4 * f + 2 < total) wreg[i].z = src[4 * f + 2];
+                if (4 * f + 3 < total) wreg[i].w = src[4 * f + 3];
+            }
+        }
+    };
+    auto store_chunk = [&](int c0, uint32_t* stage) {
+        const int total = min(kRealxChunk, nb - c0) * w32;
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) {
+            const int f = (int)threadIdx.x + i * kRealxThreads;
+            if (4 * f < total) {
+                int row = (4 * f) / w32, col = 4 * f - row * w32;
+                const uint32_t w4[4] = {wreg[i].x, wreg[i].y, wreg[i].z, wreg[i].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (4 * f + j < total) stage[row * ldw + col] = w4[j];
+                    if (++col == w32) { col = 0; ++row; }
+                }
+            }
+        }
+    };
+
+    // ---- frames: wave w takes frames 2w and 2w+1, lane l elements l, l + 64, ...; every load of both rows and of
+    //      the first weight chunk is issued before the first value is used
+    constexpr int KPL = (kRealxMfmaMaxK + 63) / 64;            // elements per lane and row, at most
+    constexpr int FPW = kRealxBM / (kRealxThreads / kWave);     // frames per wave
     float xv[FPW][KPL];
 #pragma unroll
     for (int t = 0; t < FPW; ++t) {
@@ -131,54 +167,16 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
             xv[t][i] = (i * 64 < kpad && k < K) ? x[k] : 0.0f;   // first test is wave-uniform: unused slots cost nothing
         }
     }
-    // ---- weights: the block's rows are one contiguous run of nb * w32 words; 16 bytes per load, every load of
-    //      a thread issued before its first LDS write (VEC16: the run starts 16-byte aligned)
-    if (VEC16) {
-        const uint4* src = reinterpret_cast<const uint4*>(Wp + (size_t)n_block * w32);
-        const int total = nb * w32;                      // words
-        constexpr int PER = (2048 * 32 / 4 + kRealxThreads - 1) / kRealxThreads;   // 16-byte pieces per thread, at most
-        uint4 v[PER];
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int f = (int)threadIdx.x + i * kRealxThreads;
-            v[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (i * kRealxThreads * 4 < total) {              // uniform: unused slots cost nothing
-                if (4 * f + 3 < total) {
-                    v[i] = src[f];
-                } else if (4 * f < total) {                   // last, partial piece: never read past the matrix
-                    const uint32_t* p = reinterpret_cast<const uint32_t*>(src + f);
-                    v[i].x = p[0];
-                    if (4 * f + 1 < total) v[i].y = p[1];
-                    if (4 * f + 2 < total) v[i].z = p[2];
-                }
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int f = (int)threadIdx.x + i * kRealxThreads;
-            if (i * kRealxThreads * 4 < total && 4 * f < total) {   // first test is uniform: unused slots cost nothing
-                int row = (4 * f) / w32, col = 4 * f - row * w32;
-                const uint32_t w4[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (4 * f + j < total) wl[(size_t)row * ldw + col] = w4[j];
-                    if (++col == w32) { col = 0; ++row; }
-                }
-            }
-        }
-    } else {
-        for (int i = threadIdx.x; i < nb * w32; i += kRealxThreads) {
-            const int row = i / w32;
-            wl[(size_t)row * ldw + (i - row * w32)] = Wp[(size_t)n_block * w32 + i];
-        }
-    }
-    // ---- quantise the frames of this wave into the three digit planes
+    fetch_chunk(0);
 #pragma unroll
     for (int t = 0; t < FPW; ++t) {
         const int ml = wave * FPW + t;
         unsigned int mx = 0;   // largest |x| of the row as a bit pattern (NaN/Inf have the largest patterns)
 #pragma unroll
-        for (int i = 0; i < KPL; ++i) mx = max(mx, __float_as_uint(xv[t][i]) & 0x7fffffffu);
+        for (int i = 0; i < KPL; ++i) {
+            mx = max(mx, __float_as_uint(xv[t][i]) & 0x7fffffffu);
+            if (i * 64 < kpad && lane + 64 * i < K) xs[ml * xstride + lane + 64 * i] = xv[t][i];
+        }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) mx = max(mx, (unsigned int)__shfl_xor((int)mx, off, kWave));
         const int e = (int)(mx >> 23) - 127;                 // floor(log2 max|x|) for normal numbers
@@ -190,7 +188,6 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
 #pragma unroll
         for (int i = 0; i < KPL; ++i) {
             if (i * 64 < kpad) {   // wave-uniform
-                const int k = lane + 64 * i;
                 const int xq = flags ? 0 : (int)__builtin_rintf(xv[t][i] * qs);   // slots past K hold 0
                 R += xq;
                 A += xq < 0 ? -xq : xq;
@@ -218,9 +215,10 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
             meta[ml] = rm;
         }
     }
+    store_chunk(0, wst);
     __syncthreads();
 
-    // ---- products and decisions, 256 outputs at a time; this wave's 64 outputs are nw .. nw+63 of the block
+    // ---- products and decisions, 512 outputs at a time; this wave's 64 outputs are nw .. nw+63 of the block
     const int nsteps = kpad >> 6;
     const int sh = 4 * (g & 1);
     const int8_t* al = planes + (size_t)r * plrow + 16 * g;
@@ -228,139 +226,128 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
 #pragma unroll
     for (int q = 0; q < 4; ++q) rmeta[q] = meta[4 * g + q];
 
-    for (int c0 = 0; c0 < nb; c0 += kRealxChunk) {
+    for (int c0 = 0, ci = 0; c0 < nb; c0 += kRealxChunk, ++ci) {
+        const uint32_t* stage = wst + (ci & 1) * stage_words;
+        const bool more = c0 + kRealxChunk < nb;     // workgroup-uniform
+        if (more) fetch_chunk(c0 + kRealxChunk);
+        __builtin_amdgcn_sched_barrier(0);
         const int nw = c0 + wave * (WN * 16);
-        if (nw >= nb) continue;   // wave-uniform
-        float sc[WN], bi[WN];
-        bool nvalid[WN];
-#pragma unroll
-        for (int fn = 0; fn < WN; ++fn) {
-            const int nl = nw + fn * 16 + r;
-            nvalid[fn] = nl < nb;
-            sc[fn] = (scale && nvalid[fn]) ? scale[n_block + nl] : 1.0f;
-            bi[fn] = (bias && nvalid[fn]) ? bias[n_block + nl] : 0.0f;
-        }
-        v4i32 acc[kDigits][WN];
-#pragma unroll
-        for (int d = 0; d < kDigits; ++d)
-#pragma unroll
-            for (int j = 0; j < WN; ++j) acc[d][j] = v4i32{0, 0, 0, 0};
-
-        const uint32_t* bl = wl + (size_t)(nw + r) * ldw + (g >> 1);
-        for (int st = 0; st < nsteps; ++st) {
-            v4i32 bx[WN];
-#pragma unroll
-            for (int f = 0; f < WN; ++f) {
-                const int wi = 2 * st + (g >> 1);
-                // rows past the block's outputs hold stale LDS (never stored); words past the row read as 0 (pad)
-                const uint32_t w = (wi < w32) ? bl[(size_t)f * 16 * ldw + 2 * st] : 0u;
-                const uint32_t ws = w >> sh;
-                bx[f][0] = (int)(ws & 0x01010101u);
-                bx[f][1] = (int)((ws >> 1) & 0x01010101u);
-                bx[f][2] = (int)((ws >> 2) & 0x01010101u);
-                bx[f][3] = (int)((ws >> 3) & 0x01010101u);
-            }
-#pragma unroll
-            for (int d = 0; d < kDigits; ++d) {
-                const v4i32 ax = *reinterpret_cast<const v4i32*>(al + (size_t)d * kRealxBM * plrow + st * 64);
-#pragma unroll
-                for (int fn = 0; fn < WN; ++fn)
-                    acc[d][fn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ax, bx[fn], acc[d][fn], 0, 0, 0);
-            }
-        }
-
-        // accumulator register q of lane (r, g), fragment fn: frame 4g+q of the tile, output nw + 16 fn + r of the block
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int ml = 4 * g + q;
-            const int m = m_base + ml;
-            const bool mvalid = m < M;
-            const RowMeta rm = rmeta[q];
-            unsigned long long b[WN];
+        if (nw < nb) {   // wave-uniform
+            float sc[WN], bi[WN];
+            bool nvalid[WN];
 #pragma unroll
             for (int fn = 0; fn < WN; ++fn) {
-                const int P = acc[0][fn][q] + acc[1][fn][q] * (1 << kDigitBits) + acc[2][fn][q] * (1 << (2 * kDigitBits));
-                const float a = (float)(2 * P - rm.R) * rm.inv_scale;
-                const float Ew = rm.E + __builtin_fabsf(a) * 2.384185791015625e-07f;   // + 2^-22 |a| for the two roundings below
-                const bool lo = sign_bit(affine(sc[fn], a - Ew, bi[fn]));
-                const bool hi = sign_bit(affine(sc[fn], a + Ew, bi[fn]));
-                bool bit = lo;
-                if (mvalid && nvalid[fn] && (lo != hi || rm.flags)) {
-                    const int nl = nw + fn * 16 + r;
-                    const unsigned int slot = atomicAdd(&list_count, 1u);
-                    if (slot < (unsigned int)kRealxListCap) {
-                        list[slot] = ((unsigned int)ml << 16) | (unsigned int)nl;
-                        bit = false;                       // resolved below; set by an LDS atomic OR if it is 1
-                    } else {
-                        bit = sign_bit(affine(sc[fn], canonical_acc_global(X + (size_t)m * K, Wp + (size_t)(n_block + nl) * w32, K), bi[fn]));
-                    }
-                }
-                b[fn] = __ballot(nvalid[fn] && bit);
+                const int nl = nw + fn * 16 + r;
+                nvalid[fn] = nl < nb;
+                sc[fn] = (scale && nvalid[fn]) ? scale[n_block + nl] : 1.0f;
+                bi[fn] = (bias && nvalid[fn]) ? bias[n_block + nl] : 0.0f;
             }
-            if (lane < 4) {   // ballot bit 16 gg + rr: frame 4 gg + q, output 16 fn + rr; lane gg assembles frame 4 gg + q
-                const int shb = 16 * lane;
-                const uint32_t lo32 = (uint32_t)((b[0] >> shb) & 0xFFFFu) | ((uint32_t)((b[1] >> shb) & 0xFFFFu) << 16);
-                const uint32_t hi32 = (uint32_t)((b[2] >> shb) & 0xFFFFu) | ((uint32_t)((b[3] >> shb) & 0xFFFFu) << 16);
-                uint32_t* trow = tile + (size_t)(4 * lane + q) * tw + (nw >> 5);
-                trow[0] = lo32;
-                trow[1] = hi32;
+            v4i32 acc[kDigits][WN];
+#pragma unroll
+            for (int d = 0; d < kDigits; ++d)
+#pragma unroll
+                for (int j = 0; j < WN; ++j) acc[d][j] = v4i32{0, 0, 0, 0};
+
+            const uint32_t* bl = stage + (size_t)(wave * (WN * 16) + r) * ldw + (g >> 1);
+            for (int st = 0; st < nsteps; ++st) {
+                v4i32 bx[WN];
+#pragma unroll
+                for (int f = 0; f < WN; ++f) {
+                    const int wi = 2 * st + (g >> 1);
+                    // rows past the block's outputs hold stale LDS (never stored); words past the row read as 0 (pad)
+                    const uint32_t w = (wi < w32) ? bl[(size_t)f * 16 * ldw + 2 * st] : 0u;
+                    const uint32_t ws = w >> sh;
+                    bx[f][0] = (int)(ws & 0x01010101u);
+                    bx[f][1] = (int)((ws >> 1) & 0x01010101u);
+                    bx[f][2] = (int)((ws >> 2) & 0x01010101u);
+                    bx[f][3] = (int)((ws >> 3) & 0x01010101u);
+                }
+#pragma unroll
+                for (int d = 0; d < kDigits; ++d) {
+                    const v4i32 ax = *reinterpret_cast<const v4i32*>(al + (size_t)d * kRealxBM * plrow + st * 64);
+#pragma unroll
+                    for (int fn = 0; fn < WN; ++fn)
+                        acc[d][fn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ax, bx[fn], acc[d][fn], 0, 0, 0);
+                }
+            }
+
+            // accumulator register q of lane (r, g), fragment fn: frame 4g+q of the tile, output nw + 16 fn + r of the block
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ml = 4 * g + q;
+                const int m = m_base + ml;
+                const bool mvalid = m < M;
+                const RowMeta rm = rmeta[q];
+                unsigned long long b[WN];
+#pragma unroll
+                for (int fn = 0; fn < WN; ++fn) {
+                    const int P = acc[0][fn][q] + acc[1][fn][q] * (1 << kDigitBits) + acc[2][fn][q] * (1 << (2 * kDigitBits));
+                    const float a = (float)(2 * P - rm.R) * rm.inv_scale;
+                    const float Ew = rm.E + __builtin_fabsf(a) * 2.384185791015625e-07f;   // + 2^-22 |a| for the two roundings below
+                    const bool lo = sign_bit(affine(sc[fn], a - Ew, bi[fn]));
+                    const bool hi = sign_bit(affine(sc[fn], a + Ew, bi[fn]));
+                    bool bit = lo;
+                    if (mvalid && nvalid[fn] && (lo != hi || rm.flags)) {
+                        const int nl = nw + fn * 16 + r;
+                        const unsigned int slot = atomicAdd(&list_count, 1u);
+                        if (slot < (unsigned int)kRealxListCap) {
+                            list[slot] = ((unsigned int)ml << 16) | (unsigned int)nl;
+                            bit = false;                       // resolved below; set by an LDS atomic OR if it is 1
+                        } else {
+                            bit = sign_bit(affine(sc[fn], canonical_acc_global(X + (size_t)m * K, Wp + (size_t)(n_block + nl) * w32, K), bi[fn]));
+                        }
+                    }
+                    b[fn] = __builtin_amdgcn_ballot_w64(nvalid[fn] && bit);
+                }
+                if (lane < 4) {   // ballot bit 16 gg + rr: frame 4 gg + q, output 16 fn + rr; lane gg assembles frame 4 gg + q
+                    const int shb = 16 * lane;
+                    const uint32_t lo32 = (uint32_t)((b[0] >> shb) & 0xFFFFu) | ((uint32_t)((b[1] >> shb) & 0xFFFFu) << 16);
+                    const uint32_t hi32 = (uint32_t)((b[2] >> shb) & 0xFFFFu) | ((uint32_t)((b[3] >> shb) & 0xFFFFu) << 16);
+                    uint32_t* trow = tile + (size_t)(4 * lane + q) * tw + (nw >> 5);
+                    trow[0] = lo32;
+                    trow[1] = hi32;
+                }
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) store_chunk(c0 + kRealxChunk, wst + ((ci + 1) & 1) * stage_words);
+        __syncthreads();
+    }
+
+    // ---- resolve the listed outputs exactly: fp32 sum in ascending k, one lane per output; the frame comes from
+    //      LDS, the packed weight row (all its words fetched first: one memory latency) from global memory
+    const int count = (int)min(list_count, (unsigned int)kRealxListCap);
+    for (int i = threadIdx.x; i < count; i += kRealxThreads) {
+        const unsigned int e = list[i];
+        const int ml = (int)(e >> 16), nl = (int)(e & 0xFFFFu);
+        const int n = n_block + nl;
+        const uint32_t* wrow = Wp + (size_t)n * w32;
+        const float* xr = xs + ml * xstride;
+        constexpr int WMAX = (kRealxMfmaMaxK + 31) / 32;
+        uint32_t wq[WMAX];
+#pragma unroll
+        for (int kw = 0; kw < WMAX; ++kw) wq[kw] = (kw * 32 < K) ? wrow[kw] : 0u;
+        float acc = 0.0f;
+        const int kfull = K >> 5;
+#pragma unroll
+        for (int kw = 0; kw < WMAX; ++kw) {
+            if (kw >= kfull) break;
+            const uint32_t inv = ~wq[kw];
+            float xq[32];
+#pragma unroll
+            for (int kk = 0; kk < 32; ++kk) xq[kk] = xr[kw * 32 + kk];      // 32 independent LDS reads, then the chain
+#pragma unroll
+            for (int kk = 0; kk < 32; ++kk) acc = __builtin_fmaf(pm1_from_inverted_bit(inv, kk), xq[kk], acc);
+        }
+        if (K & 31) {
+            const uint32_t inv = ~wrow[kfull];
+            for (int kk = 0; kfull * 32 + kk < K; ++kk)
+                acc = __builtin_fmaf(pm1_from_inverted_bit(inv, kk), xr[kfull * 32 + kk], acc);
+        }
+        const float s1 = scale ? scale[n] : 1.0f, b1 = bias ? bias[n] : 0.0f;
+        if (sign_bit(affine(s1, acc, b1))) atomicOr(&tile[(size_t)ml * tw + (nl >> 5)], 1u << (nl & 31));
     }
     __syncthreads();
-
-    // ---- resolve the listed outputs exactly: fp32 sum in ascending k, one lane per output.  The products are
-    //      done, so the LDS of the weight rows now takes the 16 frames in fp32 (row stride K + 1 words keeps the
-    //      lanes on different banks); the few weight words an output needs come straight from global memory.
-    const int count = (int)min(list_count, (unsigned int)kRealxListCap);
-    if (count > 0) {   // workgroup-uniform
-        float* xs = reinterpret_cast<float*>(wl);
-        const int xstride = K + 1;
-        {   // 32 threads per frame, every load issued before the first LDS write
-            const int ml = (int)threadIdx.x >> 5, k0 = (int)threadIdx.x & 31;
-            const int m = m_base + ml;
-            const float* x = X + (size_t)(m < M ? m : M - 1) * K;
-            constexpr int PER = (kRealxMfmaMaxK + 31) / 32;
-            float v[PER];
-#pragma unroll
-            for (int i = 0; i < PER; ++i) v[i] = (i * 32 < K && k0 + 32 * i < K) ? x[k0 + 32 * i] : 0.0f;
-#pragma unroll
-            for (int i = 0; i < PER; ++i)
-                if (i * 32 < K && k0 + 32 * i < K) xs[ml * xstride + k0 + 32 * i] = v[i];
-        }
-        __syncthreads();
-        for (int i = threadIdx.x; i < count; i += kRealxThreads) {
-            const unsigned int e = list[i];
-            const int ml = (int)(e >> 16), nl = (int)(e & 0xFFFFu);
-            const int n = n_block + nl;
-            const uint32_t* wrow = Wp + (size_t)n * w32;
-            const float* xr = xs + ml * xstride;
-            constexpr int WMAX = (kRealxMfmaMaxK + 31) / 32;
-            uint32_t wreg[WMAX];                              // all words of the row first: one memory latency, not w32
-#pragma unroll
-            for (int kw = 0; kw < WMAX; ++kw) wreg[kw] = (kw * 32 < K) ? wrow[kw] : 0u;
-            float acc = 0.0f;
-            const int kfull = K >> 5;
-#pragma unroll
-            for (int kw = 0; kw < WMAX; ++kw) {
-                if (kw >= kfull) break;
-                const uint32_t inv = ~wreg[kw];
-                float xv[32];
-#pragma unroll
-                for (int kk = 0; kk < 32; ++kk) xv[kk] = xr[kw * 32 + kk];      // 32 independent LDS reads, then the chain
-#pragma unroll
-                for (int kk = 0; kk < 32; ++kk) acc = __builtin_fmaf(pm1_from_inverted_bit(inv, kk), xv[kk], acc);
-            }
-            if (K & 31) {
-                const uint32_t inv = ~wrow[kfull];
-                for (int kk = 0; kfull * 32 + kk < K; ++kk)
-                    acc = __builtin_fmaf(pm1_from_inverted_bit(inv, kk), xr[kfull * 32 + kk], acc);
-            }
-            const float s1 = scale ? scale[n] : 1.0f, b1 = bias ? bias[n] : 0.0f;
-            if (sign_bit(affine(s1, acc, b1))) atomicOr(&tile[(size_t)ml * tw + (nl >> 5)], 1u << (nl & 31));
-        }
-        __syncthreads();
-    }
 
     // ---- write the tile: each frame's words are contiguous in memory
     const int words_here = min(tw, yw32 - (n_block >> 5));           // words of this block that exist in a row of Y
