@@ -78,8 +78,12 @@ typedef enum bnn_option {
                                    0 = product kernel followed by a row kernel (default: measured faster)        */
     BNN_OPT_MFMA_SHAPE = 7,      /* matrix-core arm: 16 = 16x16x128 MFMA (64 x 64 wave tiles), 32 = 32x32x64 MFMA
                                    (128 x 64 wave tiles), 0 = by batch size (32 from 1024 frames; default)       */
-    BNN_OPT_MFMA32_WM = 8        /* 32-row accumulator fragments per wavefront of the 32x32x64 kernel: 2, 4, or 0 =
+    BNN_OPT_MFMA32_WM = 8,       /* 32-row accumulator fragments per wavefront of the 32x32x64 kernel: 2, 4, or 0 =
                                    by grid size (default)                                                        */
+    BNN_OPT_MFMA32_PIPELINE = 9  /* operand fetch of the 32x32x64 kernel on 16-byte aligned rows with K % 512 == 0:
+                                   0 or 1 = two register sets, the fetch of the next piece of K pinned ahead of
+                                   the products of the current one (default), 2 = one set, order left to the
+                                   compiler (kept for comparison)                                                */
 } bnn_option;
 
 /* One layer of a network for bnn_forward.  HOST struct; the three pointers are DEVICE pointers. */

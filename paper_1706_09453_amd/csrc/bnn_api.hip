@@ -29,6 +29,7 @@ std::atomic<int> g_realx_sign_mfma{1};
 std::atomic<int> g_fused_softmax{0};
 std::atomic<int> g_mfma_shape{0};
 std::atomic<int> g_mfma32_wm{0};
+std::atomic<int> g_mfma32_pipeline{0};
 
 inline bool word_bits_ok(int wb) { return wb == 32 || wb == 64; }
 inline int64_t words_per_row(int64_t K, int wb) { return (K + wb - 1) / wb; }
@@ -220,18 +221,21 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
                          (!scale || aligned(scale, 16)) && (!bias || aligned(bias, 16));
         if (i16) act = ACT_DOT_I16;
         // 128-row wave tiles expand fewer operand words per MAC; 64-row ones give twice the workgroups, which
-        // matters more while the 128-row grid cannot put two workgroups on every CU (measured on MI355X)
+        // matters more while the 128-row grid leaves CUs without a workgroup (measured on MI355X: 64-row tiles win
+        // up to 2048 frames x 2048 outputs, 128-row tiles from 4096 x 2048 on)
         const int64_t blocks4 = ((M + 255) / 256) * ((N + 127) / 128);
         const int wm32 = g_mfma32_wm.load();
-        if (al && K >= 4096 && wm32 != 2) {
-            // long K: operand fetch and products explicitly overlapped (two register sets)
-            launch_binx_mfma32<4, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
-        } else if (wm32 == 2 || (wm32 == 0 && blocks4 < 400)) {
-            if (al) launch_binx_mfma32<2, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
-            else launch_binx_mfma32<2, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        const bool wm2 = wm32 == 2 || (wm32 == 0 && blocks4 < 200);
+        const bool pinned = g_mfma32_pipeline.load() != 2;   // fetch pinned ahead of the products: faster on every shape measured
+        if (!al) {
+            // ragged rows: bounds-checked word loads, 64-row wave tiles only
+            launch_binx_mfma32<2, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        } else if (wm2) {
+            if (pinned) launch_binx_mfma32<2, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_mfma32<2, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         } else {
-            if (al) launch_binx_mfma32<4, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
-            else launch_binx_mfma32<4, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            if (pinned) launch_binx_mfma32<4, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_mfma32<4, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         }
     } else {
         const bool al = rows16 && (K % 512 == 0);
@@ -374,6 +378,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_MFMA32_WM:
             if (value != 0 && value != 2 && value != 4) return BNN_EINVAL;
             g_mfma32_wm.store(value);
+            return BNN_OK;
+        case BNN_OPT_MFMA32_PIPELINE:
+            if (value < 0 || value > 2) return BNN_EINVAL;
+            g_mfma32_pipeline.store(value);
             return BNN_OK;
         case BNN_OPT_FUSED_LOGSOFTMAX:
             if (value != 0 && value != 1) return BNN_EINVAL;

@@ -48,9 +48,23 @@ __device__ __forceinline__ Raw8 load_raw8(const uint32_t* __restrict__ row, int 
     return v;
 }
 
-// words[lane `lane`] = value (a wave-uniform value; `lane` must be a compile-time constant after unrolling).
-__device__ __forceinline__ void write_lane(int& words, uint32_t value, int lane) {
-    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(words) : "s"(value), "n"(lane));
+// words[lane_lo] = lo, words[lane_hi] = hi (wave-uniform values; the lanes must be compile-time constants after
+// unrolling).
+// On this core a vector instruction that reads an SGPR needs two wait states after the vector instruction (here
+// the compare behind a ballot) that wrote it.  The compiler inserts them for its own instructions but does not
+// look inside inline assembly, so the two wait states are part of the statement.
+__device__ __forceinline__ void write_lane_pair(int& words, uint32_t lo, uint32_t hi, int lane_lo, int lane_hi) {
+    asm volatile("s_nop 1\n\tv_writelane_b32 %0, %1, %3\n\tv_writelane_b32 %0, %2, %4"
+                 : "+v"(words) : "s"(lo), "s"(hi), "n"(lane_lo), "n"(lane_hi));
+}
+
+// Called inside the product loop, after the first products: the loads that produced sc/bi then stay in front of
+// the loop, where they were written, instead of moving next to their use in the epilogue, and by the time this
+// point is reached they have long returned (the operand words used by those products were requested later).
+template <int WN>
+__device__ __forceinline__ void pin_loaded(float (&sc)[WN], float (&bi)[WN]) {
+#pragma unroll
+    for (int f = 0; f < WN; ++f) asm volatile("" : "+v"(sc[f]), "+v"(bi[f]));
 }
 
 __device__ __forceinline__ uint32_t word_of(const Raw8& v, int j) {
@@ -87,6 +101,16 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
         brow[f] = Wp + (size_t)(n < N ? n : N - 1) * w32;
     }
 
+    // Scale and bias of this lane's columns, requested before the product so that the epilogue does not wait for
+    // them.  Columns past N get scale = bias = 0: their pre-activation is 0, their Sign bit 0 (pad bits stay 0).
+    float sc[WN], bi[WN];
+#pragma unroll
+    for (int f = 0; f < WN; ++f) {
+        const int n = n_base + f * 32 + r;
+        sc[f] = n < N ? (scale ? scale[n] : 1.0f) : 0.0f;
+        bi[f] = n < N ? (bias ? bias[n] : 0.0f) : 0.0f;
+    }
+
     v16f acc[WM][WN];
 #pragma unroll
     for (int i = 0; i < WM; ++i)
@@ -97,7 +121,47 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
 
     const ExpandConsts ec = expand_consts();
     const int nS = (K + 511) >> 9;
-    if constexpr (PINGPONG) {
+    static_assert(ALIGNED || !PINGPONG, "the pinned pipelines fetch whole 16-byte pieces of whole super-steps");
+    if constexpr (PINGPONG && WM >= 4) {
+        // 128-row wave tiles leave no room for two whole operand sets beside the 128 accumulator registers: the
+        // two sets are the two halves of a super-step (words 0..3 and 4..7 of every lane's share) instead.
+        uint4 alo[WM], blo[WN], ahi[WM], bhi[WN];
+        auto fetch = [&](uint4 (&a)[WM], uint4 (&b)[WN], int S, int half) {
+            const int Sc = S < nS ? S : nS - 1;   // past the end: re-read the last super-step (in bounds, unused)
+            const int base = Sc * 16 + g * 8 + half * 4;
+#pragma unroll
+            for (int f = 0; f < WM; ++f) a[f] = *reinterpret_cast<const uint4*>(arow[f] + base);
+#pragma unroll
+            for (int f = 0; f < WN; ++f) b[f] = *reinterpret_cast<const uint4*>(brow[f] + base);
+        };
+        auto multiply = [&](const uint4 (&a)[WM], const uint4 (&b)[WN]) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v8i bx[WN];
+#pragma unroll
+                for (int f = 0; f < WN; ++f) bx[f] = expand_pm1_fp4(word_of(b[f], j), ec);
+#pragma unroll
+                for (int fm = 0; fm < WM; ++fm) {
+                    const v8i ax = expand_pm1_fp4(word_of(a[fm], j), ec);
+#pragma unroll
+                    for (int fn = 0; fn < WN; ++fn)
+                        acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bx[fn], acc[fm][fn], 4, 4, 0, 0, 0, 0);
+                }
+            }
+        };
+        fetch(alo, blo, 0, 0);
+        for (int S = 0; S < nS; ++S) {
+            fetch(ahi, bhi, S, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(alo, blo);
+            pin_loaded(sc, bi);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(alo, blo, S + 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(ahi, bhi);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else if constexpr (PINGPONG) {
         Raw8 a0[WM], b0[WN], a1[WM], b1[WN];
         auto fetch = [&](Raw8 (&a)[WM], Raw8 (&b)[WN], int S) {
             const int Sc = S < nS ? S : nS - 1;   // past the end: re-read the last super-step (in bounds, unused)
@@ -121,17 +185,22 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
                 }
             }
         };
+        // Both fetches of a round are unconditional: a fetch whose only use sits behind a branch gets moved
+        // behind that branch by the compiler, next to its use, and then nothing overlaps.
         fetch(a0, b0, 0);
-        for (int S = 0; S < nS; S += 2) {
+        int S = 0;
+        for (; S + 1 < nS; S += 2) {
             fetch(a1, b1, S + 1);
             __builtin_amdgcn_sched_barrier(0);
             multiply(a0, b0);
+            pin_loaded(sc, bi);
             __builtin_amdgcn_sched_barrier(0);
             fetch(a0, b0, S + 2);
             __builtin_amdgcn_sched_barrier(0);
-            if (S + 1 < nS) multiply(a1, b1);   // wave-uniform
+            multiply(a1, b1);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (S < nS) multiply(a0, b0);   // odd number of super-steps: the last one is already in the first set
     } else {
         Raw8 araw[WM], braw[WN];
 #pragma unroll
@@ -160,6 +229,7 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
                         acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bx[fn], acc[fm][fn], 4, 4, 0, 0, 0, 0);
                 }
             }
+            pin_loaded(sc, bi);
 #pragma unroll
             for (int f = 0; f < WM; ++f) araw[f] = anext[f];
 #pragma unroll
@@ -174,10 +244,6 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
         uint32_t* Yw = (uint32_t*)Y;
 #pragma unroll
         for (int fn = 0; fn < WN; ++fn) {
-            const int n = n_base + fn * 32 + r;
-            const bool nvalid = n < N;
-            const float sc = (scale && nvalid) ? scale[n] : 1.0f;
-            const float bi = (bias && nvalid) ? bias[n] : 0.0f;
             const int wcol = (n_base >> 5) + fn;
 #pragma unroll
             for (int fm = 0; fm < WM; ++fm) {
@@ -188,9 +254,8 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const float dot = ALIGNED ? acc[fm][fn][v] : acc[fm][fn][v] - pad;   // whole super-steps: no pad
-                    const unsigned long long b = __builtin_amdgcn_ballot_w64(nvalid && sign_bit(affine(sc, dot, bi)));
-                    write_lane(words, (uint32_t)b, v);
-                    write_lane(words, (uint32_t)(b >> 32), 32 + v);
+                    const unsigned long long b = __builtin_amdgcn_ballot_w64(sign_bit(affine(sc[fn], dot, bi[fn])));
+                    write_lane_pair(words, (uint32_t)b, (uint32_t)(b >> 32), v, 32 + v);
                 }
                 if (r < 16) {
                     const int m = m_base + fm * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
@@ -206,15 +271,6 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
         constexpr int LDW = 32 * WN + 4;                       // padded row length in words
         __shared__ __attribute__((aligned(16))) uint32_t stage[4][32 * LDW];
         uint32_t* st = stage[wave];
-        float sc[WN], bi[WN];
-        bool nvalid[WN];
-#pragma unroll
-        for (int fn = 0; fn < WN; ++fn) {
-            const int n = n_base + fn * 32 + r;
-            nvalid[fn] = n < N;
-            sc[fn] = (scale && nvalid[fn]) ? scale[n] : 1.0f;
-            bi[fn] = (bias && nvalid[fn]) ? bias[n] : 0.0f;
-        }
         const bool rows_vec = ((N & 3) == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
         const int c4 = (lane & 15) * 4;                        // this lane's 4 columns of the 64
 #pragma unroll

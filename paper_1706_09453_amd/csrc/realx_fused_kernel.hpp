@@ -62,7 +62,9 @@ __device__ __forceinline__ int permuted_byte_of_k(int kk) {
 
 // LDS layout (bytes from the start of the dynamic LDS): digit planes | fp32 frames | two weight stages | output tile
 __host__ __device__ constexpr int realx_plane_row(int kpad) { return kpad + 16; }   // +16 spreads the 16 rows over the banks
-__host__ __device__ constexpr int realx_wrow(int w32) { return w32 | 1; }           // words; odd for the same reason
+// Words per weight row in an LDS stage.  16 lanes read the same word of 16 consecutive rows: a row length of
+// 2 * odd words puts them in 16 different banks, and then a chunk is one contiguous copy; otherwise pad to odd.
+__host__ __device__ constexpr int realx_wrow(int w32) { return (w32 & 3) == 2 ? w32 : (w32 | 1); }
 __host__ __device__ constexpr size_t realx_off_xs(int kpad) { return (size_t)kDigits * kRealxBM * realx_plane_row(kpad); }
 __host__ __device__ constexpr size_t realx_off_w(int K, int kpad) {
     return realx_off_xs(kpad) + ((size_t)kRealxBM * (K + 1) * 4 + 15) / 16 * 16;
@@ -140,7 +142,9 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
 #pragma unroll
         for (int i = 0; i < WPT; ++i) {
             const int f = (int)threadIdx.x + i * kRealxThreads;
-            if (4 * f < total) {
+            if (ldw == w32 && 4 * f + 3 < total) {             // unpadded rows: the chunk is one contiguous run in LDS too
+                reinterpret_cast<uint4*>(stage)[f] = wreg[i];
+            } else if (4 * f < total) {
                 int row = (4 * f) / w32, col = 4 * f - row * w32;
                 const uint32_t w4[4] = {wreg[i].x, wreg[i].y, wreg[i].z, wreg[i].w};
 #pragma unroll
