@@ -215,7 +215,8 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
             const float e_conv = u * (float)A;                                   // (float)a
             const float inv = __uint_as_float((unsigned int)(127 - s) << 23);
             RowMeta rm;
-            rm.R = R; rm.inv_scale = inv; rm.E = (e_seq + e_quant + e_conv) * 1.01f * inv; rm.flags = flags;
+            rm.R = R; rm.inv_scale = inv; rm.flags = flags;
+            rm.E = flags ? __builtin_inff() : (e_seq + e_quant + e_conv) * 1.01f * inv;   // infinite bound: every output uncertain
             meta[ml] = rm;
         }
     }
@@ -227,8 +228,12 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
     const int sh = 4 * (g & 1);
     const int8_t* al = planes + (size_t)r * plrow + 16 * g;
     RowMeta rmeta[4];
+    unsigned long long mv[4];   // lanes whose frame 4g+q exists
 #pragma unroll
-    for (int q = 0; q < 4; ++q) rmeta[q] = meta[4 * g + q];
+    for (int q = 0; q < 4; ++q) {
+        rmeta[q] = meta[4 * g + q];
+        mv[q] = __builtin_amdgcn_ballot_w64(m_base + 4 * g + q < M);
+    }
 
     for (int c0 = 0, ci = 0; c0 < nb; c0 += kRealxChunk, ++ci) {
         const uint32_t* stage = wst + (ci & 1) * stage_words;
@@ -237,14 +242,18 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
         __builtin_amdgcn_sched_barrier(0);
         const int nw = c0 + wave * (WN * 16);
         if (nw < nb) {   // wave-uniform
-            float sc[WN], bi[WN];
-            bool nvalid[WN];
+            // Outputs past the block's end get scale 0 and bias -1: pre-activation -1, certain, bit 0.
+            float sc[WN], bi[WN], asc[WN];
+            unsigned long long nv[WN];   // lanes whose output exists
 #pragma unroll
             for (int fn = 0; fn < WN; ++fn) {
                 const int nl = nw + fn * 16 + r;
-                nvalid[fn] = nl < nb;
-                sc[fn] = (scale && nvalid[fn]) ? scale[n_block + nl] : 1.0f;
-                bi[fn] = (bias && nvalid[fn]) ? bias[n_block + nl] : 0.0f;
+                const bool nvalid = nl < nb;
+                nv[fn] = __builtin_amdgcn_ballot_w64(nvalid);
+                sc[fn] = nvalid ? (scale ? scale[n_block + nl] : 1.0f) : 0.0f;
+                bi[fn] = nvalid ? (bias ? bias[n_block + nl] : 0.0f) : -1.0f;
+                // |scale| (1 + 2^-16.6) covers the roundings of the margin; the floor covers a product that underflows
+                asc[fn] = __builtin_fmaxf(__builtin_fabsf(sc[fn]) * 1.00001f, 1e-30f);
             }
             v4i32 acc[kDigits][WN];
 #pragma unroll
@@ -275,33 +284,45 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
                 }
             }
 
-            // accumulator register q of lane (r, g), fragment fn: frame 4g+q of the tile, output nw + 16 fn + r of the block
+            // accumulator register q of lane (r, g), fragment fn: frame 4g+q of the tile, output nw + 16 fn + r of the block.
+            // With t = fma(scale, a, bias): if |t| > |scale| E (1 + 2^-16.6) + 1e-30, then scale x + bias has the sign
+            // of t, and at least 1e-30 in magnitude, for every real x within E of a, so its rounding has that sign
+            // too and the bit of the fp32 sum is (t > 0).  Anything else (NaN included) is uncertain.
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int ml = 4 * g + q;
-                const int m = m_base + ml;
-                const bool mvalid = m < M;
                 const RowMeta rm = rmeta[q];
-                unsigned long long b[WN];
+                unsigned long long b[WN], u[WN];
+                unsigned long long any_u = 0ull;
 #pragma unroll
                 for (int fn = 0; fn < WN; ++fn) {
-                    const int P = acc[0][fn][q] + acc[1][fn][q] * (1 << kDigitBits) + acc[2][fn][q] * (1 << (2 * kDigitBits));
-                    const float a = (float)(2 * P - rm.R) * rm.inv_scale;
-                    const float Ew = rm.E + __builtin_fabsf(a) * 2.384185791015625e-07f;   // + 2^-22 |a| for the two roundings below
-                    const bool lo = sign_bit(affine(sc[fn], a - Ew, bi[fn]));
-                    const bool hi = sign_bit(affine(sc[fn], a + Ew, bi[fn]));
-                    bool bit = lo;
-                    if (mvalid && nvalid[fn] && (lo != hi || rm.flags)) {
-                        const int nl = nw + fn * 16 + r;
-                        const unsigned int slot = atomicAdd(&list_count, 1u);
-                        if (slot < (unsigned int)kRealxListCap) {
-                            list[slot] = ((unsigned int)ml << 16) | (unsigned int)nl;
-                            bit = false;                       // resolved below; set by an LDS atomic OR if it is 1
-                        } else {
-                            bit = sign_bit(affine(sc[fn], canonical_acc_global(X + (size_t)m * K, Wp + (size_t)(n_block + nl) * w32, K), bi[fn]));
+                    const unsigned int P = ((((unsigned int)acc[2][fn][q] << kDigitBits) + (unsigned int)acc[1][fn][q]) << kDigitBits) +
+                                           (unsigned int)acc[0][fn][q];
+                    const float a = (float)(int)((P << 1) - (unsigned int)rm.R) * rm.inv_scale;
+                    const float t = affine(sc[fn], a, bi[fn]);
+                    const float margin = __builtin_fmaf(asc[fn], rm.E, 1e-30f);
+                    const unsigned long long certain = __builtin_amdgcn_ballot_w64(__builtin_fabsf(t) > margin);
+                    const unsigned long long pos = __builtin_amdgcn_ballot_w64(t > 0.0f);
+                    u[fn] = ~certain & nv[fn] & mv[q];
+                    b[fn] = pos & certain;
+                    any_u |= u[fn];
+                }
+                if (any_u != 0ull) {   // wave-uniform, a few in 10^4 outputs
+#pragma unroll
+                    for (int fn = 0; fn < WN; ++fn) {
+                        bool bit = false;
+                        if ((u[fn] >> lane) & 1ull) {
+                            const int nl = nw + fn * 16 + r;
+                            const unsigned int slot = atomicAdd(&list_count, 1u);
+                            if (slot < (unsigned int)kRealxListCap) {
+                                list[slot] = ((unsigned int)ml << 16) | (unsigned int)nl;   // resolved below; set by an LDS atomic OR if it is 1
+                            } else {
+                                const int m = m_base + ml;
+                                bit = sign_bit(affine(sc[fn], canonical_acc_global(X + (size_t)m * K, Wp + (size_t)(n_block + nl) * w32, K), bi[fn]));
+                            }
                         }
+                        b[fn] |= __builtin_amdgcn_ballot_w64(bit);
                     }
-                    b[fn] = __builtin_amdgcn_ballot_w64(nvalid[fn] && bit);
                 }
                 if (lane < 4) {   // ballot bit 16 gg + rr: frame 4 gg + q, output 16 fn + rr; lane gg assembles frame 4 gg + q
                     const int shb = 16 * lane;
