@@ -155,22 +155,23 @@ template <int WM, bool AL, bool PP = false>
 void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
                         int w32, int act, void* Y, int yw32, hipStream_t st) {
     constexpr int WN = 2;
+    const unsigned int ab = (unsigned int)((size_t)M * w32 * 4), bb = (unsigned int)((size_t)N * w32 * 4);   // used by the PP variants only
     const dim3 grid((M + 64 * WM - 1) / (64 * WM), (N + 64 * WN - 1) / (64 * WN)), block(256);
     switch (act) {
         case ACT_DOT_I16:
-            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
             break;
         case BNN_ACT_RAW_I32:
-            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
             break;
         case BNN_ACT_SIGN:
-            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
             break;
         case BNN_ACT_HARDTANH:
-            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
             break;
         default:
-            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
             break;
     }
 }
@@ -226,7 +227,8 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
         const int64_t blocks4 = ((M + 255) / 256) * ((N + 127) / 128);
         const int wm32 = g_mfma32_wm.load();
         const bool wm2 = wm32 == 2 || (wm32 == 0 && blocks4 < 200);
-        const bool pinned = g_mfma32_pipeline.load() != 2;   // fetch pinned ahead of the products: faster on every shape measured
+        // fetch pinned ahead of the products: faster on every shape measured; buffer addressing needs operands below 2 GiB
+        const bool pinned = g_mfma32_pipeline.load() != 2 && (size_t)M * w32 * 4 < 0x7fffffffu && (size_t)N * w32 * 4 < 0x7fffffffu;
         if (!al) {
             // ragged rows: bounds-checked word loads, 64-row wave tiles only
             launch_binx_mfma32<2, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);

@@ -67,6 +67,13 @@ __device__ __forceinline__ void pin_loaded(float (&sc)[WN], float (&bi)[WN]) {
     for (int f = 0; f < WN; ++f) asm volatile("" : "+v"(sc[f]), "+v"(bi[f]));
 }
 
+// 16 bytes at byte offset voff (per lane) + soff (wave-uniform) of a buffer.
+__device__ __forceinline__ uint4 load16(__amdgpu_buffer_rsrc_t rs, int voff, int soff) {
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 __device__ __forceinline__ uint32_t word_of(const Raw8& v, int j) {
     return j < 4 ? word_of(v.lo, j) : word_of(v.hi, j - 4);
 }
@@ -79,7 +86,8 @@ __device__ __forceinline__ uint32_t word_of(const Raw8& v, int j) {
 template <int WM, int WN, int ACT, bool ALIGNED, bool PINGPONG = false>
 __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
                                                           const float* __restrict__ scale, const float* __restrict__ bias,
-                                                          int M, int K, int N, int w32, void* __restrict__ Y, int yw32) {
+                                                          int M, int K, int N, int w32, void* __restrict__ Y, int yw32,
+                                                          unsigned int a_bytes, unsigned int b_bytes) {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     const int r = lane & 31;   // row of the operand fragment / column of the accumulator fragment
@@ -112,29 +120,37 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
     }
 
     v16f acc[WM][WN];
+    if constexpr (!PINGPONG || WM >= 4) {   // (the 64-row pinned variant starts its accumulators with a zero addend instead)
 #pragma unroll
-    for (int i = 0; i < WM; ++i)
+        for (int i = 0; i < WM; ++i)
 #pragma unroll
-        for (int j = 0; j < WN; ++j)
+            for (int j = 0; j < WN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    }
 
     const ExpandConsts ec = expand_consts();
     const int nS = (K + 511) >> 9;
     static_assert(ALIGNED || !PINGPONG, "the pinned pipelines fetch whole 16-byte pieces of whole super-steps");
-    if constexpr (PINGPONG && WM >= 4) {
-        // 128-row wave tiles leave no room for two whole operand sets beside the 128 accumulator registers: the
-        // two sets are the two halves of a super-step (words 0..3 and 4..7 of every lane's share) instead.
-        uint4 alo[WM], blo[WN], ahi[WM], bhi[WN];
-        auto fetch = [&](uint4 (&a)[WM], uint4 (&b)[WN], int S, int half) {
-            const int Sc = S < nS ? S : nS - 1;   // past the end: re-read the last super-step (in bounds, unused)
-            const int base = Sc * 16 + g * 8 + half * 4;
+    const v16f zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (PINGPONG) {
+        // Buffer addressing: one byte offset per fragment row in a VGPR, the position along K in an SGPR, so the loop
+        // carries no 64-bit address arithmetic.  (The host selects these variants only for operands below 2 GiB.)
+        const __amdgpu_buffer_rsrc_t ars = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(Xp), 0, (int)a_bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(Wp), 0, (int)b_bytes, 0x00020000);
+        int aoff[WM], boff[WN];
 #pragma unroll
-            for (int f = 0; f < WM; ++f) a[f] = *reinterpret_cast<const uint4*>(arow[f] + base);
+        for (int f = 0; f < WM; ++f) {
+            const int m = m_base + f * 32 + r;
+            aoff[f] = ((m < M ? m : M - 1) * w32 + g * 8) * 4;
+        }
 #pragma unroll
-            for (int f = 0; f < WN; ++f) b[f] = *reinterpret_cast<const uint4*>(brow[f] + base);
-        };
-        auto multiply = [&](const uint4 (&a)[WM], const uint4 (&b)[WN]) {
+        for (int f = 0; f < WN; ++f) {
+            const int n = n_base + f * 32 + r;
+            boff[f] = ((n < N ? n : N - 1) * w32 + g * 8) * 4;
+        }
+        // the first product into each accumulator takes a zero addend instead of a cleared register
+        auto products = [&](const uint4 (&a)[WM], const uint4 (&b)[WN], bool first) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 v8i bx[WN];
@@ -145,62 +161,74 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
                     const v8i ax = expand_pm1_fp4(word_of(a[fm], j), ec);
 #pragma unroll
                     for (int fn = 0; fn < WN; ++fn)
-                        acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bx[fn], acc[fm][fn], 4, 4, 0, 0, 0, 0);
+                        acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bx[fn], (first && j == 0) ? zero16 : acc[fm][fn],
+                                                                                    4, 4, 0, 0, 0, 0);
                 }
             }
         };
-        fetch(alo, blo, 0, 0);
-        for (int S = 0; S < nS; ++S) {
-            fetch(ahi, bhi, S, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(alo, blo);
-            pin_loaded(sc, bi);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(alo, blo, S + 1, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(ahi, bhi);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    } else if constexpr (PINGPONG) {
-        Raw8 a0[WM], b0[WN], a1[WM], b1[WN];
-        auto fetch = [&](Raw8 (&a)[WM], Raw8 (&b)[WN], int S) {
-            const int Sc = S < nS ? S : nS - 1;   // past the end: re-read the last super-step (in bounds, unused)
+        if constexpr (WM >= 4) {
+            // 128-row wave tiles leave no room for two whole operand sets beside the 128 accumulator registers: the
+            // two sets are the two halves of a super-step (words 0..3 and 4..7 of every lane's share) instead.
+            uint4 alo[WM], blo[WN], ahi[WM], bhi[WN];
+            // (plain pointer loads here: buffer addressing saves the address arithmetic but measured 3 % slower on
+            //  this variant, as did a peeled first round with zero addends: more code to fetch for four rounds)
+            auto fetch = [&](uint4 (&a)[WM], uint4 (&b)[WN], int S, int half) {
+                const int Sc = S < nS ? S : nS - 1;   // past the end: re-read the last super-step (in bounds, unused)
+                const int base = Sc * 16 + g * 8 + half * 4;
 #pragma unroll
-            for (int f = 0; f < WM; ++f) a[f] = load_raw8<ALIGNED>(arow[f], Sc, g, w32);
+                for (int f = 0; f < WM; ++f) a[f] = *reinterpret_cast<const uint4*>(arow[f] + base);
 #pragma unroll
-            for (int f = 0; f < WN; ++f) b[f] = load_raw8<ALIGNED>(brow[f], Sc, g, w32);
-        };
-        auto multiply = [&](const Raw8 (&a)[WM], const Raw8 (&b)[WN]) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                v8i bx[WN];
-#pragma unroll
-                for (int f = 0; f < WN; ++f) bx[f] = expand_pm1_fp4(word_of(b[f], j), ec);
-#pragma unroll
-                for (int fm = 0; fm < WM; ++fm) {
-                    const v8i ax = expand_pm1_fp4(word_of(a[fm], j), ec);
-#pragma unroll
-                    for (int fn = 0; fn < WN; ++fn)
-                        acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax, bx[fn], acc[fm][fn], 4, 4, 0, 0, 0, 0);
-                }
+                for (int f = 0; f < WN; ++f) b[f] = *reinterpret_cast<const uint4*>(brow[f] + base);
+            };
+            // Every fetch is unconditional: a fetch whose only use sits behind a branch gets moved behind that
+            // branch by the compiler, next to its use, and then nothing overlaps.
+            fetch(alo, blo, 0, 0);
+            for (int S = 0; S < nS; ++S) {
+                fetch(ahi, bhi, S, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                products(alo, blo, false);
+                pin_loaded(sc, bi);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(alo, blo, S + 1, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                products(ahi, bhi, false);
+                __builtin_amdgcn_sched_barrier(0);
             }
-        };
-        // Both fetches of a round are unconditional: a fetch whose only use sits behind a branch gets moved
-        // behind that branch by the compiler, next to its use, and then nothing overlaps.
-        fetch(a0, b0, 0);
-        int S = 0;
-        for (; S + 1 < nS; S += 2) {
-            fetch(a1, b1, S + 1);
+        } else {
+            // two whole super-steps in registers; set 0 holds the even ones at first, then the sets alternate
+            uint4 a0l[WM], a0h[WM], b0l[WN], b0h[WN], a1l[WM], a1h[WM], b1l[WN], b1h[WN];
+            auto fetch = [&](uint4 (&al)[WM], uint4 (&ah)[WM], uint4 (&bl)[WN], uint4 (&bh)[WN], int S) {
+                const int so = (S < nS ? S : nS - 1) * 64;
+#pragma unroll
+                for (int f = 0; f < WM; ++f) { al[f] = load16(ars, aoff[f], so); ah[f] = load16(ars, aoff[f], so + 16); }
+#pragma unroll
+                for (int f = 0; f < WN; ++f) { bl[f] = load16(brs, boff[f], so); bh[f] = load16(brs, boff[f], so + 16); }
+            };
+            fetch(a0l, a0h, b0l, b0h, 0);
+            fetch(a1l, a1h, b1l, b1h, 1);
             __builtin_amdgcn_sched_barrier(0);
-            multiply(a0, b0);
-            pin_loaded(sc, bi);
+            products(a0l, b0l, true);
+            products(a0h, b0h, false);
             __builtin_amdgcn_sched_barrier(0);
-            fetch(a0, b0, S + 2);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(a1, b1);
-            __builtin_amdgcn_sched_barrier(0);
+            int S = 1;   // set 1 holds super-step S, set 0 is free
+            for (; S + 1 < nS; S += 2) {
+                fetch(a0l, a0h, b0l, b0h, S + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                products(a1l, b1l, false);
+                products(a1h, b1h, false);
+                pin_loaded(sc, bi);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(a1l, a1h, b1l, b1h, S + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                products(a0l, b0l, false);
+                products(a0h, b0h, false);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (S < nS) {   // one super-step left, already in set 1
+                products(a1l, b1l, false);
+                products(a1h, b1h, false);
+            }
         }
-        if (S < nS) multiply(a0, b0);   // odd number of super-steps: the last one is already in the first set
     } else {
         Raw8 araw[WM], braw[WN];
 #pragma unroll
