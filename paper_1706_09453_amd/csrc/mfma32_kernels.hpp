@@ -169,12 +169,15 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
         if constexpr (WM >= 4) {
             // 128-row wave tiles leave no room for two whole operand sets beside the 128 accumulator registers: the
             // two sets are the two halves of a super-step (words 0..3 and 4..7 of every lane's share) instead.
-            uint4 alo[WM], blo[WN], ahi[WM], bhi[WN];
+            // Three sets in rotation, fetched two half-steps ahead: with one wave per SIMD (4096 x 2048 outputs fill the
+            // chip exactly once) nothing else covers the memory latency, and one half-step of products is shorter.
+            uint4 a0[WM], b0[WN], a1[WM], b1[WN], a2[WM], b2[WN];
+            const int H = 2 * nS;   // half-steps
             // (plain pointer loads here: buffer addressing saves the address arithmetic but measured 3 % slower on
             //  this variant, as did a peeled first round with zero addends: more code to fetch for four rounds)
-            auto fetch = [&](uint4 (&a)[WM], uint4 (&b)[WN], int S, int half) {
-                const int Sc = S < nS ? S : nS - 1;   // past the end: re-read the last super-step (in bounds, unused)
-                const int base = Sc * 16 + g * 8 + half * 4;
+            auto fetch = [&](uint4 (&a)[WM], uint4 (&b)[WN], int h) {
+                const int hc = h < H ? h : H - 1;   // past the end: re-read the last half-step (in bounds, unused)
+                const int base = (hc >> 1) * 16 + g * 8 + (hc & 1) * 4;
 #pragma unroll
                 for (int f = 0; f < WM; ++f) a[f] = *reinterpret_cast<const uint4*>(arow[f] + base);
 #pragma unroll
@@ -182,18 +185,77 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
             };
             // Every fetch is unconditional: a fetch whose only use sits behind a branch gets moved behind that
             // branch by the compiler, next to its use, and then nothing overlaps.
-            fetch(alo, blo, 0, 0);
-            for (int S = 0; S < nS; ++S) {
-                fetch(ahi, bhi, S, 1);
+            // Issue order inside a half-step, written out and pinned slot by slot.  A wave issues in order, and an
+            // MFMA that finds the pipe busy (32 clocks per 32x32x64) blocks whatever follows it: left to the
+            // compiler's order (expansions in clumps, MFMAs back to back) one wave per SIMD ran at 70 clocks per
+            // MFMA.  Here every MFMA is followed by the 5-6 expansion instructions of an operand needed two to
+            // eight MFMAs later, which issue in its shadow: the frames fragment fm+1 of this step while fm is
+            // multiplied, and the two weights fragments and frames fragment 0 of the NEXT step (taken from the next
+            // register set after the last step of a half-step) spread over the eight slots.
+            static_assert(WM == 4 && WN == 2, "the slot plan below is written for 4 x 2 fragments");
+            v8i bx[2][WN];   // expanded weights: [parity of the step][fragment]
+            v8i ax[2];       // expanded frames: fragment fm lives in ax[fm & 1]
+            auto piece = [&](v8i& dst, uint32_t w, int part) {   // part 0..2: shifted dwords (2 instructions), 3: unshifted (1)
+                dst[part] = (int)((((part < 3) ? (w << (3 - part)) : w) & ec.sign_mask) | ec.one_bits);
+            };
+            auto clear_hi = [&](v8i& d) { d[4] = 0; d[5] = 0; d[6] = 0; d[7] = 0; };   // unused by the 4-bit format
+            clear_hi(ax[0]); clear_hi(ax[1]);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int f = 0; f < WN; ++f) clear_hi(bx[t][f]);
+            auto half_step = [&](const uint4 (&a)[WM], const uint4 (&b)[WN], const uint4 (&an)[WM], const uint4 (&bn)[WN]) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int pc = j & 1, pn = pc ^ 1;
+                    // words of the next step: the next word of this set, or the first word of the next set
+                    const uint32_t wb0 = j < 3 ? word_of(b[0], j + 1) : word_of(bn[0], 0);
+                    const uint32_t wb1 = j < 3 ? word_of(b[1], j + 1) : word_of(bn[1], 0);
+                    const uint32_t wa0 = j < 3 ? word_of(a[0], j + 1) : word_of(an[0], 0);
+                    const uint32_t wa1 = word_of(a[1], j), wa2 = word_of(a[2], j), wa3 = word_of(a[3], j);
+#define BNN_MFMA(fm, fn) acc[fm][fn] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ax[(fm) & 1], bx[pc][fn], acc[fm][fn], 4, 4, 0, 0, 0, 0)
+#define BNN_SLOT_END __builtin_amdgcn_sched_barrier(0)
+                    BNN_MFMA(0, 0); piece(ax[1], wa1, 0); piece(ax[1], wa1, 1); piece(ax[1], wa1, 3); BNN_SLOT_END;
+                    BNN_MFMA(0, 1); piece(ax[1], wa1, 2); piece(bx[pn][0], wb0, 0); piece(bx[pn][0], wb0, 3); BNN_SLOT_END;
+                    BNN_MFMA(1, 0); piece(ax[0], wa2, 0); piece(ax[0], wa2, 1); piece(ax[0], wa2, 3); BNN_SLOT_END;
+                    BNN_MFMA(1, 1); piece(ax[0], wa2, 2); piece(bx[pn][0], wb0, 1); piece(bx[pn][0], wb0, 2); BNN_SLOT_END;
+                    BNN_MFMA(2, 0); piece(ax[1], wa3, 0); piece(ax[1], wa3, 1); piece(ax[1], wa3, 3); BNN_SLOT_END;
+                    BNN_MFMA(2, 1); piece(ax[1], wa3, 2); piece(bx[pn][1], wb1, 0); piece(bx[pn][1], wb1, 3); BNN_SLOT_END;
+                    BNN_MFMA(3, 0); piece(bx[pn][1], wb1, 1); piece(bx[pn][1], wb1, 2); BNN_SLOT_END;
+                    BNN_MFMA(3, 1); BNN_SLOT_END;
+                    // frames fragment 0 of the next step overwrites ax[0], which MFMA (2, *) has finished reading
+                    piece(ax[0], wa0, 0); piece(ax[0], wa0, 1); piece(ax[0], wa0, 2); piece(ax[0], wa0, 3); BNN_SLOT_END;
+#undef BNN_MFMA
+#undef BNN_SLOT_END
+                }
+            };
+            // Every fetch is unconditional: a fetch whose only use sits behind a branch gets moved behind that
+            // branch by the compiler, next to its use, and then nothing overlaps.
+            fetch(a0, b0, 0);
+            fetch(a1, b1, 1);
+            {   // operands of the very first step
+                const uint32_t wb0 = word_of(b0[0], 0), wb1 = word_of(b0[1], 0), wa0 = word_of(a0[0], 0);
+#pragma unroll
+                for (int part = 0; part < 4; ++part) { piece(bx[0][0], wb0, part); piece(bx[0][1], wb1, part); piece(ax[0], wa0, part); }
+            }
+            int h = 0;
+            for (; h + 2 < H; h += 3) {
+                fetch(a2, b2, h + 2);
                 __builtin_amdgcn_sched_barrier(0);
-                products(alo, blo, false);
+                half_step(a0, b0, a1, b1);
                 pin_loaded(sc, bi);
                 __builtin_amdgcn_sched_barrier(0);
-                fetch(alo, blo, S + 1, 0);
+                fetch(a0, b0, h + 3);
                 __builtin_amdgcn_sched_barrier(0);
-                products(ahi, bhi, false);
+                half_step(a1, b1, a2, b2);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(a1, b1, h + 4);
+                __builtin_amdgcn_sched_barrier(0);
+                half_step(a2, b2, a0, b0);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (h < H) half_step(a0, b0, a1, b1);       // one or two half-steps left, already fetched
+            if (h + 1 < H) half_step(a1, b1, a2, b2);
         } else {
             // two whole super-steps in registers; set 0 holds the even ones at first, then the sets alternate
             uint4 a0l[WM], a0h[WM], b0l[WN], b0h[WN], a1l[WM], a1h[WM], b1l[WN], b1h[WN];
