@@ -39,7 +39,7 @@ def gemm_sweep(args, bnn, workloads, G, torch) -> int:
         A = G.to_dev(workloads.random_words(0, 500 + workloads.TENSOR_ABITS, M, K // 32))
         B = G.to_dev(workloads.random_words(0, 500 + workloads.TENSOR_BBITS, N, K // 32))
         Y = torch.empty((M, N), dtype=torch.int32, device=G.DEV)
-        for arm_name, arm in (("mfma", bnn.BNN_ARM_MFMA), ("valu", bnn.BNN_ARM_VALU_XOR)):
+        for arm_name, arm in (("mfma", bnn.BNN_ARM_MFMA), ("mfma_i8", bnn.BNN_ARM_MFMA_I8), ("valu", bnn.BNN_ARM_VALU_XOR)):
             def call():
                 bnn.bnn_layer_binw_binx_arm(A.data_ptr(), B.data_ptr(), 0, 0, M, K, N, bnn.BNN_ACT_RAW_I32, 32,
                                             Y.data_ptr(), arm, G.stream())
@@ -69,7 +69,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--arm", choices=["mfma", "valu"], default="mfma")
+    ap.add_argument("--arm", choices=["mfma", "mfma_i8", "valu"], default="mfma",
+                    help="arm of the binary product: 4-bit-float MFMA (default), int8 MFMA, or XOR/popcount on the vector ALU")
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
     ap.add_argument("--copy-calibration", action="store_true", help="run 10 plain 256 MiB device copies (counter calibration)")
     ap.add_argument("--gemm-sweep", action="store_true", help="time the isolated binary GEMM sweep (Config 5) instead")
@@ -107,7 +108,7 @@ def main() -> int:
     model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
     X = G.to_dev(X_host)
     out = torch.empty((M, model.N_out), dtype=torch.float32, device=G.DEV)
-    arm = bnn.BNN_ARM_MFMA if args.arm == "mfma" else bnn.BNN_ARM_VALU_XOR
+    arm = {"mfma": bnn.BNN_ARM_MFMA, "mfma_i8": bnn.BNN_ARM_MFMA_I8, "valu": bnn.BNN_ARM_VALU_XOR}[args.arm]
     bnn.bnn_set_option(bnn.BNN_OPT_BINX_ARM, arm)
     for kv in args.opt:
         key, val = kv.split("=")
@@ -181,6 +182,8 @@ def main() -> int:
         bound, peak = "mfma", PEAK_MFMA_INT8_TOPS / 3.0   # three int8 digit products per fp32 multiply-add
     elif args.arm == "mfma":
         bound, peak = "mfma", PEAK_MFMA_FP4_TFLOPS
+    elif args.arm == "mfma_i8":
+        bound, peak = "mfma", PEAK_MFMA_INT8_TOPS
     else:
         bound, peak = "alu", PEAK_XOR_POPC_TOPS
     # HBM bytes per launch of each kernel group from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
@@ -199,7 +202,9 @@ def main() -> int:
         "metric": "frames/sec, 6x2048 binarized DNN (binary weights and activations), batch 4096, 1xMI355X",
         "value": round(frames_per_s, 1), "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "b1 (+-1 as fp4-e2m1 MFMA operands, exact fp32 accumulate) + f32" if args.arm == "mfma" else "b1 (xor+popcount u32) + f32",
+        "dtype": {"mfma": "b1 (+-1 as fp4-e2m1 MFMA operands, exact fp32 accumulate) + f32",
+                  "mfma_i8": "b1 (+-1 as int8 MFMA operands, int32 accumulate) + f32",
+                  "valu": "b1 (xor+popcount u32) + f32"}[args.arm],
         "data": "synthetic",
         "config": {"workload": cfg.name, "dims": list(cfg.dims), "batch_frames": M, "word_bits": cfg.word_bits,
                    "binx_arm": args.arm},

@@ -62,12 +62,13 @@ typedef enum bnn_act {
 typedef enum bnn_binx_arm {
     BNN_ARM_AUTO = 0,      /* the arm measurement showed to be faster for the shape */
     BNN_ARM_VALU_XOR = 1,  /* v_xor + accumulating v_bcnt on packed words (Sec. 2.3 of the paper, literally) */
-    BNN_ARM_MFMA = 2       /* +-1 expanded in registers to a matrix-core operand format, MFMA accumulate    */
+    BNN_ARM_MFMA = 2,      /* +-1 expanded in registers to the 4-bit float matrix-core operand format (exact)  */
+    BNN_ARM_MFMA_I8 = 3    /* +-1 expanded in registers to int8, int8 MFMA with int32 accumulate (comparison)  */
 } bnn_binx_arm;
 
 /* Kernel-selection knobs for bnn_set_option (measurement and tuning; results never change). */
 typedef enum bnn_option {
-    BNN_OPT_BINX_ARM = 1,      /* arm used for BNN_ARM_AUTO: BNN_ARM_VALU_XOR or BNN_ARM_MFMA                    */
+    BNN_OPT_BINX_ARM = 1,      /* arm used for BNN_ARM_AUTO: BNN_ARM_VALU_XOR, BNN_ARM_MFMA or BNN_ARM_MFMA_I8   */
     BNN_OPT_REALX_TM = 2,      /* frames per wavefront of the real-input kernel: 8, 16 or 32                    */
     BNN_OPT_BINX_VALU_TM = 3,  /* frames per wavefront of the XOR/popcount kernel: 8, 16 or 32                  */
     BNN_OPT_MFMA_WM = 4,       /* 16-row accumulator fragments per wavefront of the matrix-core kernel: 2 or 4  */

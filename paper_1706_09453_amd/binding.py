@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbnn_hip.so")
 
 BNN_OK, BNN_EINVAL, BNN_ESHAPE, BNN_EALIGN, BNN_EWORKSPACE, BNN_EDEVICE = 0, -1, -2, -3, -4, -5
 BNN_ACT_RAW_I32, BNN_ACT_LINEAR, BNN_ACT_HARDTANH, BNN_ACT_SIGN, BNN_ACT_LOGSOFTMAX = 0, 1, 2, 3, 4
-BNN_ARM_AUTO, BNN_ARM_VALU_XOR, BNN_ARM_MFMA = 0, 1, 2
+BNN_ARM_AUTO, BNN_ARM_VALU_XOR, BNN_ARM_MFMA, BNN_ARM_MFMA_I8 = 0, 1, 2, 3
 BNN_OPT_BINX_ARM, BNN_OPT_REALX_TM, BNN_OPT_BINX_VALU_TM, BNN_OPT_MFMA_WM = 1, 2, 3, 4
 BNN_OPT_REALX_SIGN_MFMA, BNN_OPT_FUSED_LOGSOFTMAX, BNN_OPT_MFMA_SHAPE, BNN_OPT_MFMA32_WM = 5, 6, 7, 8
 BNN_OPT_MFMA32_PIPELINE = 9

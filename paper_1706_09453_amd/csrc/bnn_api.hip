@@ -8,6 +8,7 @@
 
 #include "../../include/bnn.h"
 #include "mfma32_kernels.hpp"
+#include "mfma_i8_kernels.hpp"
 #include "mfma_kernels.hpp"
 #include "pack_kernels.hpp"
 #include "realx_fused_kernel.hpp"
@@ -176,6 +177,26 @@ void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* sca
     }
 }
 
+template <bool AL>
+void launch_binx_mfma_i8(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
+                         int w32, int act, void* Y, int yw32, hipStream_t st) {
+    const dim3 grid((M + 127) / 128, (N + 127) / 128), block(256);
+    switch (act) {
+        case BNN_ACT_RAW_I32:
+            binx_mfma_i8_kernel<ACT_RAW_I32, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_SIGN:
+            binx_mfma_i8_kernel<ACT_SIGN, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_HARDTANH:
+            binx_mfma_i8_kernel<ACT_HARDTANH, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        default:
+            binx_mfma_i8_kernel<ACT_LINEAR, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+    }
+}
+
 int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K, int64_t N,
              int act, int wb, void* Y, int arm, hipStream_t st) {
     if (M == 0) return BNN_OK;
@@ -196,6 +217,9 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
             else if (tm == 32) launch_binx_valu_tm<32, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
             else launch_binx_valu_tm<16, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         }
+    } else if (arm == BNN_ARM_MFMA_I8) {
+        if (rows16 && K % 512 == 0) launch_binx_mfma_i8<true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        else launch_binx_mfma_i8<false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
     } else if (act == BNN_ACT_LOGSOFTMAX && g_fused_softmax.load() && rows16 &&
                ((K % 512 == 0 && N <= 16 * 8 * 16) || (K % 256 == 0 && N <= 16 * 8 * 32)) &&
                (size_t)(M + 16) * w32 * 4 < 0x7fffffffu && (size_t)(N + 512) * w32 * 4 < 0x7fffffffu) {
@@ -358,7 +382,7 @@ BNN_EXPORT const char* bnn_status_string(int status) {
 BNN_EXPORT int bnn_set_option(int option, int value) {
     switch (option) {
         case BNN_OPT_BINX_ARM:
-            if (value != BNN_ARM_VALU_XOR && value != BNN_ARM_MFMA) return BNN_EINVAL;
+            if (value != BNN_ARM_VALU_XOR && value != BNN_ARM_MFMA && value != BNN_ARM_MFMA_I8) return BNN_EINVAL;
             g_default_arm.store(value);
             return BNN_OK;
         case BNN_OPT_REALX_TM:
@@ -433,7 +457,7 @@ BNN_EXPORT int bnn_layer_binw_realx(const float* X, const void* Wp, const float*
 
 BNN_EXPORT int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M,
                                        int64_t K, int64_t N, int act, int word_bits, void* Y, int arm, void* stream) {
-    if (arm != BNN_ARM_AUTO && arm != BNN_ARM_VALU_XOR && arm != BNN_ARM_MFMA) return BNN_EINVAL;
+    if (arm != BNN_ARM_AUTO && arm != BNN_ARM_VALU_XOR && arm != BNN_ARM_MFMA && arm != BNN_ARM_MFMA_I8) return BNN_EINVAL;
     const int rc = check_layer_args(Xp, Wp, M, K, N, act, word_bits, Y, true);
     if (rc != BNN_OK) return rc;
     return run_binx(Xp, Wp, scale, bias, M, K, N, act, word_bits, Y, arm, static_cast<hipStream_t>(stream));

@@ -37,7 +37,7 @@ def _close(got: np.ndarray, want: np.ndarray, what=""):
     assert err <= TOL * scale, f"{what}: max abs err {err:g} > {TOL:g} * {scale:g}"
 
 
-ARMS = ["valu", "mfma16", "mfma32", "mfma32wm2", "mfma32rot", "mfma32wm2rot"]
+ARMS = ["valu", "mfma16", "mfma32", "mfma32wm2", "mfma32rot", "mfma32wm2rot", "mfma_i8"]
 
 
 class _arm:
@@ -48,6 +48,8 @@ class _arm:
 
     def __enter__(self):
         b = self.bnn
+        if self.name == "mfma_i8":
+            return b.BNN_ARM_MFMA_I8
         if self.name != "valu":
             b.bnn_set_option(b.BNN_OPT_MFMA_SHAPE, 16 if self.name == "mfma16" else 32)
             b.bnn_set_option(b.BNN_OPT_MFMA32_WM, 2 if "wm2" in self.name else 4)
