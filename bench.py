@@ -63,6 +63,35 @@ def gemm_sweep(args, bnn, workloads, G, torch) -> int:
     return 0
 
 
+def all_configs(args, bnn, workloads, G, torch) -> int:
+    """bnn_forward on Configs 1-4 (Config 5 is --gemm-sweep): frames/s and binary (or add/sub) TOPS, one JSON line each."""
+    for kv in args.opt:
+        key, val = kv.split("=")
+        bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
+    for cid in (1, 2, 3, 4):
+        cfg = workloads.CONFIGS[cid]
+        Ws, bs = workloads.make_net_params(cfg)
+        model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
+        X = G.to_dev(workloads.make_frames(cfg))
+        out = torch.empty((cfg.M, model.N_out), dtype=torch.float32, device=G.DEV)
+        steps = 200 if cid == 1 else (10 if cid == 4 else 50)
+        for _ in range(3):
+            model.forward(X, out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            model.forward(X, out)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        print(json.dumps({"workload": cfg.name, "batch_frames": cfg.M, "ms_per_step": round(ms, 4),
+                          "frames_per_s": round(cfg.M / (ms * 1e-3), 1),
+                          "tops_all_layers": round(2.0 * cfg.macs_per_frame() * cfg.M / (ms * 1e-3) / 1e12, 2),
+                          "binbin_share_of_macs": round(cfg.binbin_macs_per_frame() / cfg.macs_per_frame(), 3)}), flush=True)
+        del model, X, out, Ws, bs
+        torch.cuda.empty_cache()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +102,8 @@ def main() -> int:
                     help="arm of the binary product: 4-bit-float MFMA (default), int8 MFMA, or XOR/popcount on the vector ALU")
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
     ap.add_argument("--copy-calibration", action="store_true", help="run 10 plain 256 MiB device copies (counter calibration)")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="time bnn_forward on Configs 1-4 instead (one JSON line each; the default run is Config 3 only)")
     ap.add_argument("--gemm-sweep", action="store_true", help="time the isolated binary GEMM sweep (Config 5) instead")
     ap.add_argument("--opt", action="append", default=[], help="kernel option as KEY=VALUE with KEY a BNN_OPT_* name, e.g. MFMA_LDS=0")
     args = ap.parse_args()
@@ -91,6 +122,8 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.gemm_sweep:
         return gemm_sweep(args, bnn, workloads, G, torch)
+    if args.all_configs:
+        return all_configs(args, bnn, workloads, G, torch)
     if args.copy_calibration:
         # A plain device-to-device copy of known size: the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by.
         nbytes = 256 << 20

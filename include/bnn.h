@@ -81,6 +81,12 @@ typedef enum bnn_option {
                                    (128 x 64 wave tiles), 0 = by batch size (32 from 1024 frames; default)       */
     BNN_OPT_MFMA32_WM = 8,       /* 32-row accumulator fragments per wavefront of the 32x32x64 kernel: 2, 4, or 0 =
                                    by grid size (default)                                                        */
+    BNN_OPT_REALX_F32_MFMA = 10, /* real-input layers with fp32 outputs (LINEAR, HARDTANH, LOGSOFTMAX) of 128 frames or
+                                   more: 0 = vector-ALU kernel (default; sum in ascending k, bit-identical to the
+                                   reference definition), 1 = fp32 matrix-core kernel, about 3x faster; its sums are
+                                   taken in the matrix core's order and differ by fp32 rounding (1e-6 of the layer's
+                                   output scale).  A deep hard-tanh network amplifies such differences from layer to
+                                   layer (measured: 8e-4 of the output scale after 7 layers of 2048 units)          */
     BNN_OPT_MFMA32_PIPELINE = 9  /* operand fetch of the 32x32x64 kernel on 16-byte aligned rows with K % 512 == 0:
                                    0 or 1 = two register sets, the fetch of the next piece of K pinned ahead of
                                    the products of the current one (default), 2 = one set, order left to the

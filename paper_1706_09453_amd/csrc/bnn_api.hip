@@ -9,6 +9,7 @@
 #include "../../include/bnn.h"
 #include "mfma32_kernels.hpp"
 #include "mfma_i8_kernels.hpp"
+#include "realx_mfma_kernels.hpp"
 #include "mfma_kernels.hpp"
 #include "pack_kernels.hpp"
 #include "realx_fused_kernel.hpp"
@@ -31,6 +32,7 @@ std::atomic<int> g_fused_softmax{0};
 std::atomic<int> g_mfma_shape{0};
 std::atomic<int> g_mfma32_wm{0};
 std::atomic<int> g_mfma32_pipeline{0};
+std::atomic<int> g_realx_f32_mfma{0};
 
 inline bool word_bits_ok(int wb) { return wb == 32 || wb == 64; }
 inline int64_t words_per_row(int64_t K, int wb) { return (K + wb - 1) / wb; }
@@ -102,6 +104,21 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
     if (M == 0) return BNN_OK;
     const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
     const uint32_t* W = static_cast<const uint32_t*>(Wp);
+    if (act != BNN_ACT_SIGN && M >= 128 && g_realx_f32_mfma.load()) {
+        // fp32 outputs of a large batch: the matrix cores (fp32 MFMA, weights as +-1.0f); Sign bits never come here
+        const dim3 grid((unsigned)((M + 255) / 256), (unsigned)((N + 127) / 128)), block(256);
+        const bool vec = (K % 16 == 0) && aligned(X, 16);
+        float* Yf = static_cast<float*>(Y);
+        if (act == BNN_ACT_HARDTANH) {
+            if (vec) realx_f32_mfma_kernel<ACT_HARDTANH, true><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+            else realx_f32_mfma_kernel<ACT_HARDTANH, false><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+        } else {
+            if (vec) realx_f32_mfma_kernel<ACT_LINEAR, true><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+            else realx_f32_mfma_kernel<ACT_LINEAR, false><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+        }
+        if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(Yf, (int)M, (int)N, st);
+        return launch_status();
+    }
     switch (g_realx_tm.load()) {
         case 8: launch_realx_tm<8>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
         case 32: launch_realx_tm<32>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
@@ -404,6 +421,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_MFMA32_WM:
             if (value != 0 && value != 2 && value != 4) return BNN_EINVAL;
             g_mfma32_wm.store(value);
+            return BNN_OK;
+        case BNN_OPT_REALX_F32_MFMA:
+            if (value != 0 && value != 1) return BNN_EINVAL;
+            g_realx_f32_mfma.store(value);
             return BNN_OK;
         case BNN_OPT_MFMA32_PIPELINE:
             if (value < 0 || value > 2) return BNN_EINVAL;

@@ -172,6 +172,7 @@ def test_binx_null_scale_bias(G, bnn, oracle):
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (64, 440, 512), (130, 440, 200),
                                    (37, 2048, 300), (50, 100, 3307)])
 def test_realx_layer(G, bnn, oracle, M, K, N, act, wb, tm):
+    """The vector-ALU kernel adds in ascending k, as the oracle's fp32 sum does: fp32 outputs are identical bits."""
     bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, tm)
     try:
         X, W, scale, bias = _rand_layer(M * 3 + K + N, M, K, N)
@@ -190,6 +191,39 @@ def test_realx_layer(G, bnn, oracle, M, K, N, act, wb, tm):
             assert np.array_equal(got, want), "same order of fp32 additions on both sides: identical bits"
     finally:
         bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, 16)
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("act", ["linear", "hardtanh", "logsoftmax", "sign"])
+@pytest.mark.parametrize("M,K,N", [(128, 16, 1), (130, 440, 200), (300, 33, 65), (257, 100, 3307), (256, 2048, 384),
+                                   (1000, 2048, 2048), (513, 1023, 129)])
+def test_realx_layer_matrix_cores(G, bnn, oracle, M, K, N, act, wb):
+    """BNN_OPT_REALX_F32_MFMA = 1, 128 frames or more: fp32 outputs come from the fp32 matrix-core kernel, whose order
+    of additions is its own: within the tolerance of the oracle's fp32 sum and of its fp64 shadow.  Sign outputs stay
+    bit-exact (other kernel)."""
+    X, W, scale, bias = _rand_layer(M * 5 + K + N, M, K, N)
+    if act == "hardtanh":
+        scale = scale / np.float32(np.sqrt(K))
+    Wp = oracle.pack_sign(W, wb)
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 1)
+    try:
+        Y = G.layer_realx(G.to_dev(X), G.to_dev(Wp), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb)
+        torch.cuda.synchronize()
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
+    want = oracle.layer_binw_realx(X, Wp, K, scale, bias, act, wb)
+    if act == "sign":
+        assert np.array_equal(G.words_to_host(Y, wb), want)
+        return
+    got = Y.cpu().numpy()
+    _close(got, want, act)
+    if act != "logsoftmax":
+        _, acc64 = oracle.realx_acc(X, oracle.unpack_pm1(Wp, K, wb))
+        z64 = oracle.affine_f64(acc64, scale, bias)
+        _close(got, np.clip(z64, -1.0, 1.0) if act == "hardtanh" else z64, act + " fp64 shadow")
+        # much closer than the tolerance: a few units in the last place of the largest partial sum
+        assert float(np.max(np.abs(got.astype(np.float64) - z64 if act == "linear" else 0.0))) <= \
+            2e-6 * float(np.max(np.abs(z64))) + 1e-30
 
 
 def test_realx_against_fp64_shadow(G, bnn, oracle):
@@ -353,6 +387,31 @@ def test_forward_config2_full_batch_sampled_frames(G, bnn, oracle):
     frames = np.unique(np.concatenate([np.arange(0, 8), np.arange(cfg.M - 8, cfg.M),
                                        np.random.default_rng(1).integers(0, cfg.M, 16)]))
     _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
+
+
+def test_forward_config2_matrix_cores_layer_by_layer(G, bnn, oracle):
+    """Config 2 at full batch with the fp32 matrix-core kernel in every layer.  Seven hard-tanh layers amplify fp32
+    rounding differences (a different order of additions) beyond the end-to-end tolerance, so each layer is checked on
+    its own: the oracle's layer, fed with the GPU's own previous activations, against the GPU's layer."""
+    cfg = workloads.CONFIGS[2]
+    Ws, bs = workloads.make_net_params(cfg)
+    X = workloads.make_frames(cfg)
+    layers = oracle.make_layers(Ws, bs, cfg.hidden_act, cfg.word_bits)
+    idx = np.unique(np.concatenate([np.arange(0, 8), np.arange(cfg.M - 8, cfg.M),
+                                    np.random.default_rng(3).integers(0, cfg.M, 48)]))
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 1)
+    try:
+        h = G.to_dev(X)
+        for l, ly in enumerate(layers):
+            Y = G.layer_realx(h, G.to_dev(ly.w_words), G.to_dev(ly.scale), G.to_dev(ly.bias), ly.K, ly.N,
+                              bnn.ACT_BY_NAME[ly.act], cfg.word_bits)
+            torch.cuda.synchronize()
+            h_in = h[torch.from_numpy(idx).to(G.DEV)].cpu().numpy()
+            want = oracle.layer_binw_realx(h_in, ly.w_words, ly.K, ly.scale, ly.bias, ly.act, cfg.word_bits)
+            _close(Y[torch.from_numpy(idx).to(G.DEV)].cpu().numpy(), want, f"layer {l + 1}")
+            h = Y
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
 
 
 def test_forward_config4_full_batch_sampled_frames(G, bnn, oracle):
