@@ -11,7 +11,7 @@
 // K advances in super-steps of 512 bits: lane (r = lane%32, g = lane/32) fetches 32 contiguous bytes (words
 // 8g..8g+7 of the super-step) of row r of every fragment in two 16-byte loads; word j feeds MFMA step j.
 // Inside a fragment the order of k is therefore permuted, identically for both operands.  The next
-// super-step is fetched while the current one is expanded and multiplied.
+// piece of K is fetched while the current one is expanded and multiplied.
 // A workgroup is 2 x 2 waves: a (64 WM) x (64 WN) tile; at M = 4096, N = 2048 with WM = 4, WN = 2 that is
 // 256 workgroups, one wave per SIMD of the chip.
 #pragma once
@@ -78,10 +78,11 @@ __device__ __forceinline__ uint32_t word_of(const Raw8& v, int j) {
     return j < 4 ? word_of(v.lo, j) : word_of(v.hi, j - 4);
 }
 
-// PINGPONG: two operand register sets used in turn with the issue order pinned by scheduling barriers (fetch the
-// next super-step | multiply the current one).  The rotating form (current = next) lets the compiler merge the
-// two sets, which serialises fetch and multiply: fine for short K where two resident workgroups per CU cover each
-// other's stalls, 15-20 % slower from K = 4096 on (measured).
+// PINGPONG (aligned rows only): the operand fetch runs ahead of the products in separate register sets, with the
+// issue order pinned by scheduling barriers: two whole super-steps for 64-row wave tiles (WM = 2), three half
+// super-steps in rotation for 128-row tiles (WM = 4), whose half-steps are also written out instruction slot by
+// slot.  Without it (current = next, order left to the compiler) the two sets get merged and every super-step
+// waits for its own loads; kept for ragged rows and for comparison.
 // Grid: x = ceil(M / (64*WM)), y = ceil(N / (64*WN)); block = 256 threads.
 template <int WM, int WN, int ACT, bool ALIGNED, bool PINGPONG = false>
 __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
