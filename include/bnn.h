@@ -81,6 +81,8 @@ typedef enum bnn_option {
                                    (128 x 64 wave tiles), 0 = by batch size (32 from 1024 frames; default)       */
     BNN_OPT_MFMA32_WM = 8,       /* 32-row accumulator fragments per wavefront of the 32x32x64 kernel: 2, 4, or 0 =
                                    by grid size (default)                                                        */
+    BNN_OPT_MFMA32_XCD_ORDER = 11, /* 32x32x64 kernel: 1 = tiles that share rows of frames run on the same XCD (one L2),
+                                   2 = tiles in dispatch order, 0 = by problem size (default)                     */
     BNN_OPT_REALX_F32_MFMA = 10, /* real-input layers with fp32 outputs (LINEAR, HARDTANH, LOGSOFTMAX) of 128 frames or
                                    more: 0 = vector-ALU kernel (default; sum in ascending k, bit-identical to the
                                    reference definition), 1 = fp32 matrix-core kernel, about 3x faster; its sums are

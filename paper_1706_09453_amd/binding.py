@@ -22,6 +22,7 @@ BNN_OPT_BINX_ARM, BNN_OPT_REALX_TM, BNN_OPT_BINX_VALU_TM, BNN_OPT_MFMA_WM = 1, 2
 BNN_OPT_REALX_SIGN_MFMA, BNN_OPT_FUSED_LOGSOFTMAX, BNN_OPT_MFMA_SHAPE, BNN_OPT_MFMA32_WM = 5, 6, 7, 8
 BNN_OPT_MFMA32_PIPELINE = 9
 BNN_OPT_REALX_F32_MFMA = 10
+BNN_OPT_MFMA32_XCD_ORDER = 11
 
 ACT_BY_NAME = {"raw": BNN_ACT_RAW_I32, "linear": BNN_ACT_LINEAR, "hardtanh": BNN_ACT_HARDTANH,
                "sign": BNN_ACT_SIGN, "logsoftmax": BNN_ACT_LOGSOFTMAX}

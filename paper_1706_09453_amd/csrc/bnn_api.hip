@@ -33,6 +33,7 @@ std::atomic<int> g_mfma_shape{0};
 std::atomic<int> g_mfma32_wm{0};
 std::atomic<int> g_mfma32_pipeline{0};
 std::atomic<int> g_realx_f32_mfma{0};
+std::atomic<int> g_mfma32_xcd_order{0};
 
 inline bool word_bits_ok(int wb) { return wb == 32 || wb == 64; }
 inline int64_t words_per_row(int64_t K, int wb) { return (K + wb - 1) / wb; }
@@ -173,23 +174,29 @@ template <int WM, bool AL, bool PP = false>
 void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
                         int w32, int act, void* Y, int yw32, hipStream_t st) {
     constexpr int WN = 2;
+    // XCD-aware tile order pays when the default order thrashes the per-XCD L2s (a frames operand of more than
+    // 8 x 4 MiB) or scatters a large packed output with long rows over many passes; it costs 5-15 % on mid-size
+    // problems (measured on MI355X), so it is chosen by size unless forced.
+    const int xsel = g_mfma32_xcd_order.load();
+    const int xo = xsel == 1 || (xsel == 0 && ((size_t)M * w32 * 4 > ((size_t)32 << 20) ||
+                                              (N >= 4096 && (size_t)M * N / 8 >= ((size_t)32 << 20))));
     const unsigned int ab = (unsigned int)((size_t)M * w32 * 4), bb = (unsigned int)((size_t)N * w32 * 4);   // used by the PP variants only
     const dim3 grid((M + 64 * WM - 1) / (64 * WM), (N + 64 * WN - 1) / (64 * WN)), block(256);
     switch (act) {
         case ACT_DOT_I16:
-            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
+            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
         case BNN_ACT_RAW_I32:
-            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
+            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
         case BNN_ACT_SIGN:
-            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
+            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
         case BNN_ACT_HARDTANH:
-            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
+            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
         default:
-            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb);
+            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
     }
 }
@@ -421,6 +428,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_MFMA32_WM:
             if (value != 0 && value != 2 && value != 4) return BNN_EINVAL;
             g_mfma32_wm.store(value);
+            return BNN_OK;
+        case BNN_OPT_MFMA32_XCD_ORDER:
+            if (value < 0 || value > 2) return BNN_EINVAL;
+            g_mfma32_xcd_order.store(value);
             return BNN_OK;
         case BNN_OPT_REALX_F32_MFMA:
             if (value != 0 && value != 1) return BNN_EINVAL;

@@ -88,13 +88,25 @@ template <int WM, int WN, int ACT, bool ALIGNED, bool PINGPONG = false>
 __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
                                                           const float* __restrict__ scale, const float* __restrict__ bias,
                                                           int M, int K, int N, int w32, void* __restrict__ Y, int yw32,
-                                                          unsigned int a_bytes, unsigned int b_bytes) {
+                                                          unsigned int a_bytes, unsigned int b_bytes, int xcd_order) {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     const int r = lane & 31;   // row of the operand fragment / column of the accumulator fragment
     const int g = lane >> 5;   // k-group of the operand fragment / row-group of the accumulator fragment
-    const int m_base = ((int)blockIdx.x * 2 + (wave >> 1)) * (WM * 32);
-    const int n_base = ((int)blockIdx.y * 2 + (wave & 1)) * (WN * 32);
+    int tile_m = (int)blockIdx.x, tile_n = (int)blockIdx.y;
+    if (xcd_order) {
+        // Workgroups go to the 8 XCDs round-robin in dispatch order, and every XCD has its own L2.  Give XCD x a
+        // contiguous run of tiles in (frames tile, outputs tile) order, outputs fastest: the workgroups that share
+        // a frames tile then run on the same XCD, one after the other, and its rows are fetched into one L2 once.
+        const int total = (int)(gridDim.x * gridDim.y);
+        const int lin = (int)(blockIdx.y * gridDim.x + blockIdx.x);
+        const int x = lin & 7, q = total >> 3, rem = total & 7;
+        const int t = x * q + (x < rem ? x : rem) + (lin >> 3);
+        tile_m = t / (int)gridDim.y;
+        tile_n = t - tile_m * (int)gridDim.y;
+    }
+    const int m_base = (tile_m * 2 + (wave >> 1)) * (WM * 32);
+    const int n_base = (tile_n * 2 + (wave & 1)) * (WN * 32);
     if (m_base >= M || n_base >= N) return;   // wave-uniform
 
     const uint32_t* arow[WM];

@@ -37,7 +37,7 @@ def _close(got: np.ndarray, want: np.ndarray, what=""):
     assert err <= TOL * scale, f"{what}: max abs err {err:g} > {TOL:g} * {scale:g}"
 
 
-ARMS = ["valu", "mfma16", "mfma32", "mfma32wm2", "mfma32rot", "mfma32wm2rot", "mfma_i8"]
+ARMS = ["valu", "mfma16", "mfma32", "mfma32wm2", "mfma32rot", "mfma32wm2rot", "mfma32xcd", "mfma_i8"]
 
 
 class _arm:
@@ -54,12 +54,14 @@ class _arm:
             b.bnn_set_option(b.BNN_OPT_MFMA_SHAPE, 16 if self.name == "mfma16" else 32)
             b.bnn_set_option(b.BNN_OPT_MFMA32_WM, 2 if "wm2" in self.name else 4)
             b.bnn_set_option(b.BNN_OPT_MFMA32_PIPELINE, 2 if self.name.endswith("rot") else 0)
+            b.bnn_set_option(b.BNN_OPT_MFMA32_XCD_ORDER, 1 if self.name.endswith("xcd") else 0)
         return b.BNN_ARM_VALU_XOR if self.name == "valu" else b.BNN_ARM_MFMA
 
     def __exit__(self, *exc):
         self.bnn.bnn_set_option(self.bnn.BNN_OPT_MFMA_SHAPE, 0)
         self.bnn.bnn_set_option(self.bnn.BNN_OPT_MFMA32_WM, 0)
         self.bnn.bnn_set_option(self.bnn.BNN_OPT_MFMA32_PIPELINE, 0)
+        self.bnn.bnn_set_option(self.bnn.BNN_OPT_MFMA32_XCD_ORDER, 0)
         return False
 
 
