@@ -64,11 +64,11 @@ def gemm_sweep(args, bnn, workloads, G, torch) -> int:
 
 
 def all_configs(args, bnn, workloads, G, torch) -> int:
-    """bnn_forward on Configs 1-4 (Config 5 is --gemm-sweep): frames/s and binary (or add/sub) TOPS, one JSON line each."""
+    """bnn_forward on Configs 1-4 and the paper-shaped Configs 6-7 (Config 5 is --gemm-sweep): one JSON line each."""
     for kv in args.opt:
         key, val = kv.split("=")
         bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
-    for cid in (1, 2, 3, 4):
+    for cid in (1, 2, 3, 4, 6, 7):
         cfg = workloads.CONFIGS[cid]
         Ws, bs = workloads.make_net_params(cfg)
         model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)

@@ -360,7 +360,7 @@ def test_forward_config1_layer_by_layer_bits(G, bnn, oracle):
         h = Y
 
 
-@pytest.mark.parametrize("cfg_id,M", [(2, 96), (3, 300), (4, 200)])
+@pytest.mark.parametrize("cfg_id,M", [(2, 96), (3, 300), (4, 200), (6, 1100), (7, 1030)])
 def test_forward_configs_reduced_batch_full_compare(G, bnn, oracle, cfg_id, M):
     cfg = workloads.CONFIGS[cfg_id]
     _net_parity(G, bnn, oracle, cfg, M)

@@ -113,6 +113,12 @@ CONFIGS = {
                  (440,) + (2048,) * 6 + (3400,), 4096, "sign", 32),
     4: NetConfig(4, "C4 binW/binX 440-6x4096-4000 sign M=16384 w64",
                  (440,) + (4096,) * 6 + (4000,), 16384, "sign", 64),
+    # the paper's own two network shapes (Sec. 3): 6 x 1024 units with 3307 tied states, 6 x 2048 units with 3972;
+    # their output sizes are no multiple of 4, 32 or 128
+    6: NetConfig(6, "C6 binW/binX 440-6x1024-3307 sign M=4096 (WSJ-shaped)",
+                 (440,) + (1024,) * 6 + (3307,), 4096, "sign", 32),
+    7: NetConfig(7, "C7 binW/binX 440-6x2048-3972 sign M=4096 (AMI-shaped)",
+                 (440,) + (2048,) * 6 + (3972,), 4096, "sign", 32),
 }
 
 GEMM_SWEEP: List[GemmShape] = [GemmShape(M, K, N)
