@@ -127,6 +127,45 @@ ORC_API void orc_dot_xor(const void* a, const void* b, int64_t M, int64_t N, int
 }
 
 /*
+ * Activations binarised to (0, 1) instead of (-1, +1) (Sec. 2.1 remark; Sec. 3.2, Tables 3 and 4): the weights stay in
+ * {-1, +1}, the activation is h = 1 where the pre-activation is positive and 0 otherwise, so the stored bit is the
+ * same and only the product reads it differently: dot[m][n] = sum_k h[m][k] * w[n][k].  The plain definition.
+ */
+ORC_API void orc_dot_x01_wpm1(const int8_t* h01, const int8_t* wpm1, int64_t M, int64_t N, int64_t K, int32_t* dot) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int32_t s = 0;
+            for (int64_t k = 0; k < K; ++k) s += (int32_t)h01[m * K + k] * (int32_t)wpm1[n * K + k];
+            dot[m * N + n] = s;
+        }
+}
+
+/*
+ * The same product on packed rows: an element adds +1 where activation and weight bit are both 1 and -1 where the
+ * activation bit is 1 and the weight bit 0, so dot = popcount(h AND w) - popcount(h AND NOT w)
+ *                                                  = 2 popcount(h AND w) - popcount(h).  Zero pad bits add nothing.
+ */
+ORC_API void orc_dot_and(const void* h, const void* w, int64_t M, int64_t N, int64_t K, int word_bits, int32_t* dot) {
+    const int64_t Kw = orc_words_per_row(K, word_bits);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t both = 0, ones = 0;
+            if (word_bits == 32) {
+                const uint32_t* hr = (const uint32_t*)h + m * Kw;
+                const uint32_t* wr = (const uint32_t*)w + n * Kw;
+                for (int64_t i = 0; i < Kw; ++i) { both += __builtin_popcount(hr[i] & wr[i]); ones += __builtin_popcount(hr[i]); }
+            } else {
+                const uint64_t* hr = (const uint64_t*)h + m * Kw;
+                const uint64_t* wr = (const uint64_t*)w + n * Kw;
+                for (int64_t i = 0; i < Kw; ++i) { both += __builtin_popcountll(hr[i] & wr[i]); ones += __builtin_popcountll(hr[i]); }
+            }
+            dot[m * N + n] = (int32_t)(2 * both - ones);
+        }
+}
+
+/*
  * Alg. 1 forward, product term with real input: acc[m][n] = sum_k w^b[n][k] * x[m][k],
  * which is an add where w^b = +1 and a subtract where w^b = -1 (no multiplications).
  * acc32: fp32, k ascending, one accumulator, every add/sub rounded to nearest.

@@ -37,6 +37,8 @@ def _L():
             "orc_unpack_pm1": [c_void_p, c_int64, c_int64, c_int, c_void_p],
             "orc_dot_pm1": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p],
             "orc_dot_xor": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_void_p],
+            "orc_dot_x01_wpm1": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p],
+            "orc_dot_and": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_void_p],
             "orc_realx_acc": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p],
             "orc_affine_f32": [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p],
             "orc_affine_f64": [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p],
@@ -105,6 +107,33 @@ def dot_pm1(a_pm1: np.ndarray, b_pm1: np.ndarray) -> np.ndarray:
     out = np.empty((M, N), dtype=np.int32)
     _L().orc_dot_pm1(_p(a), _p(b), M, N, K, _p(out))
     return out
+
+
+def dot_x01_wpm1(h01: np.ndarray, w_pm1: np.ndarray) -> np.ndarray:
+    """Activations in {0, 1}, weights in {-1, +1} (Sec. 3.2, Tables 3-4), plain definition: [M,K] x [N,K] -> int32 [M,N]."""
+    h, w = _c(h01, np.int8), _c(w_pm1, np.int8)
+    M, K = h.shape
+    N = w.shape[0]
+    assert w.shape[1] == K
+    out = np.empty((M, N), dtype=np.int32)
+    _L().orc_dot_x01_wpm1(_p(h), _p(w), M, N, K, _p(out))
+    return out
+
+
+def dot_and(h_words: np.ndarray, w_words: np.ndarray, K: int, word_bits: int) -> np.ndarray:
+    """The same product on packed rows: 2*popcount(h AND w) - popcount(h)."""
+    dt = _word_dtype(word_bits)
+    h, w = _c(h_words, dt), _c(w_words, dt)
+    Kw = words_per_row(K, word_bits)
+    assert h.shape[1] == Kw and w.shape[1] == Kw
+    out = np.empty((h.shape[0], w.shape[0]), dtype=np.int32)
+    _L().orc_dot_and(_p(h), _p(w), h.shape[0], w.shape[0], K, word_bits, _p(out))
+    return out
+
+
+def unpack_01(words: np.ndarray, K: int, word_bits: int) -> np.ndarray:
+    """Packed rows -> [rows, K] int8 in {0, 1}: the stored bit itself."""
+    return ((unpack_pm1(words, K, word_bits).astype(np.int16) + 1) // 2).astype(np.int8)
 
 
 def dot_xor(a_words: np.ndarray, b_words: np.ndarray, K: int, word_bits: int) -> np.ndarray:
@@ -183,8 +212,8 @@ def _finish(hhat32: np.ndarray, act: str, word_bits: int):
         return hhat32
     if act == "hardtanh":
         return hardtanh(hhat32)
-    if act == "sign":                      # Alg. 2: h_l = Sign(h^_l), stored as bits along n
-        return pack_sign(hhat32, word_bits)
+    if act in ("sign", "step01"):          # Alg. 2: h_l = Sign(h^_l), stored as bits along n; the (0, 1) step (Sec. 3.2)
+        return pack_sign(hhat32, word_bits)  # stores the very same bit: 1 where h^_l > 0
     if act == "logsoftmax":                # Alg. 2: Softmax at l = L
         return log_softmax(hhat32)[0]
     raise ValueError(f"unknown activation {act!r}")
@@ -214,11 +243,30 @@ def layer_binw_binx(x_words: np.ndarray, w_words: np.ndarray, K: int, scale, bia
     return _finish(affine_f32(i32_to_f32(dot), scale, bias), act, word_bits)
 
 
+def layer_binw_binx01(h_words: np.ndarray, w_words: np.ndarray, K: int, scale, bias, act: str, word_bits: int,
+                      form: str = "definition"):
+    """One layer with binary weights in {-1,+1} and binary input read as {0,1} (Sec. 3.2).
+
+    form = "definition": unpack and take the plain integer product; form = "and" (or "xor", so that
+    forward(form="xor") runs every binary layer on packed words): 2*popcount(AND) - popcount on the packed words
+    (same values, pinned by tests).
+    """
+    if form == "definition":
+        dot = dot_x01_wpm1(unpack_01(h_words, K, word_bits), unpack_pm1(w_words, K, word_bits))
+    elif form in ("and", "xor"):
+        dot = dot_and(h_words, w_words, K, word_bits)
+    else:
+        raise ValueError(form)
+    if act == "raw":
+        return dot
+    return _finish(affine_f32(i32_to_f32(dot), scale, bias), act, word_bits)
+
+
 @dataclass
 class OracleLayer:
     K: int
     N: int
-    act: str                    # "sign" | "hardtanh" | "linear" | "logsoftmax"
+    act: str                    # "sign" | "step01" | "hardtanh" | "linear" | "logsoftmax"
     word_bits: int
     w_words: np.ndarray         # [N, ceil(K/wb)]
     scale: Optional[np.ndarray]  # [N] fp32 or None
@@ -241,17 +289,21 @@ def make_layers(Ws: Sequence[np.ndarray], biases: Sequence[np.ndarray], hidden_a
 def forward(layers: Sequence[OracleLayer], x: np.ndarray, form: str = "definition", keep: bool = False):
     """Whole forward pass (Alg. 2 forward with Alg. 1's binary weights): returns log-posteriors [M, N_L].
 
-    The input of a layer is binary exactly when the previous layer's activation was Sign.
+    The input of a layer is binary exactly when the previous layer's activation was Sign (read as -1/+1) or the (0, 1)
+    step (act "step01": the same stored bits, read as 0/1 by the next layer).
     With keep=True also returns the list of every layer's output.
     """
     h = np.ascontiguousarray(x, dtype=np.float32)
-    binary = False
+    domain = "real"
     outs = []
     for ly in layers:
-        if binary:
-            h = layer_binw_binx(h, ly.w_words, ly.K, ly.scale, ly.bias, ly.act, ly.word_bits, form=form)
+        act = ly.act
+        if domain == "pm1":
+            h = layer_binw_binx(h, ly.w_words, ly.K, ly.scale, ly.bias, act, ly.word_bits, form=form)
+        elif domain == "01":
+            h = layer_binw_binx01(h, ly.w_words, ly.K, ly.scale, ly.bias, act, ly.word_bits, form=form)
         else:
-            h = layer_binw_realx(h, ly.w_words, ly.K, ly.scale, ly.bias, ly.act, ly.word_bits)
-        binary = ly.act == "sign"
+            h = layer_binw_realx(h, ly.w_words, ly.K, ly.scale, ly.bias, act, ly.word_bits)
+        domain = {"sign": "pm1", "step01": "01"}.get(ly.act, "real")
         outs.append(h)
     return (h, outs) if keep else h

@@ -299,6 +299,73 @@ def test_log_softmax_vs_scipy_and_invariants(oracle):
     assert np.allclose(oracle.log_softmax(big)[1][0], [0.0, -1e4, -2e4])
 
 
+# ----------------------------------------------------------------------------- (0, 1) activations (Sec. 3.2)
+
+def test_x01_hand_cases(oracle):
+    with open(os.path.join(GOLD, "x01_hand_cases.txt")) as f:
+        rows = [ln.split("|") for ln in f if ln.strip() and not ln.startswith("#")]
+    for hs, ws, ds in rows:
+        h = np.array([[int(v) for v in hs.split()]], np.int8)
+        w = np.array([[int(v) for v in ws.split()]], np.int8)
+        want = int(ds)
+        assert oracle.dot_x01_wpm1(h, w)[0, 0] == want
+        K = h.shape[1]
+        for wb in (32, 64):
+            hp = oracle.pack_sign(h.astype(np.float32), wb)           # bit 1 <=> h = 1 (h > 0)
+            wp = oracle.pack_sign(w.astype(np.float32), wb)
+            assert oracle.unpack_01(hp, K, wb).tolist() == h.tolist()
+            assert oracle.dot_and(hp, wp, K, wb)[0, 0] == want
+
+
+@pytest.mark.parametrize("K", [1, 31, 32, 33, 63, 64, 65, 440, 2048])
+def test_x01_vs_numpy_and_packed_form(oracle, K):
+    rng = np.random.default_rng(K)
+    M, N = 7, 9
+    h = rng.integers(0, 2, (M, K)).astype(np.int8)
+    w = (2 * rng.integers(0, 2, (N, K)) - 1).astype(np.int8)
+    want = h.astype(np.int64) @ w.astype(np.int64).T                   # library integer matmul
+    assert np.array_equal(oracle.dot_x01_wpm1(h, w), want)
+    # not transposed: a non-square case with distinct rows
+    assert oracle.dot_x01_wpm1(h[:2], w[:5]).shape == (2, 5)
+    for wb in (32, 64):
+        hp, wp = oracle.pack_sign(h.astype(np.float32), wb), oracle.pack_sign(w.astype(np.float32), wb)
+        assert np.array_equal(oracle.dot_and(hp, wp, K, wb), want)
+        # relation to the -1/+1 product of the same bits: h = (a + 1) / 2  =>  h.w = (a.w + sum_k w_k) / 2
+        a_dot = oracle.dot_xor(hp, wp, K, wb).astype(np.int64)
+        assert np.array_equal(2 * want, a_dot + w.astype(np.int64).sum(1)[None, :])
+    # closed forms: no active input -> 0; every input active -> the row sum of the weights; all weights +1 -> popcount(h)
+    assert np.array_equal(oracle.dot_x01_wpm1(np.zeros((1, K), np.int8), w), np.zeros((1, N)))
+    assert np.array_equal(oracle.dot_x01_wpm1(np.ones((1, K), np.int8), w)[0], w.astype(np.int64).sum(1))
+    assert np.array_equal(oracle.dot_x01_wpm1(h, np.ones((1, K), np.int8))[:, 0], h.astype(np.int64).sum(1))
+    # unlike the -1/+1 product it is NOT odd in the activations: complementing h gives (sum_k w_k) - dot
+    assert np.array_equal(oracle.dot_x01_wpm1(1 - h, w), w.astype(np.int64).sum(1)[None, :] - want)
+
+
+def test_x01_network_vs_independent_numpy(oracle):
+    """A small network with (0, 1) hidden activations: the oracle's forward against plain numpy on unpacked values."""
+    rng = np.random.default_rng(5)
+    dims = (13, 40, 33, 17)
+    Ws = [rng.uniform(-1, 1, (dims[i + 1], dims[i])).astype(np.float32) for i in range(3)]
+    bs = [(0.1 * rng.standard_normal(dims[i + 1])).astype(np.float32) for i in range(3)]
+    X = rng.standard_normal((6, 13)).astype(np.float32)
+    for wb in (32, 64):
+        layers = oracle.make_layers(Ws, bs, "step01", wb)
+        out_def, keep = oracle.forward(layers, X, form="definition", keep=True)
+        out_pk = oracle.forward(layers, X, form="xor")
+        assert np.array_equal(out_def, out_pk)
+        # plain numpy: layer 1 real input (ascending-k fp32 sum via cumsum), then {0,1} activations against +-1 weights
+        S = [np.where(W > 0, 1.0, -1.0).astype(np.float32) for W in Ws]
+        sc = [np.float32(np.abs(W.astype(np.float64)).mean()) for W in Ws]
+        acc = np.stack([[np.cumsum((S[0][n] * x).astype(np.float32), dtype=np.float32)[-1] for n in range(dims[1])] for x in X])
+        h = (np.float32(sc[0]) * acc.astype(np.float32) + bs[0] > 0)
+        assert np.array_equal(oracle.unpack_01(keep[0], dims[1], wb), h.astype(np.int8))
+        d2 = h.astype(np.int64) @ S[1].astype(np.int64).T
+        z2 = (sc[1].astype(np.float64) * d2 + bs[1].astype(np.float64))
+        h2 = z2 > 0
+        clear = np.abs(z2) > 1e-4                                         # away from fp32 rounding of the affine step
+        assert np.array_equal(oracle.unpack_01(keep[1], dims[2], wb)[clear], h2.astype(np.int8)[clear])
+
+
 # ----------------------------------------------------------------------------- layers and network
 
 def _load_hand():
