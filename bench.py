@@ -68,7 +68,7 @@ def all_configs(args, bnn, workloads, G, torch) -> int:
     for kv in args.opt:
         key, val = kv.split("=")
         bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
-    for cid in (1, 2, 3, 4, 6, 7):
+    for cid in (1, 2, 3, 4, 6, 7, 8):
         cfg = workloads.CONFIGS[cid]
         Ws, bs = workloads.make_net_params(cfg)
         model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)

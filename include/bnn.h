@@ -101,7 +101,8 @@ typedef struct bnn_layer_desc {
     int64_t N;            /* outputs                                                       */
     int32_t act;          /* bnn_act of this layer (not BNN_ACT_RAW_I32)                   */
     int32_t word_bits;    /* 32 or 64: packing of Wp, of a binary input and of a SIGN output */
-    int32_t x_is_binary;  /* 1: input is packed bits [M][Kw]; 0: input is fp32 [M][K]      */
+    int32_t x_is_binary;  /* 0: input is fp32 [M][K]; 1: packed bits [M][Kw] read as -1/+1;
+                             2: packed bits read as 0/1 (see bnn_layer_binw_binx01)            */
     int32_t reserved;     /* must be 0                                                      */
     const void* Wp;       /* packed weights [N][Kw]                                         */
     const float* scale;   /* [N] or NULL (= 1)                                              */
@@ -155,6 +156,16 @@ int bnn_layer_binw_realx(const float* X, const void* Wp, const float* scale, con
 int bnn_layer_binw_binx(const void* Xp, const void* Wp, const float* scale, const float* bias,
                         int64_t M, int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream);
 
+/*
+ * As bnn_layer_binw_binx, with the input bits read as 0/1 instead of -1/+1: the activations binarised to (0, 1) of
+ * Sec. 3.2 (Tables 3 and 4; the paper calls it the hard version of Sigmoid: 1 where the pre-activation is positive,
+ * so the producing layer stores the same bit as Sign and uses BNN_ACT_SIGN).  Weights stay in {-1, +1}:
+ * dot[m][n] = sum_k h[m][k] w[n][k] = 2 * popcount(Xp[m] AND Wp[n]) - popcount(Xp[m]), exact in int32.
+ * Arguments, outputs and errors as bnn_layer_binw_binx.
+ */
+int bnn_layer_binw_binx01(const void* Xp, const void* Wp, const float* scale, const float* bias,
+                          int64_t M, int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream);
+
 /* As bnn_layer_binw_binx, with the arithmetic unit chosen by the caller (bnn_binx_arm); same results. */
 int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, const float* bias,
                             int64_t M, int64_t K, int64_t N, int act, int word_bits, void* Y, int arm,
@@ -171,7 +182,8 @@ size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, i
  * Whole forward pass (Alg. 2 forward with Alg. 1's binary weights): layer 0 reads X, every layer reads the
  * previous layer's output, the last layer writes `out`.
  *   layers    HOST array of n_layers descriptors.  layers[0].x_is_binary says whether X is fp32 [M][K0] or
- *             packed bits; for l > 0, x_is_binary must equal (layers[l-1].act == BNN_ACT_SIGN),
+ *             packed bits; for l > 0, x_is_binary must be nonzero exactly when layers[l-1].act == BNN_ACT_SIGN
+ *             (1: the bits are read as -1/+1, 2: as 0/1),
  *             K must equal layers[l-1].N and word_bits must match across a binary link.
  *   X         input of layer 0
  *   out       output of the last layer: fp32 [M][N_last] (log-posteriors when its act is LOGSOFTMAX),

@@ -25,7 +25,7 @@ BNN_OPT_REALX_F32_MFMA = 10
 BNN_OPT_MFMA32_XCD_ORDER = 11
 
 ACT_BY_NAME = {"raw": BNN_ACT_RAW_I32, "linear": BNN_ACT_LINEAR, "hardtanh": BNN_ACT_HARDTANH,
-               "sign": BNN_ACT_SIGN, "logsoftmax": BNN_ACT_LOGSOFTMAX}
+               "sign": BNN_ACT_SIGN, "step01": BNN_ACT_SIGN, "logsoftmax": BNN_ACT_LOGSOFTMAX}
 
 
 class bnn_layer_desc(ctypes.Structure):
@@ -49,6 +49,8 @@ _SIGNATURES = {
                                      c_void_p, c_void_p]),
     "bnn_layer_binw_binx": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_int,
                                     c_void_p, c_void_p]),
+    "bnn_layer_binw_binx01": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_int,
+                                      c_void_p, c_void_p]),
     "bnn_layer_binw_binx_arm": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_int,
                                         c_void_p, c_int, c_void_p]),
     "bnn_forward_workspace_bytes": (c_size_t, [c_void_p, c_int, c_int64]),
@@ -104,6 +106,12 @@ def bnn_layer_binw_binx(Xp: int, Wp: int, scale: int, bias: int, M: int, K: int,
                         Y: int, stream: int = 0) -> int:
     return _check(_lib.bnn_layer_binw_binx(Xp, Wp, scale or None, bias or None, M, K, N, act, word_bits, Y,
                                            stream or None))
+
+
+def bnn_layer_binw_binx01(Xp: int, Wp: int, scale: int, bias: int, M: int, K: int, N: int, act: int, word_bits: int,
+                          Y: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_layer_binw_binx01(Xp, Wp, scale or None, bias or None, M, K, N, act, word_bits, Y,
+                                             stream or None))
 
 
 def bnn_layer_binw_binx_arm(Xp: int, Wp: int, scale: int, bias: int, M: int, K: int, N: int, act: int,

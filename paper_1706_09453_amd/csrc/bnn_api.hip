@@ -170,7 +170,7 @@ void launch_binx_mfma_wm(const uint32_t* Xp, const uint32_t* Wp, const float* sc
     }
 }
 
-template <int WM, bool AL, bool PP = false>
+template <int WM, bool AL, bool PP = false, bool X01 = false>
 void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
                         int w32, int act, void* Y, int yw32, hipStream_t st) {
     constexpr int WN = 2;
@@ -184,19 +184,19 @@ void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* sca
     const dim3 grid((M + 64 * WM - 1) / (64 * WM), (N + 64 * WN - 1) / (64 * WN)), block(256);
     switch (act) {
         case ACT_DOT_I16:
-            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
         case BNN_ACT_RAW_I32:
-            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
         case BNN_ACT_SIGN:
-            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
         case BNN_ACT_HARDTANH:
-            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
         default:
-            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
     }
 }
@@ -222,9 +222,10 @@ void launch_binx_mfma_i8(const uint32_t* Xp, const uint32_t* Wp, const float* sc
 }
 
 int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K, int64_t N,
-             int act, int wb, void* Y, int arm, hipStream_t st) {
+             int act, int wb, void* Y, int arm, hipStream_t st, bool x01 = false) {
     if (M == 0) return BNN_OK;
     if (arm == BNN_ARM_AUTO) arm = g_default_arm.load();
+    if (x01) arm = BNN_ARM_MFMA;   // the 0/1 reading of the input bits exists on the 32x32x64 kernel only
     const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
     const uint32_t* A = static_cast<const uint32_t*>(Xp);
     const uint32_t* B = static_cast<const uint32_t*>(Wp);
@@ -244,7 +245,7 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
     } else if (arm == BNN_ARM_MFMA_I8) {
         if (rows16 && K % 512 == 0) launch_binx_mfma_i8<true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         else launch_binx_mfma_i8<false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
-    } else if (act == BNN_ACT_LOGSOFTMAX && g_fused_softmax.load() && rows16 &&
+    } else if (!x01 && act == BNN_ACT_LOGSOFTMAX && g_fused_softmax.load() && rows16 &&
                ((K % 512 == 0 && N <= 16 * 8 * 16) || (K % 256 == 0 && N <= 16 * 8 * 32)) &&
                (size_t)(M + 16) * w32 * 4 < 0x7fffffffu && (size_t)(N + 512) * w32 * 4 < 0x7fffffffu) {
         // output layer: product, affine step and log-Softmax fused, one workgroup per 16 frames
@@ -261,7 +262,7 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
         else
             binx_mfma_logsoftmax_kernel<32, 2><<<grid, block, 0, st>>>(A, B, scale, bias, Mi, Ki, Ni, w32, Yf, ab, bb);
         return launch_status();
-    } else if (g_mfma_shape.load() == 32 || (g_mfma_shape.load() == 0 && M >= 1024)) {
+    } else if (x01 || g_mfma_shape.load() == 32 || (g_mfma_shape.load() == 0 && M >= 1024)) {
         // large batch: 32x32x64 MFMA, 128 x 64 (or 64 x 64) wave tiles
         const bool al = rows16 && (K % 512 == 0);
         // Output layer: the product goes to memory as int16 (half the bytes of fp32 pre-activations), and the row
@@ -277,7 +278,11 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
         const bool wm2 = wm32 == 2 || (wm32 == 0 && blocks4 < 200);
         // fetch pinned ahead of the products: faster on every shape measured; buffer addressing needs operands below 2 GiB
         const bool pinned = g_mfma32_pipeline.load() != 2 && (size_t)M * w32 * 4 < 0x7fffffffu && (size_t)N * w32 * 4 < 0x7fffffffu;
-        if (!al) {
+        if (x01) {
+            if (!al) launch_binx_mfma32<2, false, false, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else if (wm2 || !pinned) launch_binx_mfma32<2, true, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_mfma32<4, true, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        } else if (!al) {
             // ragged rows: bounds-checked word loads, 64-row wave tiles only
             launch_binx_mfma32<2, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         } else if (wm2) {
@@ -369,12 +374,12 @@ int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
         const bnn_layer_desc& d = L[l];
         if (!word_bits_ok(d.word_bits) || d.K <= 0 || d.N <= 0 || d.K > kMaxDim || d.N > kMaxDim) return BNN_ESHAPE;
         if (d.act < BNN_ACT_LINEAR || d.act > BNN_ACT_LOGSOFTMAX || d.reserved != 0) return BNN_EINVAL;
-        if (d.x_is_binary != 0 && d.x_is_binary != 1) return BNN_EINVAL;
+        if (d.x_is_binary < 0 || d.x_is_binary > 2) return BNN_EINVAL;
         if (!d.Wp) return BNN_EINVAL;
         if (l > 0) {
             const bnn_layer_desc& p = L[l - 1];
             if (d.K != p.N) return BNN_ESHAPE;
-            if (d.x_is_binary != (p.act == BNN_ACT_SIGN ? 1 : 0)) return BNN_ESHAPE;
+            if ((d.x_is_binary != 0) != (p.act == BNN_ACT_SIGN)) return BNN_ESHAPE;
             if (d.x_is_binary && d.word_bits != p.word_bits) return BNN_ESHAPE;
             if (p.act == BNN_ACT_LOGSOFTMAX) return BNN_ESHAPE;   // Softmax only closes a network (Alg. 2)
         }
@@ -495,6 +500,13 @@ BNN_EXPORT int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const flo
     return run_binx(Xp, Wp, scale, bias, M, K, N, act, word_bits, Y, arm, static_cast<hipStream_t>(stream));
 }
 
+BNN_EXPORT int bnn_layer_binw_binx01(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M,
+                                     int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream) {
+    const int rc = check_layer_args(Xp, Wp, M, K, N, act, word_bits, Y, true);
+    if (rc != BNN_OK) return rc;
+    return run_binx(Xp, Wp, scale, bias, M, K, N, act, word_bits, Y, BNN_ARM_MFMA, static_cast<hipStream_t>(stream), true);
+}
+
 BNN_EXPORT int bnn_layer_binw_binx(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M,
                                    int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream) {
     return bnn_layer_binw_binx_arm(Xp, Wp, scale, bias, M, K, N, act, word_bits, Y, BNN_ARM_AUTO, stream);
@@ -537,7 +549,7 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
                 rc = check_layer_args(in, d.Wp, M, d.K, d.N, d.act, d.word_bits, o, d.x_is_binary != 0);
             } else if (d.x_is_binary) {
                 rc = run_binx(in, d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o, BNN_ARM_AUTO,
-                              static_cast<hipStream_t>(stream));
+                              static_cast<hipStream_t>(stream), d.x_is_binary == 2);
             } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load()) {
                 rc = run_realx_sign_mfma(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
                                          o, static_cast<hipStream_t>(stream));

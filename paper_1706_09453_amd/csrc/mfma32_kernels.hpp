@@ -83,8 +83,12 @@ __device__ __forceinline__ uint32_t word_of(const Raw8& v, int j) {
 // super-steps in rotation for 128-row tiles (WM = 4), whose half-steps are also written out instruction slot by
 // slot.  Without it (current = next, order left to the compiler) the two sets get merged and every super-step
 // waits for its own loads; kept for ragged rows and for comparison.
+// X01: the activation bits are read as 0/1 instead of -1/+1 (paper Sec. 3.2).  With a the -1/+1 reading of the same
+// bits, h = (a + 1) / 2 and h.w = (a.w + sum_k w_k) / 2: the product runs unchanged, every lane counts the 1 bits of
+// the weight words it fetches anyway (the two lanes that share a row add theirs up), and the epilogue forms
+// 0.5 (a.w) + (popcount(w) - K/2), exact in fp32.
 // Grid: x = ceil(M / (64*WM)), y = ceil(N / (64*WN)); block = 256 threads.
-template <int WM, int WN, int ACT, bool ALIGNED, bool PINGPONG = false>
+template <int WM, int WN, int ACT, bool ALIGNED, bool PINGPONG = false, bool X01 = false>
 __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
                                                           const float* __restrict__ scale, const float* __restrict__ bias,
                                                           int M, int K, int N, int w32, void* __restrict__ Y, int yw32,
@@ -132,6 +136,17 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
         bi[f] = n < N ? (bias ? bias[n] : 0.0f) : 0.0f;
     }
 
+    int ones[WN];   // X01: 1 bits of this lane's share of the weight rows
+#pragma unroll
+    for (int f = 0; f < WN; ++f) ones[f] = 0;
+    auto count4 = [&](const uint4 (&b)[WN]) {
+        if constexpr (X01) {
+#pragma unroll
+            for (int f = 0; f < WN; ++f)
+                ones[f] += __builtin_popcount(b[f].x) + __builtin_popcount(b[f].y) + __builtin_popcount(b[f].z) + __builtin_popcount(b[f].w);
+        }
+    };
+
     v16f acc[WM][WN];
     if constexpr (!PINGPONG || WM >= 4) {   // (the 64-row pinned variant starts its accumulators with a zero addend instead)
 #pragma unroll
@@ -164,6 +179,7 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
         }
         // the first product into each accumulator takes a zero addend instead of a cleared register
         auto products = [&](const uint4 (&a)[WM], const uint4 (&b)[WN], bool first) {
+            count4(b);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 v8i bx[WN];
@@ -218,6 +234,7 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
 #pragma unroll
                 for (int f = 0; f < WN; ++f) clear_hi(bx[t][f]);
             auto half_step = [&](const uint4 (&a)[WM], const uint4 (&b)[WN], const uint4 (&an)[WM], const uint4 (&bn)[WN]) {
+                count4(b);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int pc = j & 1, pn = pc ^ 1;
@@ -319,6 +336,13 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
 #pragma unroll
             for (int f = 0; f < WN; ++f) bnext[f] = load_raw8<ALIGNED>(brow[f], Sn, g, w32);
 
+            if constexpr (X01) {
+                uint4 lo[WN], hi[WN];
+#pragma unroll
+                for (int f = 0; f < WN; ++f) { lo[f] = braw[f].lo; hi[f] = braw[f].hi; }
+                count4(lo);
+                count4(hi);
+            }
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 v8i bx[WN];
@@ -343,6 +367,17 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
     // ---- epilogue.  Accumulator fragment (fm, fn), register v of lane (r, g) is
     //      dot[m_base + 32 fm + 8 (v/4) + 4 g + v%4][n_base + 32 fn + r] + pad.
     const float pad = (float)(nS * 512 - K);
+    float half_wsum[WN];   // X01: popcount(w) - K/2 = (sum_k w_k) / 2 of this lane's columns
+#pragma unroll
+    for (int f = 0; f < WN; ++f) {
+        half_wsum[f] = 0.0f;
+        if constexpr (X01) half_wsum[f] = (float)(ones[f] + __shfl_xor(ones[f], 32, kWave)) - 0.5f * (float)K;
+    }
+    auto dot_of = [&](float a, int fn) -> float {
+        const float d = ALIGNED ? a : a - pad;   // whole super-steps: no pad
+        if constexpr (X01) return __builtin_fmaf(d, 0.5f, half_wsum[fn]);
+        else return d;
+    };
     if constexpr (ACT == ACT_SIGN) {
         uint32_t* Yw = (uint32_t*)Y;
 #pragma unroll
@@ -356,7 +391,7 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
                 int words = 0;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float dot = ALIGNED ? acc[fm][fn][v] : acc[fm][fn][v] - pad;   // whole super-steps: no pad
+                    const float dot = dot_of(acc[fm][fn][v], fn);
                     const unsigned long long b = __builtin_amdgcn_ballot_w64(sign_bit(affine(sc[fn], dot, bi[fn])));
                     write_lane_pair(words, (uint32_t)b, (uint32_t)(b >> 32), v, 32 + v);
                 }
@@ -382,7 +417,7 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
             for (int fn = 0; fn < WN; ++fn)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float dot = ALIGNED ? acc[fm][fn][v] : acc[fm][fn][v] - pad;
+                    const float dot = dot_of(acc[fm][fn][v], fn);
                     uint32_t bits;
                     if constexpr (ACT == ACT_RAW_I32 || ACT == ACT_DOT_I16) {
                         bits = (uint32_t)(int)dot;

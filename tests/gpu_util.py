@@ -74,6 +74,13 @@ def layer_binx(Xp, Wp, scale, bias, K, N, act, word_bits, arm=bnn.BNN_ARM_AUTO):
     return Y
 
 
+def layer_binx01(Xp, Wp, scale, bias, K, N, act, word_bits):
+    M = Xp.shape[0]
+    Y = out_tensor(M, N, act, word_bits)
+    bnn.bnn_layer_binw_binx01(ptr(Xp), ptr(Wp), ptr(scale), ptr(bias), M, K, N, act, word_bits, ptr(Y), stream())
+    return Y
+
+
 class GpuModel:
     """Packed model on the GPU, prepared with bnn_pack_weights from real-valued weights (Alg. 1: w^b = Sign(w))."""
 
@@ -82,7 +89,7 @@ class GpuModel:
         self.keep = []           # device tensors referenced by the descriptors
         self.scales = []
         descs = []
-        binary = x_is_binary
+        binary = int(x_is_binary)   # 0: real input, 1: bits read as -1/+1, 2: bits read as 0/1 ("step01" hidden layers)
         for l, (W, r) in enumerate(zip(Ws, biases)):
             N, K = W.shape
             Wd = to_dev(W.astype(np.float32))
@@ -94,7 +101,7 @@ class GpuModel:
             self.scales.append(sc)
             descs.append(dict(K=K, N=N, act=act, word_bits=word_bits, x_is_binary=binary,
                               Wp=ptr(Wp), scale=ptr(scale), bias=ptr(bias)))
-            binary = act == bnn.BNN_ACT_SIGN
+            binary = (2 if hidden_act == "step01" else 1) if act == bnn.BNN_ACT_SIGN else 0
             del Wd
         self.descs = descs
         self.layers = bnn.make_layer_array(descs)

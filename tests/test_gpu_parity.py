@@ -166,6 +166,30 @@ def test_binx_null_scale_bias(G, bnn, oracle):
         assert np.array_equal(G.words_to_host(Y, wb), oracle.layer_binw_binx(aw, bw, K, None, None, "sign", wb))
 
 
+# ----------------------------------------------------------------------------- activations read as 0/1 (Sec. 3.2)
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("act", ["raw", "sign", "linear", "hardtanh", "logsoftmax"])
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (130, 440, 200), (257, 512, 129),
+                                   (200, 2048, 1000), (96, 1024, 3307), (1100, 1024, 384), (4096, 2048, 256)])
+def test_binx01_layer(G, bnn, oracle, M, K, N, act, wb):
+    aw, bw = _bin_operands(oracle, 7 * M + K + N, M, K, N, wb)
+    _, _, scale, bias = _rand_layer(M + N, 1, 1, N)
+    if act == "hardtanh":
+        scale = scale / np.float32(np.sqrt(K))
+    Y = G.layer_binx01(G.to_dev(aw), G.to_dev(bw), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb)
+    want = oracle.layer_binw_binx01(aw, bw, K, scale, bias, act, wb, form="and")
+    if M * K * N <= 40_000_000:
+        assert np.array_equal(oracle.layer_binw_binx01(aw, bw, K, None, None, "raw", wb, form="definition"),
+                              oracle.layer_binw_binx01(aw, bw, K, None, None, "raw", wb, form="and"))
+    if act == "sign":
+        assert np.array_equal(G.words_to_host(Y, wb), want)
+    elif act == "logsoftmax":
+        _close(Y.cpu().numpy(), want, "logsoftmax")
+    else:
+        assert np.array_equal(Y.cpu().numpy(), want)     # exact integer, then one fma: identical bits
+
+
 # ----------------------------------------------------------------------------- real x binary
 
 @pytest.mark.parametrize("tm", [8, 16, 32])
@@ -360,7 +384,7 @@ def test_forward_config1_layer_by_layer_bits(G, bnn, oracle):
         h = Y
 
 
-@pytest.mark.parametrize("cfg_id,M", [(2, 96), (3, 300), (4, 200), (6, 1100), (7, 1030)])
+@pytest.mark.parametrize("cfg_id,M", [(2, 96), (3, 300), (4, 200), (6, 1100), (7, 1030), (8, 300), (8, 1280)])
 def test_forward_configs_reduced_batch_full_compare(G, bnn, oracle, cfg_id, M):
     cfg = workloads.CONFIGS[cfg_id]
     _net_parity(G, bnn, oracle, cfg, M)
@@ -414,6 +438,14 @@ def test_forward_config2_matrix_cores_layer_by_layer(G, bnn, oracle):
             h = Y
     finally:
         bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
+
+
+def test_forward_config8_full_batch_sampled_frames(G, bnn, oracle):
+    """(0, 1) hidden activations at the benchmark's size."""
+    cfg = workloads.CONFIGS[8]
+    frames = np.unique(np.concatenate([np.arange(0, 8), np.arange(cfg.M - 8, cfg.M),
+                                       np.random.default_rng(4).integers(0, cfg.M, 48)]))
+    _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
 
 
 def test_forward_config4_full_batch_sampled_frames(G, bnn, oracle):

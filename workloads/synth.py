@@ -70,8 +70,8 @@ def random_words(seed: int, tensor_id: int, rows: int, words_per_row: int, start
 class NetConfig:
     """One feedforward acoustic-model workload.
 
-    dims = [K0, hidden..., N_out]; hidden_act is "sign" (binary activations) or
-    "hardtanh" (real activations); the last layer always ends in log-softmax.
+    dims = [K0, hidden..., N_out]; hidden_act is "sign" (binary activations in {-1, +1}), "step01" (binary
+    activations in {0, 1}) or "hardtanh" (real activations); the last layer always ends in log-softmax.
     """
     cfg_id: int
     name: str
@@ -93,7 +93,7 @@ class NetConfig:
         return sum(self.dims[l] * self.dims[l + 1] for l in range(self.n_layers))
 
     def binbin_macs_per_frame(self) -> int:
-        if self.hidden_act != "sign":
+        if self.hidden_act not in ("sign", "step01"):
             return 0
         return sum(self.dims[l] * self.dims[l + 1] for l in range(1, self.n_layers))
 
@@ -119,6 +119,9 @@ CONFIGS = {
                  (440,) + (1024,) * 6 + (3307,), 4096, "sign", 32),
     7: NetConfig(7, "C7 binW/binX 440-6x2048-3972 sign M=4096 (AMI-shaped)",
                  (440,) + (2048,) * 6 + (3972,), 4096, "sign", 32),
+    # Config 3 with the hidden activations binarised to (0, 1) instead of (-1, +1) (Sec. 3.2, Tables 3 and 4)
+    8: NetConfig(8, "C8 binW/binX(0,1) 440-6x2048-3400 step01 M=4096",
+                 (440,) + (2048,) * 6 + (3400,), 4096, "step01", 32),
 }
 
 GEMM_SWEEP: List[GemmShape] = [GemmShape(M, K, N)
