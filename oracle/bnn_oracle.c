@@ -223,6 +223,15 @@ ORC_API void orc_hardtanh(const float* hhat, int64_t count, float* out) {
 }
 
 /*
+ * The real hidden nonlinearity of the paper's own networks (Sec. 3: Sigmoid hidden layers in the baselines and in the
+ * first and last hidden layer of the binary-activation systems, Table 2): sigma(v) = 1 / (1 + exp(-v)), evaluated in
+ * fp64 from the fp32 pre-activation and rounded to fp32.
+ */
+ORC_API void orc_sigmoid(const float* hhat, int64_t count, float* out) {
+    for (int64_t i = 0; i < count; ++i) out[i] = (float)(1.0 / (1.0 + exp(-(double)hhat[i])));
+}
+
+/*
  * Alg. 2, last layer: Softmax over the N outputs of each frame, returned as
  * log-posteriors: logp[n] = z[n] - max_j z[j] - log sum_j exp(z[j] - max_j z[j]).
  * Evaluated in fp64 from the fp32 pre-activations; result kept in fp64 and also rounded to fp32.

@@ -44,6 +44,7 @@ def _L():
             "orc_affine_f64": [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p],
             "orc_i32_to_f32": [c_void_p, c_int64, c_void_p],
             "orc_hardtanh": [c_void_p, c_int64, c_void_p],
+            "orc_sigmoid": [c_void_p, c_int64, c_void_p],
             "orc_log_softmax": [c_void_p, c_int64, c_int64, c_void_p, c_void_p],
         }.items():
             fn = getattr(lib, name)
@@ -194,6 +195,14 @@ def hardtanh(h: np.ndarray) -> np.ndarray:
     return out
 
 
+def sigmoid(h: np.ndarray) -> np.ndarray:
+    """Sigmoid of the paper's real hidden layers (Sec. 3), fp64 from the fp32 pre-activation, rounded to fp32."""
+    h = _c(h, np.float32)
+    out = np.empty_like(h)
+    _L().orc_sigmoid(_p(h), h.size, _p(out))
+    return out
+
+
 def log_softmax(z: np.ndarray):
     """Alg. 2 output layer as log-posteriors: returns (fp32 rounded, fp64)."""
     z = _c(z, np.float32)
@@ -212,6 +221,8 @@ def _finish(hhat32: np.ndarray, act: str, word_bits: int):
         return hhat32
     if act == "hardtanh":
         return hardtanh(hhat32)
+    if act == "sigmoid":
+        return sigmoid(hhat32)
     if act in ("sign", "step01"):          # Alg. 2: h_l = Sign(h^_l), stored as bits along n; the (0, 1) step (Sec. 3.2)
         return pack_sign(hhat32, word_bits)  # stores the very same bit: 1 where h^_l > 0
     if act == "logsoftmax":                # Alg. 2: Softmax at l = L
@@ -275,11 +286,14 @@ class OracleLayer:
 
 def make_layers(Ws: Sequence[np.ndarray], biases: Sequence[np.ndarray], hidden_act: str, word_bits: int,
                 use_scale: bool = True) -> List[OracleLayer]:
-    """Alg. 1, first step of the forward loop: w^b_l = Sign(w_l), done once; scale_l = mean|w_l| broadcast over n."""
+    """Alg. 1, first step of the forward loop: w^b_l = Sign(w_l), done once; scale_l = mean|w_l| broadcast over n.
+
+    hidden_act: one activation name for every hidden layer, or a sequence with one name per hidden layer.
+    """
     layers = []
     for l, (W, r) in enumerate(zip(Ws, biases)):
         N, K = W.shape
-        act = "logsoftmax" if l == len(Ws) - 1 else hidden_act
+        act = "logsoftmax" if l == len(Ws) - 1 else (hidden_act if isinstance(hidden_act, str) else hidden_act[l])
         scale = np.full(N, mean_abs(W), dtype=np.float32) if use_scale else None
         layers.append(OracleLayer(K, N, act, word_bits, pack_sign(W, word_bits), scale,
                                   np.ascontiguousarray(r, dtype=np.float32)))

@@ -278,6 +278,21 @@ def test_hardtanh(oracle):
 
 # ----------------------------------------------------------------------------- log-softmax
 
+def test_sigmoid_vs_scipy_and_identities(oracle):
+    from scipy.special import expit
+    rng = np.random.default_rng(9)
+    v = np.concatenate([rng.standard_normal(1000) * 8, [0.0, -0.0, 1e-30, -1e-30, 88.0, -88.0, 104.0, -104.0, 1e30, -1e30]]).astype(np.float32)
+    got = oracle.sigmoid(v)
+    assert got.dtype == np.float32
+    assert np.array_equal(got, expit(v.astype(np.float64)).astype(np.float32))     # library routine, same rounding
+    assert oracle.sigmoid(np.zeros(1, np.float32))[0] == np.float32(0.5)
+    assert np.allclose(got.astype(np.float64) + oracle.sigmoid(-v).astype(np.float64), 1.0, atol=2e-7)   # sigma(-v) = 1 - sigma(v)
+    order = np.argsort(v, kind="stable")
+    assert np.all(np.diff(got[order]) >= 0)                                         # monotone
+    assert got.min() >= 0.0 and got.max() <= 1.0
+    assert oracle.sigmoid(np.array([1e30], np.float32))[0] == 1.0 and oracle.sigmoid(np.array([-1e30], np.float32))[0] == 0.0
+
+
 def test_log_softmax_vs_scipy_and_invariants(oracle):
     rng = _rng(31)
     for N in (2, 1000, 3307, 3400, 3972):
