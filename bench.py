@@ -68,13 +68,13 @@ def all_configs(args, bnn, workloads, G, torch) -> int:
     for kv in args.opt:
         key, val = kv.split("=")
         bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
-    for cid in (1, 2, 3, 4, 6, 7, 8):
+    for cid in (1, 2, 3, 4, 6, 7, 8, 9):
         cfg = workloads.CONFIGS[cid]
         Ws, bs = workloads.make_net_params(cfg)
         model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
         X = G.to_dev(workloads.make_frames(cfg))
         out = torch.empty((cfg.M, model.N_out), dtype=torch.float32, device=G.DEV)
-        steps = 200 if cid == 1 else (10 if cid == 4 else 50)
+        steps = 200 if cid == 1 else (10 if cid in (4, 9) else 50)
         for _ in range(3):
             model.forward(X, out)
         torch.cuda.synchronize()

@@ -55,7 +55,8 @@ typedef enum bnn_act {
     BNN_ACT_LINEAR = 1,    /* fp32 h^                                                                     */
     BNN_ACT_HARDTANH = 2,  /* fp32 min(1, max(-1, h^))                                                    */
     BNN_ACT_SIGN = 3,      /* packed bits of Sign(h^): bit = (h^ > 0), packed along n                     */
-    BNN_ACT_LOGSOFTMAX = 4 /* fp32 log-posteriors: h^ - max_n h^ - log sum_n exp(h^ - max_n h^)           */
+    BNN_ACT_LOGSOFTMAX = 4, /* fp32 log-posteriors: h^ - max_n h^ - log sum_n exp(h^ - max_n h^)          */
+    BNN_ACT_SIGMOID = 5     /* fp32 1 / (1 + exp(-h^)): the real hidden layers of the paper's networks (Sec. 3) */
 } bnn_act;
 
 /* Which arithmetic unit carries the binary x binary product (same results, different speed). */
@@ -83,7 +84,7 @@ typedef enum bnn_option {
                                    by grid size (default)                                                        */
     BNN_OPT_MFMA32_XCD_ORDER = 11, /* 32x32x64 kernel: 1 = tiles that share rows of frames run on the same XCD (one L2),
                                    2 = tiles in dispatch order, 0 = by problem size (default)                     */
-    BNN_OPT_REALX_F32_MFMA = 10, /* real-input layers with fp32 outputs (LINEAR, HARDTANH, LOGSOFTMAX) of 128 frames or
+    BNN_OPT_REALX_F32_MFMA = 10, /* real-input layers with fp32 outputs (LINEAR, HARDTANH, SIGMOID, LOGSOFTMAX) of 128 frames or
                                    more: 0 = vector-ALU kernel (default; sum in ascending k, bit-identical to the
                                    reference definition), 1 = fp32 matrix-core kernel, about 3x faster; its sums are
                                    taken in the matrix core's order and differ by fp32 rounding (1e-6 of the layer's
@@ -140,7 +141,7 @@ int bnn_pack_activations(const float* X, int64_t M, int64_t K, int word_bits, vo
  * add/subtract, acc[m][n] = sum_k (Wp bit ? +X[m][k] : -X[m][k]), accumulated in fp32 in ascending k
  * with one accumulator per output; then h^ = fmaf(scale[n], acc, bias[n]) and the activation.
  *   X [M][K] fp32; Wp [N][Kw]; scale, bias [N] or NULL
- *   act: LINEAR, HARDTANH, LOGSOFTMAX -> Y fp32 [M][N];  SIGN -> Y words [M][bnn_packed_words(N, word_bits)]
+ *   act: LINEAR, HARDTANH, SIGMOID, LOGSOFTMAX -> Y fp32 [M][N];  SIGN -> Y words [M][bnn_packed_words(N, word_bits)]
  */
 int bnn_layer_binw_realx(const float* X, const void* Wp, const float* scale, const float* bias,
                          int64_t M, int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream);
@@ -150,7 +151,7 @@ int bnn_layer_binw_realx(const float* X, const void* Wp, const float* scale, con
  * values = K - 2 * popcount(Xp[m] XOR Wp[n]), exact in int32; then h^ = fmaf(scale[n], (float)dot, bias[n])
  * and the activation.
  *   Xp [M][Kw]; Wp [N][Kw]; K < 2^24
- *   act: RAW_I32 -> Y int32 [M][N] (scale, bias ignored); LINEAR, HARDTANH, LOGSOFTMAX -> Y fp32 [M][N];
+ *   act: RAW_I32 -> Y int32 [M][N] (scale, bias ignored); LINEAR, HARDTANH, SIGMOID, LOGSOFTMAX -> Y fp32 [M][N];
  *        SIGN -> Y words [M][bnn_packed_words(N, word_bits)]
  */
 int bnn_layer_binw_binx(const void* Xp, const void* Wp, const float* scale, const float* bias,

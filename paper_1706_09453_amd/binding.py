@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbnn_hip.so")
 
 BNN_OK, BNN_EINVAL, BNN_ESHAPE, BNN_EALIGN, BNN_EWORKSPACE, BNN_EDEVICE = 0, -1, -2, -3, -4, -5
-BNN_ACT_RAW_I32, BNN_ACT_LINEAR, BNN_ACT_HARDTANH, BNN_ACT_SIGN, BNN_ACT_LOGSOFTMAX = 0, 1, 2, 3, 4
+BNN_ACT_RAW_I32, BNN_ACT_LINEAR, BNN_ACT_HARDTANH, BNN_ACT_SIGN, BNN_ACT_LOGSOFTMAX, BNN_ACT_SIGMOID = 0, 1, 2, 3, 4, 5
 BNN_ARM_AUTO, BNN_ARM_VALU_XOR, BNN_ARM_MFMA, BNN_ARM_MFMA_I8 = 0, 1, 2, 3
 BNN_OPT_BINX_ARM, BNN_OPT_REALX_TM, BNN_OPT_BINX_VALU_TM, BNN_OPT_MFMA_WM = 1, 2, 3, 4
 BNN_OPT_REALX_SIGN_MFMA, BNN_OPT_FUSED_LOGSOFTMAX, BNN_OPT_MFMA_SHAPE, BNN_OPT_MFMA32_WM = 5, 6, 7, 8
@@ -25,7 +25,8 @@ BNN_OPT_REALX_F32_MFMA = 10
 BNN_OPT_MFMA32_XCD_ORDER = 11
 
 ACT_BY_NAME = {"raw": BNN_ACT_RAW_I32, "linear": BNN_ACT_LINEAR, "hardtanh": BNN_ACT_HARDTANH,
-               "sign": BNN_ACT_SIGN, "step01": BNN_ACT_SIGN, "logsoftmax": BNN_ACT_LOGSOFTMAX}
+               "sign": BNN_ACT_SIGN, "step01": BNN_ACT_SIGN, "logsoftmax": BNN_ACT_LOGSOFTMAX,
+               "sigmoid": BNN_ACT_SIGMOID}
 
 
 class bnn_layer_desc(ctypes.Structure):

@@ -57,7 +57,7 @@ int check_layer_args(const void* X, const void* Wp, int64_t M, int64_t K, int64_
                      bool binx) {
     if (!word_bits_ok(wb) || M < 0 || K <= 0 || N <= 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim) return BNN_ESHAPE;
     if (binx && K >= ((int64_t)1 << 24)) return BNN_ESHAPE;
-    if (act < BNN_ACT_RAW_I32 || act > BNN_ACT_LOGSOFTMAX) return BNN_EINVAL;
+    if (act < BNN_ACT_RAW_I32 || act > BNN_ACT_SIGMOID) return BNN_EINVAL;
     if (!binx && act == BNN_ACT_RAW_I32) return BNN_EINVAL;
     if (M == 0) return BNN_OK;
     if (!X || !Wp || !Y) return BNN_EINVAL;
@@ -83,6 +83,9 @@ void launch_realx_tm(const float* X, const uint32_t* Wp, const float* scale, con
             break;
         case BNN_ACT_HARDTANH:
             realx_valu_kernel<TM, ACT_HARDTANH><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_SIGMOID:
+            realx_valu_kernel<TM, ACT_SIGMOID><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         default:
             realx_valu_kernel<TM, ACT_LINEAR><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
@@ -113,6 +116,9 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
         if (act == BNN_ACT_HARDTANH) {
             if (vec) realx_f32_mfma_kernel<ACT_HARDTANH, true><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
             else realx_f32_mfma_kernel<ACT_HARDTANH, false><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+        } else if (act == BNN_ACT_SIGMOID) {
+            if (vec) realx_f32_mfma_kernel<ACT_SIGMOID, true><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+            else realx_f32_mfma_kernel<ACT_SIGMOID, false><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
         } else {
             if (vec) realx_f32_mfma_kernel<ACT_LINEAR, true><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
             else realx_f32_mfma_kernel<ACT_LINEAR, false><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
@@ -143,6 +149,9 @@ void launch_binx_valu_tm(const uint32_t* Xp, const uint32_t* Wp, const float* sc
         case BNN_ACT_HARDTANH:
             binx_valu_kernel<TM, ACT_HARDTANH, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
+        case BNN_ACT_SIGMOID:
+            binx_valu_kernel<TM, ACT_SIGMOID, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
         default:
             binx_valu_kernel<TM, ACT_LINEAR, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
@@ -163,6 +172,9 @@ void launch_binx_mfma_wm(const uint32_t* Xp, const uint32_t* Wp, const float* sc
             break;
         case BNN_ACT_HARDTANH:
             binx_mfma_kernel<WM, WN, ACT_HARDTANH, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_SIGMOID:
+            binx_mfma_kernel<WM, WN, ACT_SIGMOID, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         default:
             binx_mfma_kernel<WM, WN, ACT_LINEAR, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
@@ -195,6 +207,9 @@ void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* sca
         case BNN_ACT_HARDTANH:
             binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
+        case BNN_ACT_SIGMOID:
+            binx_mfma32_kernel<WM, WN, ACT_SIGMOID, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            break;
         default:
             binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
             break;
@@ -214,6 +229,9 @@ void launch_binx_mfma_i8(const uint32_t* Xp, const uint32_t* Wp, const float* sc
             break;
         case BNN_ACT_HARDTANH:
             binx_mfma_i8_kernel<ACT_HARDTANH, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            break;
+        case BNN_ACT_SIGMOID:
+            binx_mfma_i8_kernel<ACT_SIGMOID, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         default:
             binx_mfma_i8_kernel<ACT_LINEAR, AL><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
@@ -373,7 +391,7 @@ int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
     for (int l = 0; l < n_layers; ++l) {
         const bnn_layer_desc& d = L[l];
         if (!word_bits_ok(d.word_bits) || d.K <= 0 || d.N <= 0 || d.K > kMaxDim || d.N > kMaxDim) return BNN_ESHAPE;
-        if (d.act < BNN_ACT_LINEAR || d.act > BNN_ACT_LOGSOFTMAX || d.reserved != 0) return BNN_EINVAL;
+        if (d.act < BNN_ACT_LINEAR || d.act > BNN_ACT_SIGMOID || d.reserved != 0) return BNN_EINVAL;
         if (d.x_is_binary < 0 || d.x_is_binary > 2) return BNN_EINVAL;
         if (!d.Wp) return BNN_EINVAL;
         if (l > 0) {

@@ -10,10 +10,10 @@ namespace bnn {
 constexpr int kWave = 64;
 
 // Activation selectors; numerically identical to bnn_act in include/bnn.h.
-enum : int { ACT_RAW_I32 = 0, ACT_LINEAR = 1, ACT_HARDTANH = 2, ACT_SIGN = 3, ACT_LOGSOFTMAX = 4 };
+enum : int { ACT_RAW_I32 = 0, ACT_LINEAR = 1, ACT_HARDTANH = 2, ACT_SIGN = 3, ACT_LOGSOFTMAX = 4, ACT_SIGMOID = 5 };
 // Kernel-internal: the integer product as int16 in the first 2 N bytes of each fp32 output row (|dot| <= K < 2^15);
 // the log-Softmax row kernel turns the row into fp32 log-posteriors in place.
-enum : int { ACT_DOT_I16 = 5 };
+enum : int { ACT_DOT_I16 = 100 };
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 
@@ -28,6 +28,13 @@ __device__ __forceinline__ float hardtanh(float v) {
     v = v < -1.0f ? -1.0f : v;
     return v;
 }
+
+// Sigmoid of the paper's real hidden layers (Sec. 3), evaluated in fp64 and rounded once to fp32, as the reference
+// definition does: a layer of Sign units that reads these values must see the same fp32 numbers, bit for bit, or a
+// unit whose pre-activation is nearly zero flips and every binary layer after it diverges.  (An fp32 exp is within
+// 1e-6, which is fine for the values and fatal for the bits.)  Two fp64 exp implementations can differ in the last
+// place of the fp64 result; that survives the rounding to fp32 with probability about 2^-29 per value.
+__device__ __forceinline__ float sigmoid(float v) { return (float)(1.0 / (1.0 + exp(-(double)v))); }
 
 // +1.0f or -1.0f from bit `pos` of `inv` where inv holds the COMPLEMENT of the weight bits
 // (weight bit 1 <=> +1 <=> float sign bit clear).

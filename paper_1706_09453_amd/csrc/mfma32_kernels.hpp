@@ -424,6 +424,7 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
                     } else {
                         float h = affine(sc[fn], dot, bi[fn]);
                         if constexpr (ACT == ACT_HARDTANH) h = hardtanh(h);
+                        if constexpr (ACT == ACT_SIGMOID) h = sigmoid(h);
                         bits = __float_as_uint(h);
                     }
                     st[(8 * (v >> 2) + 4 * g + (v & 3)) * LDW + fn * 32 + r] = bits;

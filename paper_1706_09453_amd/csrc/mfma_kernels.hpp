@@ -196,6 +196,7 @@ __global__ __launch_bounds__(256) void binx_mfma_kernel(const uint32_t* __restri
                         } else {
                             float h = affine(sc[fn], dot, bi[fn]);
                             if constexpr (ACT == ACT_HARDTANH) h = hardtanh(h);
+                            if constexpr (ACT == ACT_SIGMOID) h = sigmoid(h);
                             ((float*)Y)[(size_t)m * N + n] = h;
                         }
                     }

@@ -140,6 +140,7 @@ __global__ __launch_bounds__(256, 2) void realx_f32_mfma_kernel(const float* __r
             for (int v = 0; v < 16; ++v) {
                 float h = affine(sc[fn], acc[fm][fn][v], bi[fn]);
                 if constexpr (ACT == ACT_HARDTANH) h = hardtanh(h);
+                if constexpr (ACT == ACT_SIGMOID) h = sigmoid(h);
                 st[(8 * (v >> 2) + 4 * g + (v & 3)) * LDW + fn * 32 + r] = h;
             }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // this wave's LDS writes are done before it reads them back

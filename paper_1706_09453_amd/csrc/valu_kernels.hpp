@@ -52,6 +52,7 @@ __device__ __forceinline__ void epilogue_lanes_n(const float (&v)[TM], const int
             for (int i = 0; i < TM; ++i) {
                 float h = affine(sc, v[i], bi);
                 if constexpr (ACT == ACT_HARDTANH) h = hardtanh(h);
+                if constexpr (ACT == ACT_SIGMOID) h = sigmoid(h);
                 if (nvalid && m0 + i < M) Yf[(size_t)(m0 + i) * N + n] = h;
             }
         }

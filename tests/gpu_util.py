@@ -96,12 +96,13 @@ class GpuModel:
             Wp, sc = pack_weights(Wd, word_bits)
             scale = sc.expand(N).contiguous()           # broadcast the per-layer scalar to [N] (a copy, no arithmetic)
             bias = to_dev(r.astype(np.float32))
-            act = bnn.BNN_ACT_LOGSOFTMAX if l == len(Ws) - 1 else bnn.ACT_BY_NAME[hidden_act]
+            name = hidden_act if isinstance(hidden_act, str) else (hidden_act[l] if l < len(Ws) - 1 else None)
+            act = bnn.BNN_ACT_LOGSOFTMAX if l == len(Ws) - 1 else bnn.ACT_BY_NAME[name]
             self.keep += [Wp, scale, bias]
             self.scales.append(sc)
             descs.append(dict(K=K, N=N, act=act, word_bits=word_bits, x_is_binary=binary,
                               Wp=ptr(Wp), scale=ptr(scale), bias=ptr(bias)))
-            binary = (2 if hidden_act == "step01" else 1) if act == bnn.BNN_ACT_SIGN else 0
+            binary = (2 if name == "step01" else 1) if act == bnn.BNN_ACT_SIGN else 0
             del Wd
         self.descs = descs
         self.layers = bnn.make_layer_array(descs)

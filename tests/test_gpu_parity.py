@@ -135,21 +135,21 @@ def test_binx_raw_dot_bit_exact(G, bnn, oracle, M, K, N, wb, arm):
 
 @pytest.mark.parametrize("arm", ARMS)
 @pytest.mark.parametrize("wb", [32, 64])
-@pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax"])
+@pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax", "sigmoid"])
 @pytest.mark.parametrize("M,K,N", [(3, 31, 5), (70, 33, 65), (130, 440, 200), (257, 512, 129), (200, 2048, 1000),
                                    (96, 1024, 3307)])
 def test_binx_layer_acts(G, bnn, oracle, M, K, N, act, wb, arm):
     aw, bw = _bin_operands(oracle, 5 * M + K + N, M, K, N, wb)
     _, _, scale, bias = _rand_layer(M + N, 1, 1, N)
-    if act == "hardtanh":
+    if act in ("hardtanh", "sigmoid"):
         scale = scale / np.float32(np.sqrt(K))            # keep a good share of outputs inside (-1, 1)
     with _arm(bnn, arm) as armv:
         Y = G.layer_binx(G.to_dev(aw), G.to_dev(bw), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb, armv)
     want = oracle.layer_binw_binx(aw, bw, K, scale, bias, act, wb, form="xor")
     if act == "sign":
         assert np.array_equal(G.words_to_host(Y, wb), want)
-    elif act == "logsoftmax":
-        _close(Y.cpu().numpy(), want, "logsoftmax")
+    elif act in ("logsoftmax", "sigmoid"):
+        _close(Y.cpu().numpy(), want, act)                 # fp32 exp on the GPU, fp64 in the oracle
     else:
         assert np.array_equal(Y.cpu().numpy(), want)       # one fma on an exact integer: identical bits
         if act == "hardtanh":
@@ -169,13 +169,13 @@ def test_binx_null_scale_bias(G, bnn, oracle):
 # ----------------------------------------------------------------------------- activations read as 0/1 (Sec. 3.2)
 
 @pytest.mark.parametrize("wb", [32, 64])
-@pytest.mark.parametrize("act", ["raw", "sign", "linear", "hardtanh", "logsoftmax"])
+@pytest.mark.parametrize("act", ["raw", "sign", "linear", "hardtanh", "logsoftmax", "sigmoid"])
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (130, 440, 200), (257, 512, 129),
                                    (200, 2048, 1000), (96, 1024, 3307), (1100, 1024, 384), (4096, 2048, 256)])
 def test_binx01_layer(G, bnn, oracle, M, K, N, act, wb):
     aw, bw = _bin_operands(oracle, 7 * M + K + N, M, K, N, wb)
     _, _, scale, bias = _rand_layer(M + N, 1, 1, N)
-    if act == "hardtanh":
+    if act in ("hardtanh", "sigmoid"):
         scale = scale / np.float32(np.sqrt(K))
     Y = G.layer_binx01(G.to_dev(aw), G.to_dev(bw), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb)
     want = oracle.layer_binw_binx01(aw, bw, K, scale, bias, act, wb, form="and")
@@ -184,8 +184,8 @@ def test_binx01_layer(G, bnn, oracle, M, K, N, act, wb):
                               oracle.layer_binw_binx01(aw, bw, K, None, None, "raw", wb, form="and"))
     if act == "sign":
         assert np.array_equal(G.words_to_host(Y, wb), want)
-    elif act == "logsoftmax":
-        _close(Y.cpu().numpy(), want, "logsoftmax")
+    elif act in ("logsoftmax", "sigmoid"):
+        _close(Y.cpu().numpy(), want, act)
     else:
         assert np.array_equal(Y.cpu().numpy(), want)     # exact integer, then one fma: identical bits
 
@@ -194,7 +194,7 @@ def test_binx01_layer(G, bnn, oracle, M, K, N, act, wb):
 
 @pytest.mark.parametrize("tm", [8, 16, 32])
 @pytest.mark.parametrize("wb", [32, 64])
-@pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax"])
+@pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax", "sigmoid"])
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (64, 440, 512), (130, 440, 200),
                                    (37, 2048, 300), (50, 100, 3307)])
 def test_realx_layer(G, bnn, oracle, M, K, N, act, wb, tm):
@@ -202,15 +202,15 @@ def test_realx_layer(G, bnn, oracle, M, K, N, act, wb, tm):
     bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, tm)
     try:
         X, W, scale, bias = _rand_layer(M * 3 + K + N, M, K, N)
-        if act == "hardtanh":
+        if act in ("hardtanh", "sigmoid"):
             scale = scale / np.float32(np.sqrt(K))
         Wp = oracle.pack_sign(W, wb)
         Y = G.layer_realx(G.to_dev(X), G.to_dev(Wp), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb)
         want = oracle.layer_binw_realx(X, Wp, K, scale, bias, act, wb)
         if act == "sign":
             assert np.array_equal(G.words_to_host(Y, wb), want)
-        elif act == "logsoftmax":
-            _close(Y.cpu().numpy(), want, "logsoftmax")
+        elif act in ("logsoftmax", "sigmoid"):
+            _close(Y.cpu().numpy(), want, act)
         else:
             got = Y.cpu().numpy()
             _close(got, want, act)
@@ -220,7 +220,7 @@ def test_realx_layer(G, bnn, oracle, M, K, N, act, wb, tm):
 
 
 @pytest.mark.parametrize("wb", [32, 64])
-@pytest.mark.parametrize("act", ["linear", "hardtanh", "logsoftmax", "sign"])
+@pytest.mark.parametrize("act", ["linear", "hardtanh", "logsoftmax", "sign", "sigmoid"])
 @pytest.mark.parametrize("M,K,N", [(128, 16, 1), (130, 440, 200), (300, 33, 65), (257, 100, 3307), (256, 2048, 384),
                                    (1000, 2048, 2048), (513, 1023, 129)])
 def test_realx_layer_matrix_cores(G, bnn, oracle, M, K, N, act, wb):
@@ -228,7 +228,7 @@ def test_realx_layer_matrix_cores(G, bnn, oracle, M, K, N, act, wb):
     of additions is its own: within the tolerance of the oracle's fp32 sum and of its fp64 shadow.  Sign outputs stay
     bit-exact (other kernel)."""
     X, W, scale, bias = _rand_layer(M * 5 + K + N, M, K, N)
-    if act == "hardtanh":
+    if act in ("hardtanh", "sigmoid"):
         scale = scale / np.float32(np.sqrt(K))
     Wp = oracle.pack_sign(W, wb)
     bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 1)
@@ -243,7 +243,7 @@ def test_realx_layer_matrix_cores(G, bnn, oracle, M, K, N, act, wb):
         return
     got = Y.cpu().numpy()
     _close(got, want, act)
-    if act != "logsoftmax":
+    if act in ("linear", "hardtanh"):
         _, acc64 = oracle.realx_acc(X, oracle.unpack_pm1(Wp, K, wb))
         z64 = oracle.affine_f64(acc64, scale, bias)
         _close(got, np.clip(z64, -1.0, 1.0) if act == "hardtanh" else z64, act + " fp64 shadow")
@@ -384,7 +384,7 @@ def test_forward_config1_layer_by_layer_bits(G, bnn, oracle):
         h = Y
 
 
-@pytest.mark.parametrize("cfg_id,M", [(2, 96), (3, 300), (4, 200), (6, 1100), (7, 1030), (8, 300), (8, 1280)])
+@pytest.mark.parametrize("cfg_id,M", [(2, 96), (3, 300), (4, 200), (6, 1100), (7, 1030), (8, 300), (8, 1280), (9, 96), (9, 1100)])
 def test_forward_configs_reduced_batch_full_compare(G, bnn, oracle, cfg_id, M):
     cfg = workloads.CONFIGS[cfg_id]
     _net_parity(G, bnn, oracle, cfg, M)

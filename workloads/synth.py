@@ -77,7 +77,7 @@ class NetConfig:
     name: str
     dims: Tuple[int, ...]
     M: int
-    hidden_act: str
+    hidden_act: object          # str, or a tuple of str with one name per hidden layer
     word_bits: int
     seed: int = 0
 
@@ -89,13 +89,17 @@ class NetConfig:
         """(K, N) of layer l (0-based)."""
         return self.dims[l], self.dims[l + 1]
 
+    def hidden_act_of(self, l: int) -> str:
+        """Activation of hidden layer l (0-based): hidden_act is one name for all of them or one name per layer."""
+        return self.hidden_act if isinstance(self.hidden_act, str) else self.hidden_act[l]
+
     def macs_per_frame(self) -> int:
         return sum(self.dims[l] * self.dims[l + 1] for l in range(self.n_layers))
 
     def binbin_macs_per_frame(self) -> int:
-        if self.hidden_act not in ("sign", "step01"):
-            return 0
-        return sum(self.dims[l] * self.dims[l + 1] for l in range(1, self.n_layers))
+        """MACs of the layers whose input is binary (the previous layer's activation is Sign or the (0, 1) step)."""
+        return sum(self.dims[l] * self.dims[l + 1] for l in range(1, self.n_layers)
+                   if self.hidden_act_of(l - 1) in ("sign", "step01"))
 
 
 @dataclass(frozen=True)
@@ -122,6 +126,10 @@ CONFIGS = {
     # Config 3 with the hidden activations binarised to (0, 1) instead of (-1, +1) (Sec. 3.2, Tables 3 and 4)
     8: NetConfig(8, "C8 binW/binX(0,1) 440-6x2048-3400 step01 M=4096",
                  (440,) + (2048,) * 6 + (3400,), 4096, "step01", 32),
+    # the topology the paper's binary-activation systems keep (Sec. 3.2, Table 2: sigma, b, b, b, b, sigma, delta):
+    # Sigmoid in the first and last hidden layer, binary activations in between; binary weights in every layer here
+    9: NetConfig(9, "C9 binW 440-6x2048-3400 (sigmoid,sign,sign,sign,sign,sigmoid) M=4096",
+                 (440,) + (2048,) * 6 + (3400,), 4096, ("sigmoid", "sign", "sign", "sign", "sign", "sigmoid"), 32),
 }
 
 GEMM_SWEEP: List[GemmShape] = [GemmShape(M, K, N)
