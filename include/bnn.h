@@ -84,12 +84,13 @@ typedef enum bnn_option {
                                    by grid size (default)                                                        */
     BNN_OPT_MFMA32_XCD_ORDER = 11, /* 32x32x64 kernel: 1 = tiles that share rows of frames run on the same XCD (one L2),
                                    2 = tiles in dispatch order, 0 = by problem size (default)                     */
-    BNN_OPT_REALX_F32_MFMA = 10, /* real-input layers with fp32 outputs (LINEAR, HARDTANH, SIGMOID, LOGSOFTMAX) of 128 frames or
-                                   more: 0 = vector-ALU kernel (default; sum in ascending k, bit-identical to the
-                                   reference definition), 1 = fp32 matrix-core kernel, about 3x faster; its sums are
-                                   taken in the matrix core's order and differ by fp32 rounding (1e-6 of the layer's
-                                   output scale).  A deep hard-tanh network amplifies such differences from layer to
-                                   layer (measured: 8e-4 of the output scale after 7 layers of 2048 units)          */
+    BNN_OPT_REALX_F32_MFMA = 10, /* real-input layers with fp32 outputs of 128 frames or more: which of them run on the fp32
+                                   matrix-core kernel (about 3x faster; sums in the matrix core's order, within 2e-6 of
+                                   the layer's output scale of the ascending-k sum) instead of the vector-ALU kernel
+                                   (ascending k, bit-identical to the reference definition): 0 = LOGSOFTMAX layers only
+                                   (default: nothing follows them), 1 = LINEAR, HARDTANH and SIGMOID layers too, 2 =
+                                   none.  A deep hard-tanh network amplifies the different rounding from layer to layer
+                                   (measured: 8e-4 of the output scale after 7 layers of 2048 units), hence the default */
     BNN_OPT_MFMA32_PIPELINE = 9  /* operand fetch of the 32x32x64 kernel on 16-byte aligned rows with K % 512 == 0:
                                    0 or 1 = two register sets, the fetch of the next piece of K pinned ahead of
                                    the products of the current one (default), 2 = one set, order left to the

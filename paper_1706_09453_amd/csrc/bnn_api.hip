@@ -108,8 +108,10 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
     if (M == 0) return BNN_OK;
     const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
     const uint32_t* W = static_cast<const uint32_t*>(Wp);
-    if (act != BNN_ACT_SIGN && M >= 128 && g_realx_f32_mfma.load()) {
-        // fp32 outputs of a large batch: the matrix cores (fp32 MFMA, weights as +-1.0f); Sign bits never come here
+    const int f32_mfma = g_realx_f32_mfma.load();
+    if (act != BNN_ACT_SIGN && M >= 128 && (f32_mfma == 1 || (f32_mfma == 0 && act == BNN_ACT_LOGSOFTMAX))) {
+        // fp32 outputs of a large batch on the matrix cores (fp32 MFMA, weights as +-1.0f).  By default only where
+        // nothing but the log-Softmax follows; Sign bits never come here
         const dim3 grid((unsigned)((M + 255) / 256), (unsigned)((N + 127) / 128)), block(256);
         const bool vec = (K % 16 == 0) && aligned(X, 16);
         float* Yf = static_cast<float*>(Y);
@@ -457,7 +459,7 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
             g_mfma32_xcd_order.store(value);
             return BNN_OK;
         case BNN_OPT_REALX_F32_MFMA:
-            if (value != 0 && value != 1) return BNN_EINVAL;
+            if (value < 0 || value > 2) return BNN_EINVAL;
             g_realx_f32_mfma.store(value);
             return BNN_OK;
         case BNN_OPT_MFMA32_PIPELINE:

@@ -200,6 +200,7 @@ def test_binx01_layer(G, bnn, oracle, M, K, N, act, wb):
 def test_realx_layer(G, bnn, oracle, M, K, N, act, wb, tm):
     """The vector-ALU kernel adds in ascending k, as the oracle's fp32 sum does: fp32 outputs are identical bits."""
     bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, tm)
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 2)
     try:
         X, W, scale, bias = _rand_layer(M * 3 + K + N, M, K, N)
         if act in ("hardtanh", "sigmoid"):
@@ -217,6 +218,7 @@ def test_realx_layer(G, bnn, oracle, M, K, N, act, wb, tm):
             assert np.array_equal(got, want), "same order of fp32 additions on both sides: identical bits"
     finally:
         bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, 16)
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
 
 
 @pytest.mark.parametrize("wb", [32, 64])
