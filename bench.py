@@ -221,8 +221,8 @@ def main() -> int:
         bound, peak = "alu", PEAK_XOR_POPC_TOPS
     # HBM bytes per launch of each kernel group from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
     # (profiles/forward_c3_hbm_traffic.txt); measured for this workload with the matrix-core arm only
-    measured_traffic = {"realx": (8.19 + 1.00) * 2 ** 20, "binx hidden": (5.29 + 1.00) * 2 ** 20,
-                        "binx output": (8.03 + 26.83 + 27.27 + 53.13) * 2 ** 20}
+    measured_traffic = {"realx": (8.19 + 1.00) * 2 ** 20, "binx hidden": (5.35 + 1.00) * 2 ** 20,
+                        "binx output": (8.09 + 26.81 + 27.27 + 53.13) * 2 ** 20}
     traffic = None
     if args.arm == "mfma" and not args.opt:
         traffic = next(int(v) for k, v in measured_traffic.items() if dominant.startswith(k))
