@@ -485,6 +485,35 @@ def test_gemm_sweep_int32(G, bnn, oracle, shape, arm):
 
 # ----------------------------------------------------------------------------- edges
 
+def test_forward_in_a_captured_graph_replays_identically(G, bnn, oracle):
+    """bnn_forward only enqueues kernels on the caller's stream: it can be captured and replayed; every replay, with
+    eager work and synchronisations in between, gives the eager result bit for bit."""
+    cfg = workloads.CONFIGS[1]
+    Ws, bs = workloads.make_net_params(cfg)
+    model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
+    X = G.to_dev(workloads.make_frames(cfg, 200))
+    out = torch.empty((200, model.N_out), dtype=torch.float32, device=G.DEV)
+    model.forward(X, out)
+    torch.cuda.synchronize()
+    ref = out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        model.forward(X, out)                      # warm-up on a side stream, as graph capture wants
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        model.forward(X, out)
+    for _ in range(4):
+        out.fill_(float("nan"))                    # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
+        assert torch.equal(model.forward(X), ref)  # and eager again
+
+
 def test_zero_frames_is_a_noop(G, bnn):
     assert bnn.bnn_layer_binw_binx(0, 0, 0, 0, 0, 64, 64, bnn.BNN_ACT_SIGN, 32, 0, G.stream()) == 0
     assert bnn.bnn_layer_binw_realx(0, 0, 0, 0, 0, 64, 64, bnn.BNN_ACT_SIGN, 32, 0, G.stream()) == 0
