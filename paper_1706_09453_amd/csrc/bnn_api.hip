@@ -73,24 +73,32 @@ int check_layer_args(const void* X, const void* Wp, int64_t M, int64_t K, int64_
 
 // ---------------------------------------------------------------- launches (arguments already checked)
 
-template <int TM>
-void launch_realx_tm(const float* X, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
-                     int w32, int act, void* Y, int yw32, hipStream_t st) {
+template <int TM, bool BCAST>
+void launch_realx_tm_b(const float* X, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
+                       int w32, int act, void* Y, int yw32, hipStream_t st) {
     const dim3 grid((M + TM - 1) / TM, (N + 255) / 256), block(256);
     switch (act) {
         case BNN_ACT_SIGN:
-            realx_valu_kernel<TM, ACT_SIGN><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            realx_valu_kernel<TM, ACT_SIGN, BCAST><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         case BNN_ACT_HARDTANH:
-            realx_valu_kernel<TM, ACT_HARDTANH><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            realx_valu_kernel<TM, ACT_HARDTANH, BCAST><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         case BNN_ACT_SIGMOID:
-            realx_valu_kernel<TM, ACT_SIGMOID><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            realx_valu_kernel<TM, ACT_SIGMOID, BCAST><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         default:
-            realx_valu_kernel<TM, ACT_LINEAR><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            realx_valu_kernel<TM, ACT_LINEAR, BCAST><<<grid, block, 0, st>>>(X, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
     }
+}
+
+// the row-broadcast variant reads 16 bytes of a frame per lane: rows 16-byte aligned
+template <int TM>
+void launch_realx_tm(const float* X, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
+                     int w32, int act, void* Y, int yw32, hipStream_t st) {
+    if ((K & 3) == 0 && aligned(X, 16)) launch_realx_tm_b<TM, true>(X, Wp, scale, bias, M, K, N, w32, act, Y, yw32, st);
+    else launch_realx_tm_b<TM, false>(X, Wp, scale, bias, M, K, N, w32, act, Y, yw32, st);
 }
 
 void launch_log_softmax(float* Z, int M, int N, hipStream_t st) {

@@ -10,9 +10,20 @@
 // instruction: no LDS traffic and no cross-lane exchange in the inner loop.
 #pragma once
 
+#include <type_traits>
+
 #include "bnn_device.hpp"
 
 namespace bnn {
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a compile-time constant
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, I + 1>(f);
+    }
+}
 
 // Epilogue for the lanes<->n layout.  v[i] is the product term of frame m0+i and output n (this lane).
 //   ACT_RAW_I32            Y int32 [M][N]          (vi[i], no affine step)
@@ -59,11 +70,25 @@ __device__ __forceinline__ void epilogue_lanes_n(const float (&v)[TM], const int
     }
 }
 
+// acc += x[lane J of this lane's row of 16] * w: the frame operand comes through the DPP row broadcast of the fmac
+// itself, so it costs no instruction of its own.  (The compiler does not fold a DPP move into a three-operand fma.)
+// x must have been written by a memory load, not by a VALU instruction within the two instructions before: the
+// assembler adds no wait states for inline assembly.
+template <int J>
+__device__ __forceinline__ void fmac_row_bcast(float& acc, float x, float w) {
+    asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(x), "v"(w), "n"(J));
+}
+
 // acc[m][n] = sum_k (w[n][k] ? +x[m][k] : -x[m][k]) in fp32, k ascending, one accumulator per output:
 // each step is fma(+-1.0f, x, acc), which rounds exactly like acc +- x.  The +-1.0f is built per lane
-// from the lane's weight bit (2 VALU ops per k, shared by the TM frames), x[m][k] is an SGPR operand.
+// from the lane's weight bit (2 VALU ops per k, shared by the TM frames).
+//   BCAST  (K a multiple of 4, X 16-byte aligned): lane l holds x[m][kc + KV (l mod 16) .. + KV - 1] of a chunk of
+//          16 KV k (one load per frame and chunk, the same in each row of 16 lanes); the fmac takes x[m][k] by a
+//          row broadcast.  The k of the last, partial chunk go the way of !BCAST.
+//   !BCAST x[m][k] is a wave-uniform load and arrives through the scalar cache as an SGPR operand (61 % of the
+//          4-cycle VALU issue rate measured; BCAST reaches 73 % with TM = 16, where 16 of 18 instructions are fmas).
 // Grid: x = ceil(M / TM), y = ceil(N / 256) (4 waves x 64 outputs).
-template <int TM, int ACT>
+template <int TM, int ACT, bool BCAST>
 __global__ __launch_bounds__(256) void realx_valu_kernel(const float* __restrict__ X, const uint32_t* __restrict__ Wp,
                                                          const float* __restrict__ scale, const float* __restrict__ bias,
                                                          int M, int K, int N, int w32, void* __restrict__ Y, int yw32) {
@@ -83,24 +108,91 @@ __global__ __launch_bounds__(256) void realx_valu_kernel(const float* __restrict
 #pragma unroll
     for (int i = 0; i < TM; ++i) acc[i] = 0.0f;
 
-    const int kfull = K >> 5;
-    for (int kw = 0; kw < kfull; ++kw) {
-        const uint32_t inv = ~wrow[kw];
-        const int kb = kw << 5;
+    if constexpr (BCAST) {
+        // KV floats per lane and chunk: a chunk is 16 KV k; two register sets of TM x KV values
+        constexpr int KV = TM <= 8 ? 4 : (TM <= 16 ? 2 : 1);
+        constexpr int KC = 16 * KV;
+        const int nchunks = K / KC;
+        const int lk = (lane & 15) * KV;
+        constexpr int NW = KV == 4 ? 2 : 1;   // weight words a chunk touches
+        auto fetch = [&](float (&v)[TM][KV], uint32_t (&wv)[NW], int c) {
+            if constexpr (KV == 4) {
+                wv[0] = wrow[2 * c], wv[1] = wrow[2 * c + 1];
+            } else {
+                wv[0] = wrow[(c * KC) >> 5];
+            }
 #pragma unroll
-        for (int kk = 0; kk < 32; ++kk) {
-            const float w = pm1_from_inverted_bit(inv, kk);
+            for (int i = 0; i < TM; ++i) {
+                const float* p = xr[i] + c * KC + lk;
+                if constexpr (KV == 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(p);
+                    v[i][0] = t.x, v[i][1] = t.y, v[i][2] = t.z, v[i][3] = t.w;
+                } else if constexpr (KV == 2) {
+                    const float2 t = *reinterpret_cast<const float2*>(p);
+                    v[i][0] = t.x, v[i][1] = t.y;
+                } else {
+                    v[i][0] = *p;
+                }
+            }
+        };
+        auto products = [&](const float (&v)[TM][KV], const uint32_t (&wv)[NW], int c) {
+            // bit (KV J + q) of inv[.] is the complement of the weight of the chunk's k number KV J + q
+            uint32_t inv[NW];
+            if constexpr (KV == 4) {
+                inv[0] = ~wv[0], inv[1] = ~wv[1];
+            } else {
+                inv[0] = ~wv[0] >> ((c * KC) & 31);
+            }
+            static_for<16>([&](auto jc) {
+                constexpr int J = decltype(jc)::value;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) acc[i] = __builtin_fmaf(w, xr[i][kb + kk], acc[i]);
+                for (int q = 0; q < KV; ++q) {
+                    const float w = pm1_from_inverted_bit(inv[(KV * J + q) >> 5], (KV * J + q) & 31);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) fmac_row_bcast<J>(acc[i], v[i][q], w);
+                }
+            });
+        };
+        if (nchunks > 0) {
+            // every fetch unconditional (the one past the end re-reads the last chunk, unused)
+            float va[TM][KV], vb[TM][KV];
+            uint32_t wa[NW], wb[NW];
+            const int last = nchunks - 1;
+            fetch(va, wa, 0);
+            int c = 0;
+            for (; c + 1 < nchunks; c += 2) {
+                fetch(vb, wb, c + 1);
+                products(va, wa, c);
+                fetch(va, wa, c + 2 < last ? c + 2 : last);
+                products(vb, wb, c + 1);
+            }
+            if (c < nchunks) products(va, wa, c);
         }
-    }
-    if (K & 31) {
-        const uint32_t inv = ~wrow[kfull];
-        const int kb = kfull << 5;
-        for (int kk = 0; kb + kk < K; ++kk) {
-            const float w = pm1_from_inverted_bit(inv, kk);
+        for (int k = nchunks * KC; k < K; ++k) {   // fewer than 16 KV of them
+            const float w = pm1_from_inverted_bit(~wrow[k >> 5], k & 31);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) acc[i] = __builtin_fmaf(w, xr[i][kb + kk], acc[i]);
+            for (int i = 0; i < TM; ++i) acc[i] = __builtin_fmaf(w, xr[i][k], acc[i]);
+        }
+    } else {
+        const int kfull = K >> 5;
+        for (int kw = 0; kw < kfull; ++kw) {
+            const uint32_t inv = ~wrow[kw];
+            const int kb = kw << 5;
+#pragma unroll
+            for (int kk = 0; kk < 32; ++kk) {
+                const float w = pm1_from_inverted_bit(inv, kk);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) acc[i] = __builtin_fmaf(w, xr[i][kb + kk], acc[i]);
+            }
+        }
+        if (K & 31) {
+            const uint32_t inv = ~wrow[kfull];
+            const int kb = kfull << 5;
+            for (int kk = 0; kb + kk < K; ++kk) {
+                const float w = pm1_from_inverted_bit(inv, kk);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) acc[i] = __builtin_fmaf(w, xr[i][kb + kk], acc[i]);
+            }
         }
     }
     int dummy[TM];
