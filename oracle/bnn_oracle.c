@@ -189,6 +189,44 @@ ORC_API void orc_realx_acc(const float* x, const int8_t* wpm1, int64_t M, int64_
 }
 
 /*
+ * Eq. 1 for a layer whose weights stay real-valued (Sec. 2.2, last paragraph, and Sec. 3.1: the input layer and the
+ * Softmax layer of the paper's systems keep the real-valued weights of the model they were initialised from):
+ * acc[m][n] = sum_k w[n][k] * x[m][k].  Reading: fp32, ascending k, one accumulator per output, each step ONE fused
+ * multiply-add (a single rounding per step), the same order as the binary-weight product above, to which it
+ * reduces bit for bit when every w is +1 or -1.  acc64 is the fp64 shadow sum (every product of two fp32 numbers
+ * is exact in fp64).
+ */
+ORC_API void orc_realw_acc(const float* x, const float* w, int64_t M, int64_t N, int64_t K,
+                           float* acc32, double* acc64) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            float s32 = 0.0f;
+            double s64 = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                s32 = fmaf(w[n * K + k], x[m * K + k], s32);
+                s64 += (double)w[n * K + k] * (double)x[m * K + k];
+            }
+            if (acc32) acc32[m * N + n] = s32;
+            if (acc64) acc64[m * N + n] = s64;
+        }
+}
+
+/* Bits of a binary hidden layer as the real numbers the next, real-weight layer multiplies: bit 1 -> +1.0, bit 0 ->
+ * -1.0 (Sign units, Alg. 2) or bit 1 -> 1.0, bit 0 -> 0.0 (the (0, 1) units of Sec. 3.2). */
+ORC_API void orc_bits_to_real(const void* words, int64_t M, int64_t K, int word_bits, int zero_one, float* out) {
+    const int64_t Kw = (K + word_bits - 1) / word_bits;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            uint64_t word;
+            if (word_bits == 64) word = ((const uint64_t*)words)[m * Kw + k / 64];
+            else                 word = ((const uint32_t*)words)[m * Kw + k / 32];
+            const int bit = (int)((word >> (k % word_bits)) & 1u);
+            out[m * K + k] = bit ? 1.0f : (zero_one ? 0.0f : -1.0f);
+        }
+}
+
+/*
  * Eq. 1 with the per-layer scale: h^[m][n] = scale[n] * v[m][n] + bias[n] as one
  * fp32 fused multiply-add (single rounding).  scale == NULL means 1, bias == NULL means 0.
  */

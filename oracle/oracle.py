@@ -40,6 +40,8 @@ def _L():
             "orc_dot_x01_wpm1": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p],
             "orc_dot_and": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_void_p],
             "orc_realx_acc": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p],
+            "orc_realw_acc": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p],
+            "orc_bits_to_real": [c_void_p, c_int64, c_int64, c_int, c_int, c_void_p],
             "orc_affine_f32": [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p],
             "orc_affine_f64": [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p],
             "orc_i32_to_f32": [c_void_p, c_int64, c_void_p],
@@ -160,6 +162,26 @@ def realx_acc(x: np.ndarray, w_pm1: np.ndarray, want64: bool = True):
     return acc32, acc64
 
 
+def realw_acc(x: np.ndarray, w: np.ndarray, want64: bool = True):
+    """Eq. 1 product of a real-weight layer: (acc32 in ascending k with one fma per step, acc64 fp64 shadow)."""
+    x, w = _c(x, np.float32), _c(w, np.float32)
+    M, K = x.shape
+    N = w.shape[0]
+    assert w.shape[1] == K
+    acc32 = np.empty((M, N), dtype=np.float32)
+    acc64 = np.empty((M, N), dtype=np.float64) if want64 else None
+    _L().orc_realw_acc(_p(x), _p(w), M, N, K, _p(acc32), _p(acc64))
+    return acc32, acc64
+
+
+def bits_to_real(words: np.ndarray, K: int, word_bits: int, zero_one: bool) -> np.ndarray:
+    """Stored bits of a binary layer as fp32 numbers: -1/+1 (Sign units) or 0/1 (Sec. 3.2)."""
+    a = _c(words, _word_dtype(word_bits))
+    out = np.empty((a.shape[0], K), dtype=np.float32)
+    _L().orc_bits_to_real(_p(a), a.shape[0], K, word_bits, int(zero_one), _p(out))
+    return out
+
+
 def affine_f32(v: np.ndarray, scale: Optional[np.ndarray], bias: Optional[np.ndarray]) -> np.ndarray:
     """h^ = fmaf(scale[n], v[m,n], bias[n]) in fp32, one rounding."""
     v = _c(v, np.float32)
@@ -236,6 +258,12 @@ def layer_binw_realx(x: np.ndarray, w_words: np.ndarray, K: int, scale, bias, ac
     return _finish(affine_f32(acc32, scale, bias), act, word_bits)
 
 
+def layer_realw(x: np.ndarray, W: np.ndarray, bias, act: str, word_bits: int):
+    """One layer with real-valued weights (Eq. 1-2; the input and Softmax layers of the paper's systems, Sec. 3.1)."""
+    acc32, _ = realw_acc(x, W, want64=False)
+    return _finish(affine_f32(acc32, None, bias), act, word_bits)
+
+
 def layer_binw_binx(x_words: np.ndarray, w_words: np.ndarray, K: int, scale, bias, act: str, word_bits: int,
                     form: str = "definition"):
     """One layer with binary weights and binary input (Sec. 2.3).
@@ -282,18 +310,24 @@ class OracleLayer:
     w_words: np.ndarray         # [N, ceil(K/wb)]
     scale: Optional[np.ndarray]  # [N] fp32 or None
     bias: Optional[np.ndarray]   # [N] fp32 or None
+    w_real: Optional[np.ndarray] = None   # [N, K] fp32: the layer keeps real-valued weights (then w_words is None)
 
 
 def make_layers(Ws: Sequence[np.ndarray], biases: Sequence[np.ndarray], hidden_act: str, word_bits: int,
-                use_scale: bool = True) -> List[OracleLayer]:
+                use_scale: bool = True, real_weight_layers: Sequence[int] = ()) -> List[OracleLayer]:
     """Alg. 1, first step of the forward loop: w^b_l = Sign(w_l), done once; scale_l = mean|w_l| broadcast over n.
 
     hidden_act: one activation name for every hidden layer, or a sequence with one name per hidden layer.
+    real_weight_layers: indices of the layers that keep their real-valued weights (Sec. 3.1: input and Softmax layer).
     """
     layers = []
     for l, (W, r) in enumerate(zip(Ws, biases)):
         N, K = W.shape
         act = "logsoftmax" if l == len(Ws) - 1 else (hidden_act if isinstance(hidden_act, str) else hidden_act[l])
+        if l in real_weight_layers:
+            layers.append(OracleLayer(K, N, act, word_bits, None, None, np.ascontiguousarray(r, dtype=np.float32),
+                                      np.ascontiguousarray(W, dtype=np.float32)))
+            continue
         scale = np.full(N, mean_abs(W), dtype=np.float32) if use_scale else None
         layers.append(OracleLayer(K, N, act, word_bits, pack_sign(W, word_bits), scale,
                                   np.ascontiguousarray(r, dtype=np.float32)))
@@ -312,7 +346,11 @@ def forward(layers: Sequence[OracleLayer], x: np.ndarray, form: str = "definitio
     outs = []
     for ly in layers:
         act = ly.act
-        if domain == "pm1":
+        if ly.w_real is not None:
+            if domain != "real":   # the bits of a binary layer, as the numbers they stand for
+                h = bits_to_real(h, ly.K, ly.word_bits, zero_one=(domain == "01"))
+            h = layer_realw(h, ly.w_real, ly.bias, act, ly.word_bits)
+        elif domain == "pm1":
             h = layer_binw_binx(h, ly.w_words, ly.K, ly.scale, ly.bias, act, ly.word_bits, form=form)
         elif domain == "01":
             h = layer_binw_binx01(h, ly.w_words, ly.K, ly.scale, ly.bias, act, ly.word_bits, form=form)

@@ -219,6 +219,92 @@ def test_realx_special_cases(oracle):
     assert np.array_equal(acc64, oracle.dot_pm1(a, b).astype(np.float64))
 
 
+# ----------------------------------------------------------------------------- real input x real weights
+
+@pytest.mark.parametrize("K", [1, 2, 33, 440, 2048])
+def test_realw_acc_vs_library_gemm(oracle, K):
+    rng = _rng(900 + K)
+    x = rng.standard_normal((5, K)).astype(np.float32)
+    w = (rng.standard_normal((7, K)) / math.sqrt(K)).astype(np.float32)
+    acc32, acc64 = oracle.realw_acc(x, w)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    want64 = x64 @ w64.T                                # library GEMM, any order
+    mag = np.abs(x64) @ np.abs(w64).T                   # sum_k |w x|
+    assert np.all(np.abs(acc64 - want64) <= K * np.finfo(np.float64).eps * mag + 1e-300)
+    u = 2.0 ** -24                                      # one rounding per step: the classical bound K u / (1 - K u)
+    assert np.all(np.abs(acc32.astype(np.float64) - want64) <= (K * u / (1 - K * u)) * mag + 1e-300)
+    # transposing the operands' roles must not matter: (x w^T)^T = w x^T
+    accT, _ = oracle.realw_acc(w, x)
+    assert np.array_equal(accT, acc32.T)                # products commute exactly, the order in k is the same
+
+
+def test_realw_reduces_to_the_binary_weight_product(oracle):
+    # every weight +1 or -1: each fused multiply-add is an exact add or subtract, i.e. Alg. 1's product, bit for bit
+    rng = _rng(41)
+    for K in (31, 440, 1000):
+        x = rng.standard_normal((6, K)).astype(np.float32)
+        w = _pm1(rng, 9, K)
+        a32, a64 = oracle.realw_acc(x, w.astype(np.float32))
+        b32, b64 = oracle.realx_acc(x, w)
+        assert np.array_equal(a32, b32) and np.array_equal(a64, b64)
+
+
+def test_realw_order_and_single_rounding(oracle):
+    one = np.ones((1, 3), np.float32)
+    # ascending k: 1e8 - 1e8 + 1 = 1, but 1 + 1e8 - 1e8 = 0 in fp32
+    assert oracle.realw_acc(np.array([[1e8, -1e8, 1.0]], np.float32), one)[0][0, 0] == 1.0
+    assert oracle.realw_acc(np.array([[1.0, 1e8, -1e8]], np.float32), one)[0][0, 0] == 0.0
+    # one rounding per step: (1 + 2^-12)^2 - (1 + 2^-11) = 2^-24 exactly; a rounded product would give 0
+    a = np.float32(1 + 2.0 ** -12)
+    x = np.array([[-(1 + 2.0 ** -11), a]], np.float32)
+    w = np.array([[1.0, a]], np.float32)
+    acc32, acc64 = oracle.realw_acc(x, w)
+    assert acc32[0, 0] == np.float32(2.0 ** -24) and acc64[0, 0] == 2.0 ** -24
+    # exact small integers
+    x = np.arange(1, 7, dtype=np.float32)[None]
+    w = np.array([[2, -1, 0, 3, -2, 1]], np.float32)
+    assert oracle.realw_acc(x, w)[0][0, 0] == 2 - 2 + 0 + 12 - 10 + 6
+
+
+def test_bits_to_real(oracle):
+    rng = _rng(5)
+    for wb in (32, 64):
+        for K in (1, 31, 33, 64, 65, 130):
+            v = rng.standard_normal((3, K)).astype(np.float32)
+            words = oracle.pack_sign(v, wb)
+            assert np.array_equal(oracle.bits_to_real(words, K, wb, False), np.where(v > 0, 1.0, -1.0).astype(np.float32))
+            assert np.array_equal(oracle.bits_to_real(words, K, wb, True), (v > 0).astype(np.float32))
+
+
+def test_real_weight_network_vs_independent_numpy(oracle):
+    # (sigmoid, sign, step01, sigmoid) hidden layers, real weights in the first, third and last layer, the rest binary
+    import workloads
+    cfg = workloads.NetConfig(11, "pin", (40, 64, 70, 48, 33, 21), 9, ("sigmoid", "sign", "step01", "sigmoid"), 32,
+                              real_weight_layers=(0, 2, 4))
+    Ws, bs = workloads.make_net_params(cfg)
+    X = workloads.make_frames(cfg)
+    layers = oracle.make_layers(Ws, bs, cfg.hidden_act, 32, real_weight_layers=cfg.real_weight_layers)
+    got, outs = oracle.forward(layers, X, keep=True)
+    # independent fp64 restatement; the binary layers' inputs are taken from the oracle's own bits so that a
+    # pre-activation within rounding of zero cannot make the two diverge
+    h = X.astype(np.float64)
+    for l, (W, r) in enumerate(zip(Ws, bs)):
+        W64 = W.astype(np.float64) if l in cfg.real_weight_layers else np.where(W > 0, 1.0, -1.0) * np.float64(np.float32(np.mean(np.abs(W), dtype=np.float64)))
+        z = h @ W64.T + r.astype(np.float64)
+        act = "logsoftmax" if l == len(Ws) - 1 else cfg.hidden_act[l]
+        if act == "sigmoid":
+            h = 1.0 / (1.0 + np.exp(-z))
+            assert np.max(np.abs(outs[l] - h)) <= 2e-6
+        elif act in ("sign", "step01"):
+            bits = oracle.unpack_01(outs[l], W.shape[0], 32).astype(bool)
+            clear = np.abs(z) > 1e-4
+            assert np.array_equal(bits[clear], (z > 0)[clear]) and clear.mean() > 0.99
+            h = np.where(bits, 1.0, -1.0 if act == "sign" else 0.0)
+        else:
+            want = z - scipy.special.logsumexp(z, axis=1, keepdims=True)
+            assert np.max(np.abs(got - want)) <= 1e-5
+
+
 # ----------------------------------------------------------------------------- affine step
 
 def _nearest_f32(fr: Fraction) -> np.float32:

@@ -80,6 +80,7 @@ class NetConfig:
     hidden_act: object          # str, or a tuple of str with one name per hidden layer
     word_bits: int
     seed: int = 0
+    real_weight_layers: Tuple[int, ...] = ()   # 0-based layers that keep real-valued weights (Sec. 3.1)
 
     @property
     def n_layers(self) -> int:
@@ -99,7 +100,7 @@ class NetConfig:
     def binbin_macs_per_frame(self) -> int:
         """MACs of the layers whose input is binary (the previous layer's activation is Sign or the (0, 1) step)."""
         return sum(self.dims[l] * self.dims[l + 1] for l in range(1, self.n_layers)
-                   if self.hidden_act_of(l - 1) in ("sign", "step01"))
+                   if self.hidden_act_of(l - 1) in ("sign", "step01") and l not in self.real_weight_layers)
 
 
 @dataclass(frozen=True)
@@ -130,6 +131,11 @@ CONFIGS = {
     # Sigmoid in the first and last hidden layer, binary activations in between; binary weights in every layer here
     9: NetConfig(9, "C9 binW 440-6x2048-3400 (sigmoid,sign,sign,sign,sign,sigmoid) M=4096",
                  (440,) + (2048,) * 6 + (3400,), 4096, ("sigmoid", "sign", "sign", "sign", "sign", "sigmoid"), 32),
+    # the same topology as the paper deploys it (Sec. 2.2 end, Sec. 3.1, Table 2 rows 1-3): the input layer and the
+    # Softmax layer keep real-valued weights, only the intermediate hidden layers have binary weights
+    10: NetConfig(10, "C10 realW in/out, binW between, 440-6x2048-3400 (sigmoid,sign,sign,sign,sign,sigmoid) M=4096",
+                  (440,) + (2048,) * 6 + (3400,), 4096, ("sigmoid", "sign", "sign", "sign", "sign", "sigmoid"), 32,
+                  real_weight_layers=(0, 6)),
 }
 
 GEMM_SWEEP: List[GemmShape] = [GemmShape(M, K, N)
@@ -145,11 +151,18 @@ def _tid(cfg_id: int, layer: int, kind: int) -> int:
 
 
 def make_net_params(cfg: NetConfig):
-    """Real-valued weights [N,K] ~ U(-1,1) and biases [N] ~ N(0, 0.1^2) for every layer."""
+    """Real-valued weights [N,K] ~ U(-1,1) and biases [N] ~ N(0, 0.1^2) for every layer.
+
+    A layer that keeps its real-valued weights gets them scaled by sqrt(3/K) (unit-variance pre-activations for
+    unit-variance inputs, the range a trained layer works in); a binarised layer's scale is its mean |w| anyway.
+    """
     Ws, bs = [], []
     for l in range(cfg.n_layers):
         K, N = cfg.layer_shape(l)
-        Ws.append(uniform_pm1(cfg.seed, _tid(cfg.cfg_id, l + 1, TENSOR_W), N * K).reshape(N, K))
+        W = uniform_pm1(cfg.seed, _tid(cfg.cfg_id, l + 1, TENSOR_W), N * K).reshape(N, K)
+        if l in cfg.real_weight_layers:
+            W = (W * np.float32(np.sqrt(3.0 / K))).astype(np.float32)
+        Ws.append(W)
         bs.append(normal(cfg.seed, _tid(cfg.cfg_id, l + 1, TENSOR_BIAS), N, std=0.1))
     return Ws, bs
 
