@@ -105,8 +105,9 @@ typedef struct bnn_layer_desc {
     int32_t word_bits;    /* 32 or 64: packing of Wp, of a binary input and of a SIGN output */
     int32_t x_is_binary;  /* 0: input is fp32 [M][K]; 1: packed bits [M][Kw] read as -1/+1;
                              2: packed bits read as 0/1 (see bnn_layer_binw_binx01)            */
-    int32_t reserved;     /* must be 0                                                      */
-    const void* Wp;       /* packed weights [N][Kw]                                         */
+    int32_t w_is_real;    /* 0: Wp is packed bits [N][Kw]; 1: the layer keeps real-valued weights (see
+                             bnn_layer_realw): Wp is fp32 [N][K] and scale must be NULL      */
+    const void* Wp;       /* weights, see w_is_real                                         */
     const float* scale;   /* [N] or NULL (= 1)                                              */
     const float* bias;    /* [N] or NULL (= 0)                                              */
 } bnn_layer_desc;
@@ -168,6 +169,30 @@ int bnn_layer_binw_binx(const void* Xp, const void* Wp, const float* scale, cons
 int bnn_layer_binw_binx01(const void* Xp, const void* Wp, const float* scale, const float* bias,
                           int64_t M, int64_t K, int64_t N, int act, int word_bits, void* Y, void* stream);
 
+/*
+ * One layer that keeps REAL-valued weights (Eq. 1-2; Sec. 2.2, last paragraph, and Sec. 3.1: the paper's systems keep
+ * the real-valued weights of the input layer and of the Softmax layer, only the intermediate hidden layers are
+ * binarised): acc[m][n] = sum_k W[n][k] X[m][k], then h^ = acc + bias[n] (one rounding) and the activation.
+ *   X [M][K] fp32; W [N][K] fp32; bias [N] or NULL
+ *   act: LINEAR, HARDTANH, SIGMOID -> Y fp32 [M][N]: the sum is taken in fp32 in ascending k, one fused multiply-add
+ *        per step, one accumulator per output (the order of bnn_layer_binw_realx);
+ *        SIGN -> Y words [M][bnn_packed_words(N, word_bits)], bits from that same sum;
+ *        LOGSOFTMAX -> Y fp32 [M][N]; for M >= 128 the sum is taken on the fp32 matrix cores in their own order
+ *        (within ordinary fp32 rounding of the ascending-k sum; BNN_OPT_REALX_F32_MFMA = 2 turns this off, = 1
+ *        extends it to LINEAR, HARDTANH and SIGMOID).
+ *   word_bits only sets the packing of a SIGN output.
+ * Errors as bnn_layer_binw_realx.
+ */
+int bnn_layer_realw(const float* X, const float* W, const float* bias, int64_t M, int64_t K, int64_t N, int act,
+                    int word_bits, void* Y, void* stream);
+
+/*
+ * The inverse of bnn_pack_activations for a real-weight layer that follows a binary one: X[m][k] = +1.0 where bit k
+ * of row m is set, else -1.0 (zero_one = 0: Sign units, Alg. 2) or 0.0 (zero_one = 1: the (0, 1) units of Sec. 3.2).
+ *   Xp words [M][bnn_packed_words(K, word_bits)];  X out, fp32 [M][K]
+ */
+int bnn_unpack_activations(const void* Xp, int64_t M, int64_t K, int word_bits, int zero_one, float* X, void* stream);
+
 /* As bnn_layer_binw_binx, with the arithmetic unit chosen by the caller (bnn_binx_arm); same results. */
 int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, const float* bias,
                             int64_t M, int64_t K, int64_t N, int act, int word_bits, void* Y, int arm,
@@ -175,8 +200,9 @@ int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, 
 
 /*
  * Bytes of scratch bnn_forward needs for M frames: two ping-pong buffers, each large enough for the
- * largest inter-layer activation (packed bits or fp32), each 256-byte aligned.  0 for a one-layer network
- * and on invalid arguments.  HOST helper; layers is a HOST array.
+ * largest inter-layer activation (packed bits or fp32), each 256-byte aligned, plus, if a real-weight layer reads
+ * the bits of a binary layer, a third buffer for those bits as fp32.  0 for a one-layer network and on invalid
+ * arguments.  HOST helper; layers is a HOST array.
  */
 size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M);
 
@@ -192,6 +218,7 @@ size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, i
  *             or packed bits when its act is SIGN
  *   workspace DEVICE scratch of at least bnn_forward_workspace_bytes() bytes, 256-byte aligned
  *             (may be NULL for a one-layer network)
+ * A layer with w_is_real = 1 runs as bnn_layer_realw (after bnn_unpack_activations if its input is binary).
  * Enqueues one kernel per layer (two for a LOGSOFTMAX layer) on `stream`, no host synchronisation.
  */
 int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,

@@ -31,7 +31,7 @@ ACT_BY_NAME = {"raw": BNN_ACT_RAW_I32, "linear": BNN_ACT_LINEAR, "hardtanh": BNN
 
 class bnn_layer_desc(ctypes.Structure):
     _fields_ = [("K", c_int64), ("N", c_int64), ("act", c_int32), ("word_bits", c_int32),
-                ("x_is_binary", c_int32), ("reserved", c_int32),
+                ("x_is_binary", c_int32), ("w_is_real", c_int32),
                 ("Wp", c_void_p), ("scale", c_void_p), ("bias", c_void_p)]
 
 
@@ -52,6 +52,8 @@ _SIGNATURES = {
                                     c_void_p, c_void_p]),
     "bnn_layer_binw_binx01": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_int,
                                       c_void_p, c_void_p]),
+    "bnn_layer_realw": (c_int, [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_int, c_void_p, c_void_p]),
+    "bnn_unpack_activations": (c_int, [c_void_p, c_int64, c_int64, c_int, c_int, c_void_p, c_void_p]),
     "bnn_layer_binw_binx_arm": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_int,
                                         c_void_p, c_int, c_void_p]),
     "bnn_forward_workspace_bytes": (c_size_t, [c_void_p, c_int, c_int64]),
@@ -115,6 +117,15 @@ def bnn_layer_binw_binx01(Xp: int, Wp: int, scale: int, bias: int, M: int, K: in
                                              stream or None))
 
 
+def bnn_layer_realw(X: int, W: int, bias: int, M: int, K: int, N: int, act: int, word_bits: int, Y: int,
+                    stream: int = 0) -> int:
+    return _check(_lib.bnn_layer_realw(X, W, bias or None, M, K, N, act, word_bits, Y, stream or None))
+
+
+def bnn_unpack_activations(Xp: int, M: int, K: int, word_bits: int, zero_one: int, X: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_unpack_activations(Xp, M, K, word_bits, zero_one, X, stream or None))
+
+
 def bnn_layer_binw_binx_arm(Xp: int, Wp: int, scale: int, bias: int, M: int, K: int, N: int, act: int,
                             word_bits: int, Y: int, arm: int, stream: int = 0) -> int:
     return _check(_lib.bnn_layer_binw_binx_arm(Xp, Wp, scale or None, bias or None, M, K, N, act, word_bits, Y, arm,
@@ -122,12 +133,13 @@ def bnn_layer_binw_binx_arm(Xp: int, Wp: int, scale: int, bias: int, M: int, K: 
 
 
 def make_layer_array(descs: Sequence[dict]):
-    """HOST array of bnn_layer_desc from dicts with keys K, N, act, word_bits, x_is_binary, Wp, scale, bias."""
+    """HOST array of bnn_layer_desc from dicts with keys K, N, act, word_bits, x_is_binary, Wp, scale, bias and,
+    optionally, w_is_real."""
     arr = (bnn_layer_desc * len(descs))()
     for i, d in enumerate(descs):
         arr[i].K, arr[i].N = d["K"], d["N"]
         arr[i].act, arr[i].word_bits = d["act"], d["word_bits"]
-        arr[i].x_is_binary, arr[i].reserved = int(d["x_is_binary"]), 0
+        arr[i].x_is_binary, arr[i].w_is_real = int(d["x_is_binary"]), int(d.get("w_is_real", 0))
         arr[i].Wp, arr[i].scale, arr[i].bias = d["Wp"] or None, d.get("scale") or None, d.get("bias") or None
     return arr
 

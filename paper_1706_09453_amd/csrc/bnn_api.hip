@@ -10,6 +10,7 @@
 #include "mfma32_kernels.hpp"
 #include "mfma_i8_kernels.hpp"
 #include "realx_mfma_kernels.hpp"
+#include "realw_kernels.hpp"
 #include "mfma_kernels.hpp"
 #include "pack_kernels.hpp"
 #include "realx_fused_kernel.hpp"
@@ -54,18 +55,18 @@ size_t out_bytes(int64_t M, int64_t N, int act, int wb) {
 }
 
 int check_layer_args(const void* X, const void* Wp, int64_t M, int64_t K, int64_t N, int act, int wb, const void* Y,
-                     bool binx) {
+                     bool binx, bool realw = false) {
     if (!word_bits_ok(wb) || M < 0 || K <= 0 || N <= 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim) return BNN_ESHAPE;
     if (binx && K >= ((int64_t)1 << 24)) return BNN_ESHAPE;
     if (act < BNN_ACT_RAW_I32 || act > BNN_ACT_SIGMOID) return BNN_EINVAL;
     if (!binx && act == BNN_ACT_RAW_I32) return BNN_EINVAL;
     if (M == 0) return BNN_OK;
     if (!X || !Wp || !Y) return BNN_EINVAL;
-    if (!aligned(Wp, wb / 8)) return BNN_EALIGN;
+    if (!aligned(Wp, realw ? 4 : wb / 8)) return BNN_EALIGN;
     if (!aligned(X, binx ? wb / 8 : 4)) return BNN_EALIGN;
     if (!aligned(Y, act == BNN_ACT_SIGN ? wb / 8 : 4)) return BNN_EALIGN;
     const size_t xb = binx ? (size_t)M * row_w32(K, wb) * 4 : (size_t)M * K * 4;
-    const size_t wbytes = (size_t)N * row_w32(K, wb) * 4;
+    const size_t wbytes = realw ? (size_t)N * K * 4 : (size_t)N * row_w32(K, wb) * 4;
     const size_t yb = out_bytes(M, N, act, wb);
     if (overlap(X, xb, Y, yb) || overlap(Wp, wbytes, Y, yb)) return BNN_EINVAL;
     return BNN_OK;
@@ -142,6 +143,57 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
         default: launch_realx_tm<16>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
     }
     if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(static_cast<float*>(Y), (int)M, (int)N, st);
+    return launch_status();
+}
+
+template <int ACT>
+void launch_realw_valu(const float* X, const float* W, const float* bias, int M, int K, int N, void* Y, int yw32,
+                       hipStream_t st) {
+    const dim3 grid((M + kRealwTM - 1) / kRealwTM, (N + 255) / 256), block(256);
+    if ((K & 3) == 0 && aligned(X, 16) && aligned(W, 16))
+        realw_valu_kernel<ACT><<<grid, block, 0, st>>>(X, W, bias, M, K, N, Y, yw32);
+    else
+        realw_valu_simple_kernel<ACT><<<grid, block, 0, st>>>(X, W, bias, M, K, N, Y, yw32);
+}
+
+template <int ACT>
+void launch_realw_mfma(const float* X, const float* W, const float* bias, int M, int K, int N, float* Y, hipStream_t st) {
+    const dim3 grid((unsigned)((M + 255) / 256), (unsigned)((N + 127) / 128)), block(256);
+    if ((K % 16 == 0) && aligned(X, 16) && aligned(W, 16))
+        realx_f32_mfma_kernel<ACT, true, true><<<grid, block, 0, st>>>(X, W, nullptr, bias, M, K, N, 0, Y);
+    else
+        realx_f32_mfma_kernel<ACT, false, true><<<grid, block, 0, st>>>(X, W, nullptr, bias, M, K, N, 0, Y);
+}
+
+// A layer with real-valued weights.  The matrix-core rule is the one of run_realx.
+int run_realw(const float* X, const float* W, const float* bias, int64_t M, int64_t K, int64_t N, int act, int wb,
+              void* Y, hipStream_t st) {
+    if (M == 0) return BNN_OK;
+    const int yw32 = (int)row_w32(N, wb);
+    const int f32_mfma = g_realx_f32_mfma.load();
+    if (act != BNN_ACT_SIGN && M >= 128 && (f32_mfma == 1 || (f32_mfma == 0 && act == BNN_ACT_LOGSOFTMAX))) {
+        float* Yf = static_cast<float*>(Y);
+        if (act == BNN_ACT_HARDTANH) launch_realw_mfma<ACT_HARDTANH>(X, W, bias, (int)M, (int)K, (int)N, Yf, st);
+        else if (act == BNN_ACT_SIGMOID) launch_realw_mfma<ACT_SIGMOID>(X, W, bias, (int)M, (int)K, (int)N, Yf, st);
+        else launch_realw_mfma<ACT_LINEAR>(X, W, bias, (int)M, (int)K, (int)N, Yf, st);
+    } else {
+        switch (act) {
+            case BNN_ACT_SIGN: launch_realw_valu<ACT_SIGN>(X, W, bias, (int)M, (int)K, (int)N, Y, yw32, st); break;
+            case BNN_ACT_HARDTANH: launch_realw_valu<ACT_HARDTANH>(X, W, bias, (int)M, (int)K, (int)N, Y, yw32, st); break;
+            case BNN_ACT_SIGMOID: launch_realw_valu<ACT_SIGMOID>(X, W, bias, (int)M, (int)K, (int)N, Y, yw32, st); break;
+            default: launch_realw_valu<ACT_LINEAR>(X, W, bias, (int)M, (int)K, (int)N, Y, yw32, st); break;
+        }
+    }
+    if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(static_cast<float*>(Y), (int)M, (int)N, st);
+    return launch_status();
+}
+
+int run_unpack(const void* Xp, int64_t M, int64_t K, int wb, int zero_one, float* X, hipStream_t st) {
+    if (M == 0) return BNN_OK;
+    const int64_t total = M * K;
+    const int64_t blocks = (total + 255) / 256;
+    bits_to_real_kernel<<<(unsigned)(blocks < 65536 ? blocks : 65536), 256, 0, st>>>(static_cast<const uint32_t*>(Xp), M, (int)K,
+                                                                                     (int)row_w32(K, wb), zero_one, X);
     return launch_status();
 }
 
@@ -401,7 +453,8 @@ int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
     for (int l = 0; l < n_layers; ++l) {
         const bnn_layer_desc& d = L[l];
         if (!word_bits_ok(d.word_bits) || d.K <= 0 || d.N <= 0 || d.K > kMaxDim || d.N > kMaxDim) return BNN_ESHAPE;
-        if (d.act < BNN_ACT_LINEAR || d.act > BNN_ACT_SIGMOID || d.reserved != 0) return BNN_EINVAL;
+        if (d.act < BNN_ACT_LINEAR || d.act > BNN_ACT_SIGMOID) return BNN_EINVAL;
+        if (d.w_is_real < 0 || d.w_is_real > 1 || (d.w_is_real && d.scale)) return BNN_EINVAL;
         if (d.x_is_binary < 0 || d.x_is_binary > 2) return BNN_EINVAL;
         if (!d.Wp) return BNN_EINVAL;
         if (l > 0) {
@@ -540,15 +593,48 @@ BNN_EXPORT int bnn_layer_binw_binx(const void* Xp, const void* Wp, const float* 
     return bnn_layer_binw_binx_arm(Xp, Wp, scale, bias, M, K, N, act, word_bits, Y, BNN_ARM_AUTO, stream);
 }
 
+BNN_EXPORT int bnn_layer_realw(const float* X, const float* W, const float* bias, int64_t M, int64_t K, int64_t N, int act,
+                               int word_bits, void* Y, void* stream) {
+    const int rc = check_layer_args(X, W, M, K, N, act, word_bits, Y, false, true);
+    if (rc != BNN_OK) return rc;
+    return run_realw(X, W, bias, M, K, N, act, word_bits, Y, static_cast<hipStream_t>(stream));
+}
+
+BNN_EXPORT int bnn_unpack_activations(const void* Xp, int64_t M, int64_t K, int word_bits, int zero_one, float* X,
+                                      void* stream) {
+    if (!word_bits_ok(word_bits) || M < 0 || K <= 0 || M > kMaxDim || K > kMaxDim) return BNN_ESHAPE;
+    if (zero_one < 0 || zero_one > 1) return BNN_EINVAL;
+    if (M == 0) return BNN_OK;
+    if (!Xp || !X) return BNN_EINVAL;
+    if (!aligned(Xp, word_bits / 8) || !aligned(X, 4)) return BNN_EALIGN;
+    if (overlap(Xp, (size_t)M * row_w32(K, word_bits) * 4, X, (size_t)M * K * 4)) return BNN_EINVAL;
+    return run_unpack(Xp, M, K, word_bits, zero_one, X, static_cast<hipStream_t>(stream));
+}
+
+// Workspace layout of bnn_forward: two ping-pong buffers of `half` bytes, then `unpacked` bytes for the fp32 copy of
+// the bits that a real-weight layer reads.
+struct ForwardWorkspace {
+    size_t half, unpacked;
+};
+static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_layers, int64_t M) {
+    size_t biggest = 0, unpacked = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        if (l + 1 < n_layers) {
+            const size_t b = out_bytes(M, layers[l].N, layers[l].act, layers[l].word_bits);
+            if (b > biggest) biggest = b;
+        }
+        if (layers[l].w_is_real && layers[l].x_is_binary) {
+            const size_t b = (size_t)M * (size_t)layers[l].K * 4;
+            if (b > unpacked) unpacked = b;
+        }
+    }
+    return {round_up(biggest, 256), round_up(unpacked, 256)};
+}
+
 BNN_EXPORT size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M) {
     if (check_chain(layers, n_layers, M) != BNN_OK) return 0;
-    size_t biggest = 0;
-    for (int l = 0; l + 1 < n_layers; ++l) {
-        const size_t b = out_bytes(M, layers[l].N, layers[l].act, layers[l].word_bits);
-        if (b > biggest) biggest = b;
-    }
-    size_t total = 2 * round_up(biggest, 256);
-    return total;
+    const ForwardWorkspace ws = forward_workspace(layers, n_layers, M);
+    return 2 * ws.half + ws.unpacked;
 }
 
 BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
@@ -561,29 +647,39 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
     if (need && (!workspace || workspace_bytes < need)) return BNN_EWORKSPACE;
     if (need && !aligned(workspace, 256)) return BNN_EALIGN;
     // Check every layer's arguments before anything is enqueued.
-    size_t biggest = 0;
-    for (int l = 0; l + 1 < n_layers; ++l) {
-        const size_t b = out_bytes(M, layers[l].N, layers[l].act, layers[l].word_bits);
-        if (b > biggest) biggest = b;
-    }
-    const size_t half = round_up(biggest, 256);
-    char* buf[2] = {static_cast<char*>(workspace), static_cast<char*>(workspace) + half};
+    const ForwardWorkspace ws = forward_workspace(layers, n_layers, M);
+    char* buf[2] = {static_cast<char*>(workspace), static_cast<char*>(workspace) + ws.half};
+    float* unpacked = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * ws.half);
+    hipStream_t st = static_cast<hipStream_t>(stream);
     for (int pass = 0; pass < 2; ++pass) {
         const void* in = X;
         for (int l = 0; l < n_layers; ++l) {
             const bnn_layer_desc& d = layers[l];
             void* o = (l == n_layers - 1) ? out : static_cast<void*>(buf[l & 1]);
             if (pass == 0) {
-                rc = check_layer_args(in, d.Wp, M, d.K, d.N, d.act, d.word_bits, o, d.x_is_binary != 0);
+                if (d.w_is_real && d.x_is_binary) {
+                    if (!aligned(in, d.word_bits / 8)) return BNN_EALIGN;
+                    rc = check_layer_args(unpacked, d.Wp, M, d.K, d.N, d.act, d.word_bits, o, false, true);
+                } else {
+                    rc = check_layer_args(in, d.Wp, M, d.K, d.N, d.act, d.word_bits, o, d.x_is_binary != 0, d.w_is_real != 0);
+                }
+            } else if (d.w_is_real) {
+                const float* xin = static_cast<const float*>(in);
+                if (d.x_is_binary) {
+                    rc = run_unpack(in, M, d.K, d.word_bits, d.x_is_binary == 2, unpacked, st);
+                    if (rc != BNN_OK) return rc;
+                    xin = unpacked;
+                }
+                rc = run_realw(xin, static_cast<const float*>(d.Wp), d.bias, M, d.K, d.N, d.act, d.word_bits, o, st);
             } else if (d.x_is_binary) {
-                rc = run_binx(in, d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o, BNN_ARM_AUTO,
-                              static_cast<hipStream_t>(stream), d.x_is_binary == 2);
+                rc = run_binx(in, d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o, BNN_ARM_AUTO, st,
+                              d.x_is_binary == 2);
             } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load()) {
                 rc = run_realx_sign_mfma(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
-                                         o, static_cast<hipStream_t>(stream));
+                                         o, st);
             } else {
                 rc = run_realx(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o,
-                               static_cast<hipStream_t>(stream));
+                               st);
             }
             if (rc != BNN_OK) return rc;
             in = o;

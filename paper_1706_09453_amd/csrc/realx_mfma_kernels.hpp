@@ -22,11 +22,15 @@ namespace bnn {
 typedef float v16f32 __attribute__((ext_vector_type(16)));
 
 // VEC: K % 16 == 0 and X rows 16-byte aligned (16-byte loads); otherwise element loads, zero past K.
-// Grid: x = ceil(M / 256), y = ceil(N / 128); block = 256 threads.  ACT: ACT_LINEAR or ACT_HARDTANH.
-template <int ACT, bool VEC>
-__global__ __launch_bounds__(256, 2) void realx_f32_mfma_kernel(const float* __restrict__ X, const uint32_t* __restrict__ Wp,
+// WREAL: the layer keeps real-valued weights (paper Sec. 3.1: input and Softmax layer): Wv is fp32 [N][K] (16-byte
+//        aligned too if VEC), fetched exactly like the frames; otherwise Wv is packed bits [N][w32].
+// Grid: x = ceil(M / 256), y = ceil(N / 128); block = 256 threads.  ACT: ACT_LINEAR, ACT_HARDTANH or ACT_SIGMOID.
+template <int ACT, bool VEC, bool WREAL = false>
+__global__ __launch_bounds__(256, 2) void realx_f32_mfma_kernel(const float* __restrict__ X, const void* __restrict__ Wv,
                                                                const float* __restrict__ scale, const float* __restrict__ bias,
                                                                int M, int K, int N, int w32, float* __restrict__ Y) {
+    const uint32_t* Wp = static_cast<const uint32_t*>(Wv);
+    const float* Wf = static_cast<const float*>(Wv);
     constexpr int WM = 4, WN = 2;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
@@ -37,6 +41,7 @@ __global__ __launch_bounds__(256, 2) void realx_f32_mfma_kernel(const float* __r
 
     const float* arow[WM];
     const uint32_t* brow[WN];
+    const float* brow_f[WN];
 #pragma unroll
     for (int f = 0; f < WM; ++f) {
         const int m = m_base + f * 32 + r;
@@ -46,6 +51,7 @@ __global__ __launch_bounds__(256, 2) void realx_f32_mfma_kernel(const float* __r
     for (int f = 0; f < WN; ++f) {
         const int n = n_base + f * 32 + r;
         brow[f] = Wp + (size_t)(n < N ? n : N - 1) * w32;
+        brow_f[f] = Wf + (size_t)(n < N ? n : N - 1) * K + 8 * g;
     }
     float sc[WN], bi[WN];
 #pragma unroll
@@ -67,40 +73,51 @@ __global__ __launch_bounds__(256, 2) void realx_f32_mfma_kernel(const float* __r
     struct Set {
         float a[WM][8];
         uint32_t b[WN];
+        float bf[WREAL ? WN : 1][8];
+    };
+    // the lane's 8 values of chunk cc of a row of floats; p points at element 8 g of the row
+    auto fetch8 = [&](float (&dst)[8], const float* p, int cc) {
+        if constexpr (VEC) {
+            const float4 lo = *reinterpret_cast<const float4*>(p + 16 * cc);
+            const float4 hi = *reinterpret_cast<const float4*>(p + 16 * cc + 4);
+            dst[0] = lo.x; dst[1] = lo.y; dst[2] = lo.z; dst[3] = lo.w;
+            dst[4] = hi.x; dst[5] = hi.y; dst[6] = hi.z; dst[7] = hi.w;
+        } else {
+            const float* row = p - 8 * g;   // start of the row
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int k = 16 * cc + 8 * g + t;
+                const float v = row[k < K ? k : K - 1];   // index clamped into the row, value dropped past K
+                dst[t] = k < K ? v : 0.0f;
+            }
+        }
     };
     auto fetch = [&](Set& s, int c) {
         const int cc = c < nC ? c : nC - 1;   // past the end: re-read the last chunk (in bounds, unused)
 #pragma unroll
-        for (int f = 0; f < WM; ++f) {
-            if constexpr (VEC) {
-                const float4 lo = *reinterpret_cast<const float4*>(arow[f] + 16 * cc);
-                const float4 hi = *reinterpret_cast<const float4*>(arow[f] + 16 * cc + 4);
-                s.a[f][0] = lo.x; s.a[f][1] = lo.y; s.a[f][2] = lo.z; s.a[f][3] = lo.w;
-                s.a[f][4] = hi.x; s.a[f][5] = hi.y; s.a[f][6] = hi.z; s.a[f][7] = hi.w;
-            } else {
-                const float* row = arow[f] - 8 * g;   // start of the row
+        for (int f = 0; f < WM; ++f) fetch8(s.a[f], arow[f], cc);
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const int k = 16 * cc + 8 * g + t;
-                    const float v = row[k < K ? k : K - 1];   // index clamped into the row, value dropped past K
-                    s.a[f][t] = k < K ? v : 0.0f;
-                }
-            }
+        for (int f = 0; f < WN; ++f) {
+            if constexpr (WREAL) fetch8(s.bf[f], brow_f[f], cc);
+            else s.b[f] = brow[f][cc >> 1];
         }
-#pragma unroll
-        for (int f = 0; f < WN; ++f) s.b[f] = brow[f][cc >> 1];
     };
     auto products = [&](const Set& s, int c) {
         // bit 16 (c & 1) + 8 g + t of the complemented word, moved to bit 24 + t: weight bit 1 <=> +1.0f <=> sign bit clear
         const int base = 16 * (c & 1) + 8 * g;
         uint32_t q[WN];
+        if constexpr (!WREAL) {
 #pragma unroll
-        for (int f = 0; f < WN; ++f) q[f] = ((~s.b[f]) >> base) << 24;
+            for (int f = 0; f < WN; ++f) q[f] = ((~s.b[f]) >> base) << 24;
+        }
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             float bx[WN];
 #pragma unroll
-            for (int f = 0; f < WN; ++f) bx[f] = __uint_as_float(((q[f] << (7 - t)) & 0x80000000u) | 0x3f800000u);
+            for (int f = 0; f < WN; ++f) {
+                if constexpr (WREAL) bx[f] = s.bf[f][t];
+                else bx[f] = __uint_as_float(((q[f] << (7 - t)) & 0x80000000u) | 0x3f800000u);
+            }
 #pragma unroll
             for (int fm = 0; fm < WM; ++fm)
 #pragma unroll

@@ -81,10 +81,24 @@ def layer_binx01(Xp, Wp, scale, bias, K, N, act, word_bits):
     return Y
 
 
+def layer_realw(X, W, bias, K, N, act, word_bits):
+    M = X.shape[0]
+    Y = out_tensor(M, N, act, word_bits)
+    bnn.bnn_layer_realw(ptr(X), ptr(W), ptr(bias), M, K, N, act, word_bits, ptr(Y), stream())
+    return Y
+
+
+def unpack_activations(Xp, K, word_bits, zero_one):
+    M = Xp.shape[0]
+    X = torch.full((M, K), float("nan"), dtype=torch.float32, device=DEV)
+    bnn.bnn_unpack_activations(ptr(Xp), M, K, word_bits, int(zero_one), ptr(X), stream())
+    return X
+
+
 class GpuModel:
     """Packed model on the GPU, prepared with bnn_pack_weights from real-valued weights (Alg. 1: w^b = Sign(w))."""
 
-    def __init__(self, Ws, biases, hidden_act: str, word_bits: int, x_is_binary: bool = False):
+    def __init__(self, Ws, biases, hidden_act: str, word_bits: int, x_is_binary: bool = False, real_weight_layers=()):
         self.word_bits = word_bits
         self.keep = []           # device tensors referenced by the descriptors
         self.scales = []
@@ -93,15 +107,21 @@ class GpuModel:
         for l, (W, r) in enumerate(zip(Ws, biases)):
             N, K = W.shape
             Wd = to_dev(W.astype(np.float32))
-            Wp, sc = pack_weights(Wd, word_bits)
-            scale = sc.expand(N).contiguous()           # broadcast the per-layer scalar to [N] (a copy, no arithmetic)
             bias = to_dev(r.astype(np.float32))
             name = hidden_act if isinstance(hidden_act, str) else (hidden_act[l] if l < len(Ws) - 1 else None)
             act = bnn.BNN_ACT_LOGSOFTMAX if l == len(Ws) - 1 else bnn.ACT_BY_NAME[name]
-            self.keep += [Wp, scale, bias]
-            self.scales.append(sc)
-            descs.append(dict(K=K, N=N, act=act, word_bits=word_bits, x_is_binary=binary,
-                              Wp=ptr(Wp), scale=ptr(scale), bias=ptr(bias)))
+            if l in real_weight_layers:                 # the layer keeps its real-valued weights, fp32 [N][K]
+                self.keep += [Wd, bias]
+                self.scales.append(None)
+                descs.append(dict(K=K, N=N, act=act, word_bits=word_bits, x_is_binary=binary, w_is_real=1,
+                                  Wp=ptr(Wd), scale=0, bias=ptr(bias)))
+            else:
+                Wp, sc = pack_weights(Wd, word_bits)
+                scale = sc.expand(N).contiguous()       # broadcast the per-layer scalar to [N] (a copy, no arithmetic)
+                self.keep += [Wp, scale, bias]
+                self.scales.append(sc)
+                descs.append(dict(K=K, N=N, act=act, word_bits=word_bits, x_is_binary=binary,
+                                  Wp=ptr(Wp), scale=ptr(scale), bias=ptr(bias)))
             binary = (2 if name == "step01" else 1) if act == bnn.BNN_ACT_SIGN else 0
             del Wd
         self.descs = descs

@@ -254,6 +254,110 @@ def test_realx_layer_matrix_cores(G, bnn, oracle, M, K, N, act, wb):
             2e-6 * float(np.max(np.abs(z64))) + 1e-30
 
 
+# ----------------------------------------------------------------------------- real x real (layers that keep their weights)
+
+def _rand_realw(seed, M, K, N):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    W = (rng.uniform(-1, 1, size=(N, K)) * np.sqrt(3.0 / K)).astype(np.float32)
+    bias = (rng.standard_normal(N) * 0.5).astype(np.float32)
+    return X, W, bias
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax", "sigmoid"])
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (64, 440, 512), (130, 440, 200), (17, 16, 257),
+                                   (37, 2048, 300), (50, 100, 3307), (33, 12, 70), (300, 452, 260)])
+def test_realw_layer(G, bnn, oracle, M, K, N, act, wb):
+    """Real-valued weights on the vector ALU: the same ascending-k chain of fused multiply-adds as the oracle's, so fp32
+    outputs are identical bits (K a multiple of 4 takes the LDS-staged kernel, any other K the element-load one)."""
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 2)
+    try:
+        X, W, bias = _rand_realw(M * 7 + K + N, M, K, N)
+        Y = G.layer_realw(G.to_dev(X), G.to_dev(W), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb)
+        want = oracle.layer_realw(X, W, bias, act, wb)
+        if act == "sign":
+            assert np.array_equal(G.words_to_host(Y, wb), want)
+        elif act in ("logsoftmax", "sigmoid"):
+            _close(Y.cpu().numpy(), want, act)
+        else:
+            assert np.array_equal(Y.cpu().numpy(), want), "same order of fp32 operations on both sides: identical bits"
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
+
+
+def test_realw_layer_with_pm1_weights_equals_binary_weight_layer(G, bnn, oracle):
+    """Every weight +1 or -1 and no scale: the real-weight layer and the binary-weight layer give the same bits."""
+    M, K, N = 70, 440, 300
+    X, W, _, bias = _rand_layer(5, M, K, N)
+    Wpm = np.where(W > 0, 1.0, -1.0).astype(np.float32)
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 2)
+    try:
+        a = G.layer_realw(G.to_dev(X), G.to_dev(Wpm), G.to_dev(bias), K, N, bnn.BNN_ACT_LINEAR, 32).cpu().numpy()
+        b = G.layer_realx(G.to_dev(X), G.to_dev(oracle.pack_sign(W, 32)), None, G.to_dev(bias), K, N, bnn.BNN_ACT_LINEAR, 32).cpu().numpy()
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("act", ["linear", "hardtanh", "logsoftmax", "sign", "sigmoid"])
+@pytest.mark.parametrize("M,K,N", [(128, 16, 1), (130, 440, 200), (300, 33, 65), (257, 100, 3307), (256, 2048, 384),
+                                   (1000, 2048, 2048), (513, 1023, 129)])
+def test_realw_layer_matrix_cores(G, bnn, oracle, M, K, N, act):
+    """BNN_OPT_REALX_F32_MFMA = 1, 128 frames or more: fp32 outputs come from the fp32 matrix-core kernel (its own order
+    of additions): within the tolerance of the oracle's fp32 chain and of the fp64 value.  Sign bits stay exact."""
+    X, W, bias = _rand_realw(M * 11 + K + N, M, K, N)
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 1)
+    try:
+        Y = G.layer_realw(G.to_dev(X), G.to_dev(W), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], 32)
+        torch.cuda.synchronize()
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
+    want = oracle.layer_realw(X, W, bias, act, 32)
+    if act == "sign":
+        assert np.array_equal(G.words_to_host(Y, 32), want)
+        return
+    got = Y.cpu().numpy()
+    _close(got, want, act)
+    if act in ("linear", "hardtanh"):
+        _, acc64 = oracle.realw_acc(X, W)
+        z64 = oracle.affine_f64(acc64, None, bias)
+        _close(got, np.clip(z64, -1.0, 1.0) if act == "hardtanh" else z64, act + " fp64 value")
+        if act == "linear":
+            assert float(np.max(np.abs(got.astype(np.float64) - z64))) <= 2e-6 * float(np.max(np.abs(z64))) + 1e-30
+
+
+def test_realw_logsoftmax_default_uses_matrix_cores_within_tolerance(G, bnn, oracle):
+    """Default options, the paper's Softmax layer shape: log-posteriors within tolerance of the oracle's."""
+    M, K, N = 300, 2048, 3400
+    X, W, bias = _rand_realw(99, M, K, N)
+    X = (1.0 / (1.0 + np.exp(-X))).astype(np.float32)      # the layer reads Sigmoid outputs (Table 2)
+    got = G.layer_realw(G.to_dev(X), G.to_dev(W), G.to_dev(bias), K, N, bnn.BNN_ACT_LOGSOFTMAX, 32).cpu().numpy()
+    _close(got, oracle.layer_realw(X, W, bias, "logsoftmax", 32), "logsoftmax")
+    assert np.allclose(np.exp(got.astype(np.float64)).sum(1), 1.0, atol=1e-4)
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("M,K", [(1, 1), (5, 31), (7, 64), (33, 65), (64, 2048), (100, 3307)])
+def test_unpack_activations(G, bnn, oracle, M, K, wb):
+    rng = np.random.default_rng(M + K)
+    words = oracle.pack_sign(rng.standard_normal((M, K)).astype(np.float32), wb)
+    for zero_one in (False, True):
+        got = G.unpack_activations(G.to_dev(words), K, wb, zero_one).cpu().numpy()
+        assert np.array_equal(got, oracle.bits_to_real(words, K, wb, zero_one))
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+def test_forward_real_weight_layers_after_binary_layers(G, bnn, oracle, wb):
+    """Real-weight layers in every position: reading features, Sign bits, (0, 1) bits and Sigmoid outputs."""
+    cfg = workloads.NetConfig(12, "mixed real/binary weights", (40, 96, 70, 130, 65, 50), 37,
+                              ("sigmoid", "sign", "step01", "sigmoid"), wb, real_weight_layers=(0, 2, 3, 4))
+    _net_parity(G, bnn, oracle, cfg, cfg.M, form="definition")
+    cfg = workloads.NetConfig(13, "real weights after sign", (33, 64, 64, 21), 150, ("sign", "step01"), wb,
+                              real_weight_layers=(1, 2))
+    _net_parity(G, bnn, oracle, cfg, cfg.M, form="definition")
+
+
 def test_realx_against_fp64_shadow(G, bnn, oracle):
     """The fp32 product also stays within the tolerance of the fp64 value of the same sum."""
     M, K, N, wb = 64, 440, 256, 32
@@ -344,10 +448,10 @@ def _net_parity(G, bnn, oracle, cfg, M, frames=None, form="xor", arm=None):
     """GPU forward on M frames of cfg; oracle on `frames` (indices) or on all of them."""
     Ws, bs = workloads.make_net_params(cfg)
     X = workloads.make_frames(cfg, M)
-    model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
-    layers = oracle.make_layers(Ws, bs, cfg.hidden_act, cfg.word_bits)
+    model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits, real_weight_layers=cfg.real_weight_layers)
+    layers = oracle.make_layers(Ws, bs, cfg.hidden_act, cfg.word_bits, real_weight_layers=cfg.real_weight_layers)
     for ly, sc in zip(layers, model.scales):
-        assert sc.cpu().numpy()[0] == ly.scale[0]
+        assert (sc is None and ly.scale is None) or sc.cpu().numpy()[0] == ly.scale[0]
     if arm is not None:
         bnn.bnn_set_option(bnn.BNN_OPT_BINX_ARM, arm)
     try:
@@ -386,7 +490,8 @@ def test_forward_config1_layer_by_layer_bits(G, bnn, oracle):
         h = Y
 
 
-@pytest.mark.parametrize("cfg_id,M", [(2, 96), (3, 300), (4, 200), (6, 1100), (7, 1030), (8, 300), (8, 1280), (9, 96), (9, 1100)])
+@pytest.mark.parametrize("cfg_id,M", [(2, 96), (3, 300), (4, 200), (6, 1100), (7, 1030), (8, 300), (8, 1280), (9, 96), (9, 1100),
+                                      (10, 96), (10, 1100)])
 def test_forward_configs_reduced_batch_full_compare(G, bnn, oracle, cfg_id, M):
     cfg = workloads.CONFIGS[cfg_id]
     _net_parity(G, bnn, oracle, cfg, M)
