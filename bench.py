@@ -64,17 +64,17 @@ def gemm_sweep(args, bnn, workloads, G, torch) -> int:
 
 
 def all_configs(args, bnn, workloads, G, torch) -> int:
-    """bnn_forward on Configs 1-4 and the paper-shaped Configs 6-7 (Config 5 is --gemm-sweep): one JSON line each."""
+    """bnn_forward on Configs 1-4 and 6-10 (Config 5 is --gemm-sweep): one JSON line each."""
     for kv in args.opt:
         key, val = kv.split("=")
         bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
-    for cid in (1, 2, 3, 4, 6, 7, 8, 9):
+    for cid in (1, 2, 3, 4, 6, 7, 8, 9, 10):
         cfg = workloads.CONFIGS[cid]
         Ws, bs = workloads.make_net_params(cfg)
-        model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
+        model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits, real_weight_layers=cfg.real_weight_layers)
         X = G.to_dev(workloads.make_frames(cfg))
         out = torch.empty((cfg.M, model.N_out), dtype=torch.float32, device=G.DEV)
-        steps = 200 if cid == 1 else (10 if cid in (4, 9) else 50)
+        steps = 200 if cid == 1 else (10 if cid in (4, 9, 10) else 50)
         for _ in range(3):
             model.forward(X, out)
         torch.cuda.synchronize()

@@ -102,6 +102,28 @@ void launch_realx_tm(const float* X, const uint32_t* Wp, const float* scale, con
     else launch_realx_tm_b<TM, false>(X, Wp, scale, bias, M, K, N, w32, act, Y, yw32, st);
 }
 
+// The fp32 matrix-core kernel runs one workgroup per CU: two that share a CU evict each other's operand rows from
+// the L1 (measured: 1.06 ms against 0.54 ms on 432 workgroups).  Its registers would admit two, so the launch asks
+// for dynamic LDS that it never touches, enough that two workgroups do not fit the CU's 160 KiB together.
+constexpr unsigned kF32MfmaPadLds = 48 * 1024;   // + 34 KiB of static LDS > 80 KiB
+template <int ACT, bool VEC, bool WREAL>
+void launch_f32_mfma(dim3 grid, dim3 block, hipStream_t st, const float* X, const void* W, const float* scale,
+                     const float* bias, int M, int K, int N, int w32, float* Y) {
+    const unsigned pad = (size_t)grid.x * grid.y > 256 ? kF32MfmaPadLds : 0;   // up to 256 workgroups get a CU each anyway
+    if (pad) {   // static + dynamic LDS above 64 KiB has to be allowed once per kernel and device
+        static std::atomic<uint64_t> allowed{0};
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        const uint64_t bit = 1ull << (dev & 63);
+        if (!(allowed.load() & bit)) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&realx_f32_mfma_kernel<ACT, VEC, WREAL>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)pad);
+            allowed.fetch_or(bit);
+        }
+    }
+    realx_f32_mfma_kernel<ACT, VEC, WREAL><<<grid, block, pad, st>>>(X, W, scale, bias, M, K, N, w32, Y);
+}
+
 void launch_log_softmax(float* Z, int M, int N, hipStream_t st) {
     const dim3 grid(M < 65536 ? M : 65536), block(256);
     const bool al = aligned(Z, 16);
@@ -125,14 +147,14 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
         const bool vec = (K % 16 == 0) && aligned(X, 16);
         float* Yf = static_cast<float*>(Y);
         if (act == BNN_ACT_HARDTANH) {
-            if (vec) realx_f32_mfma_kernel<ACT_HARDTANH, true><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
-            else realx_f32_mfma_kernel<ACT_HARDTANH, false><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+            if (vec) launch_f32_mfma<ACT_HARDTANH, true, false>(grid, block, st, X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+            else launch_f32_mfma<ACT_HARDTANH, false, false>(grid, block, st, X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
         } else if (act == BNN_ACT_SIGMOID) {
-            if (vec) realx_f32_mfma_kernel<ACT_SIGMOID, true><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
-            else realx_f32_mfma_kernel<ACT_SIGMOID, false><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+            if (vec) launch_f32_mfma<ACT_SIGMOID, true, false>(grid, block, st, X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+            else launch_f32_mfma<ACT_SIGMOID, false, false>(grid, block, st, X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
         } else {
-            if (vec) realx_f32_mfma_kernel<ACT_LINEAR, true><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
-            else realx_f32_mfma_kernel<ACT_LINEAR, false><<<grid, block, 0, st>>>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+            if (vec) launch_f32_mfma<ACT_LINEAR, true, false>(grid, block, st, X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
+            else launch_f32_mfma<ACT_LINEAR, false, false>(grid, block, st, X, W, scale, bias, (int)M, (int)K, (int)N, w32, Yf);
         }
         if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(Yf, (int)M, (int)N, st);
         return launch_status();
@@ -160,9 +182,9 @@ template <int ACT>
 void launch_realw_mfma(const float* X, const float* W, const float* bias, int M, int K, int N, float* Y, hipStream_t st) {
     const dim3 grid((unsigned)((M + 255) / 256), (unsigned)((N + 127) / 128)), block(256);
     if ((K % 16 == 0) && aligned(X, 16) && aligned(W, 16))
-        realx_f32_mfma_kernel<ACT, true, true><<<grid, block, 0, st>>>(X, W, nullptr, bias, M, K, N, 0, Y);
+        launch_f32_mfma<ACT, true, true>(grid, block, st, X, W, nullptr, bias, M, K, N, 0, Y);
     else
-        realx_f32_mfma_kernel<ACT, false, true><<<grid, block, 0, st>>>(X, W, nullptr, bias, M, K, N, 0, Y);
+        launch_f32_mfma<ACT, false, true>(grid, block, st, X, W, nullptr, bias, M, K, N, 0, Y);
 }
 
 // A layer with real-valued weights.  The matrix-core rule is the one of run_realx.

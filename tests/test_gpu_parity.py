@@ -555,6 +555,15 @@ def test_forward_config8_full_batch_sampled_frames(G, bnn, oracle):
     _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
 
 
+@pytest.mark.parametrize("cfg_id", [9, 10])
+def test_forward_sigmoid_topologies_full_batch_sampled_frames(G, bnn, oracle, cfg_id):
+    """(sigma, b, b, b, b, sigma, delta) at the benchmark's size, with binary (9) and real-valued (10) outer weights."""
+    cfg = workloads.CONFIGS[cfg_id]
+    frames = np.unique(np.concatenate([np.arange(0, 8), np.arange(cfg.M - 8, cfg.M),
+                                       np.random.default_rng(6).integers(0, cfg.M, 32)]))
+    _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
+
+
 def test_forward_config4_full_batch_sampled_frames(G, bnn, oracle):
     cfg = workloads.CONFIGS[4]
     frames = np.unique(np.concatenate([np.arange(0, 8), np.arange(cfg.M - 8, cfg.M),
