@@ -78,6 +78,47 @@ def test_layer_argument_validation(bnn):
     assert _status(bnn.bnn_layer_binw_binx_arm, P, Q, 0, 0, 4, 64, 64, S, 32, R, 7, 0) == bnn.BNN_EINVAL
 
 
+def test_real_weight_layer_argument_validation(bnn):
+    S, L = bnn.BNN_ACT_SIGN, bnn.BNN_ACT_LINEAR
+    fn = bnn.bnn_layer_realw
+    assert _status(fn, 0, Q, 0, 4, 64, 64, L, 32, R, 0) == bnn.BNN_EINVAL            # null X
+    assert _status(fn, P, 0, 0, 4, 64, 64, L, 32, R, 0) == bnn.BNN_EINVAL            # null W
+    assert _status(fn, P, Q, 0, 4, 64, 64, L, 32, 0, 0) == bnn.BNN_EINVAL            # null Y
+    assert _status(fn, P, Q, 0, -1, 64, 64, L, 32, R, 0) == bnn.BNN_ESHAPE           # M < 0
+    assert _status(fn, P, Q, 0, 4, 0, 64, L, 32, R, 0) == bnn.BNN_ESHAPE             # K = 0
+    assert _status(fn, P, Q, 0, 4, 64, 64, S, 48, R, 0) == bnn.BNN_ESHAPE            # word_bits of the Sign output
+    assert _status(fn, P, Q, 0, 4, 64, 64, bnn.BNN_ACT_RAW_I32, 32, R, 0) == bnn.BNN_EINVAL
+    assert _status(fn, P, Q + 2, 0, 4, 64, 64, L, 32, R, 0) == bnn.BNN_EALIGN        # fp32 weights at 2 mod 4
+    assert _status(fn, P, Q, 0, 4, 64, 64, L, 32, Q + 64 * 64 * 4 - 4, 0) == bnn.BNN_EINVAL   # Y overlaps the fp32 weights
+    assert bnn.bnn_layer_realw(0, 0, 0, 0, 64, 64, L, 32, 0, 0) == 0                 # M = 0: nothing to do
+    un = bnn.bnn_unpack_activations
+    assert _status(un, 0, 4, 64, 32, 0, R, 0) == bnn.BNN_EINVAL                      # null Xp
+    assert _status(un, P, 4, 64, 32, 0, 0, 0) == bnn.BNN_EINVAL                      # null X
+    assert _status(un, P, 4, 64, 32, 2, R, 0) == bnn.BNN_EINVAL                      # zero_one not 0 or 1
+    assert _status(un, P, 4, 0, 32, 0, R, 0) == bnn.BNN_ESHAPE
+    assert _status(un, P, 4, 64, 16, 0, R, 0) == bnn.BNN_ESHAPE
+    assert _status(un, P + 4, 4, 64, 64, 0, R, 0) == bnn.BNN_EALIGN
+    assert _status(un, P, 4, 64, 32, 0, P + 8, 0) == bnn.BNN_EINVAL                  # output overlaps the bits
+    assert un(0, 0, 64, 32, 0, 0, 0) == 0
+
+
+def test_real_weight_layers_in_a_chain(bnn):
+    S, G, Z = bnn.BNN_ACT_SIGN, bnn.BNN_ACT_SIGMOID, bnn.BNN_ACT_LOGSOFTMAX
+    d = _chain(bnn, (440, 2048, 2048, 3400), (G, S, Z))
+    d[0]["w_is_real"] = 1
+    d[2]["w_is_real"] = 1          # reads the bits of layer 2: needs the third buffer, 4096 x 2048 fp32
+    arr = bnn.make_layer_array(d)
+    assert bnn.bnn_forward_workspace_bytes(arr, 3, 4096) == 2 * 4096 * 2048 * 4 + 4096 * 2048 * 4
+    d[2]["w_is_real"] = 0
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4
+    d[2]["w_is_real"] = 2
+    assert _status(bnn.bnn_forward, bnn.make_layer_array(d), 3, P, 8, R, 0x4000000, 1 << 26, 0) == bnn.BNN_EINVAL
+    d[2]["w_is_real"] = 1
+    d[2]["scale"] = Q               # a real-weight layer has no scale
+    assert _status(bnn.bnn_forward, bnn.make_layer_array(d), 3, P, 8, R, 0x4000000, 1 << 26, 0) == bnn.BNN_EINVAL
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 0
+
+
 def test_pack_argument_validation(bnn):
     assert _status(bnn.bnn_pack_weights, 0, 4, 64, 32, Q, 0, 0) == bnn.BNN_EINVAL
     assert _status(bnn.bnn_pack_weights, P, 0, 64, 32, Q, 0, 0) == bnn.BNN_ESHAPE
