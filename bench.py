@@ -68,7 +68,10 @@ def all_configs(args, bnn, workloads, G, torch) -> int:
     for kv in args.opt:
         key, val = kv.split("=")
         bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
+    only = [int(v) for v in args.only.split(",")] if args.only else None
     for cid in (1, 2, 3, 4, 6, 7, 8, 9, 10):
+        if only and cid not in only:
+            continue
         cfg = workloads.CONFIGS[cid]
         Ws, bs = workloads.make_net_params(cfg)
         model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits, real_weight_layers=cfg.real_weight_layers)
@@ -102,6 +105,7 @@ def main() -> int:
                     help="arm of the binary product: 4-bit-float MFMA (default), int8 MFMA, or XOR/popcount on the vector ALU")
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
     ap.add_argument("--copy-calibration", action="store_true", help="run 10 plain 256 MiB device copies (counter calibration)")
+    ap.add_argument("--only", default="", help="with --all-configs: comma-separated configuration numbers to run")
     ap.add_argument("--all-configs", action="store_true",
                     help="time bnn_forward on Configs 1-4 instead (one JSON line each; the default run is Config 3 only)")
     ap.add_argument("--gemm-sweep", action="store_true", help="time the isolated binary GEMM sweep (Config 5) instead")
