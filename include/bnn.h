@@ -91,10 +91,14 @@ typedef enum bnn_option {
                                    (default: nothing follows them), 1 = LINEAR, HARDTANH and SIGMOID layers too, 2 =
                                    none.  A deep hard-tanh network amplifies the different rounding from layer to layer
                                    (measured: 8e-4 of the output scale after 7 layers of 2048 units), hence the default */
-    BNN_OPT_MFMA32_PIPELINE = 9  /* operand fetch of the 32x32x64 kernel on 16-byte aligned rows with K % 512 == 0:
+    BNN_OPT_MFMA32_PIPELINE = 9, /* operand fetch of the 32x32x64 kernel on 16-byte aligned rows with K % 512 == 0:
                                    0 or 1 = two register sets, the fetch of the next piece of K pinned ahead of
                                    the products of the current one (default), 2 = one set, order left to the
                                    compiler (kept for comparison)                                                */
+    BNN_OPT_STREAM_MAX_FRAMES = 12  /* batches of at most this many frames (streaming; the paper's motivation is on-device,
+                                       frame-by-frame inference) run every layer on the vector-ALU kernels with 1 or 2 frames
+                                       per workgroup, so that a layer is spread over the whole chip and takes one pass
+                                       over its weight rows; 0 = never.  Default 64.  Same results either way.          */
 } bnn_option;
 
 /* One layer of a network for bnn_forward.  HOST struct; the three pointers are DEVICE pointers. */

@@ -35,6 +35,7 @@ std::atomic<int> g_mfma32_wm{0};
 std::atomic<int> g_mfma32_pipeline{0};
 std::atomic<int> g_realx_f32_mfma{0};
 std::atomic<int> g_mfma32_xcd_order{0};
+std::atomic<int> g_stream_max_frames{64};
 
 inline bool word_bits_ok(int wb) { return wb == 32 || wb == 64; }
 inline int64_t words_per_row(int64_t K, int wb) { return (K + wb - 1) / wb; }
@@ -159,7 +160,12 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
         if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(Yf, (int)M, (int)N, st);
         return launch_status();
     }
-    switch (g_realx_tm.load()) {
+    // batches of a few frames (streaming): 1 or 2 frames per workgroup spread the layer over the chip
+    const int tm = M <= g_stream_max_frames.load() ? (M <= 16 ? 1 : 2) : g_realx_tm.load();
+    switch (tm) {
+        case 1: launch_realx_tm<1>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
+        case 2: launch_realx_tm<2>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
+        case 4: launch_realx_tm<4>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
         case 8: launch_realx_tm<8>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
         case 32: launch_realx_tm<32>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
         default: launch_realx_tm<16>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
@@ -168,14 +174,23 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
     return launch_status();
 }
 
+template <int TM, int ACT>
+void launch_realw_valu_tm(const float* X, const float* W, const float* bias, int M, int K, int N, void* Y, int yw32,
+                          hipStream_t st) {
+    const dim3 grid((M + TM - 1) / TM, (N + 255) / 256), block(256);
+    if ((K & 3) == 0 && aligned(X, 16) && aligned(W, 16))
+        realw_valu_kernel<TM, ACT><<<grid, block, 0, st>>>(X, W, bias, M, K, N, Y, yw32);
+    else
+        realw_valu_simple_kernel<TM, ACT><<<grid, block, 0, st>>>(X, W, bias, M, K, N, Y, yw32);
+}
+
+// batches of a few frames (streaming): 2 frames per workgroup, so that the layer is spread over ceil(M / 2) x N / 256
+// workgroups; otherwise 16
 template <int ACT>
 void launch_realw_valu(const float* X, const float* W, const float* bias, int M, int K, int N, void* Y, int yw32,
                        hipStream_t st) {
-    const dim3 grid((M + kRealwTM - 1) / kRealwTM, (N + 255) / 256), block(256);
-    if ((K & 3) == 0 && aligned(X, 16) && aligned(W, 16))
-        realw_valu_kernel<ACT><<<grid, block, 0, st>>>(X, W, bias, M, K, N, Y, yw32);
-    else
-        realw_valu_simple_kernel<ACT><<<grid, block, 0, st>>>(X, W, bias, M, K, N, Y, yw32);
+    if (M <= g_stream_max_frames.load()) launch_realw_valu_tm<2, ACT>(X, W, bias, M, K, N, Y, yw32, st);
+    else launch_realw_valu_tm<16, ACT>(X, W, bias, M, K, N, Y, yw32, st);
 }
 
 template <int ACT>
@@ -219,25 +234,25 @@ int run_unpack(const void* Xp, int64_t M, int64_t K, int wb, int zero_one, float
     return launch_status();
 }
 
-template <int TM, bool VEC4>
+template <int TM, bool VEC4, bool X01 = false>
 void launch_binx_valu_tm(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K,
                          int N, int w32, int act, void* Y, int yw32, hipStream_t st) {
     const dim3 grid((M + TM - 1) / TM, (N + 255) / 256), block(256);
     switch (act) {
         case BNN_ACT_RAW_I32:
-            binx_valu_kernel<TM, ACT_RAW_I32, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_valu_kernel<TM, ACT_RAW_I32, VEC4, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         case BNN_ACT_SIGN:
-            binx_valu_kernel<TM, ACT_SIGN, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_valu_kernel<TM, ACT_SIGN, VEC4, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         case BNN_ACT_HARDTANH:
-            binx_valu_kernel<TM, ACT_HARDTANH, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_valu_kernel<TM, ACT_HARDTANH, VEC4, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         case BNN_ACT_SIGMOID:
-            binx_valu_kernel<TM, ACT_SIGMOID, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_valu_kernel<TM, ACT_SIGMOID, VEC4, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
         default:
-            binx_valu_kernel<TM, ACT_LINEAR, VEC4><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
+            binx_valu_kernel<TM, ACT_LINEAR, VEC4, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32);
             break;
     }
 }
@@ -326,17 +341,39 @@ void launch_binx_mfma_i8(const uint32_t* Xp, const uint32_t* Wp, const float* sc
 int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K, int64_t N,
              int act, int wb, void* Y, int arm, hipStream_t st, bool x01 = false) {
     if (M == 0) return BNN_OK;
+    const bool stream = arm == BNN_ARM_AUTO && M <= g_stream_max_frames.load();
     if (arm == BNN_ARM_AUTO) arm = g_default_arm.load();
-    if (x01) arm = BNN_ARM_MFMA;   // the 0/1 reading of the input bits exists on the 32x32x64 kernel only
+    if (x01) arm = BNN_ARM_MFMA;   // large batches: the 0/1 reading of the input bits exists on the 32x32x64 kernel only
     const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
     const uint32_t* A = static_cast<const uint32_t*>(Xp);
     const uint32_t* B = static_cast<const uint32_t*>(Wp);
     const bool rows16 = (w32 % 4 == 0) && aligned(Xp, 16) && aligned(Wp, 16);
     const int Mi = (int)M, Ki = (int)K, Ni = (int)N;
-    if (arm == BNN_ARM_VALU_XOR) {
+    if (stream) {
+        // Batches of a few frames (streaming): the matrix-core tiles would be nearly empty and a workgroup would
+        // still walk all of K for its 64 or 128 rows.  The vector-ALU kernel with 1 or 2 frames per workgroup spreads
+        // the layer over ceil(M / TM) x N / 256 workgroups, each of which is done after one pass over its weight rows.
+        auto go = [&](auto tmc, auto vec, auto z1) {
+            launch_binx_valu_tm<decltype(tmc)::value, decltype(vec)::value, decltype(z1)::value>(A, B, scale, bias, Mi, Ki, Ni, w32,
+                                                                                                act, Y, yw32, st);
+        };
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
+        const bool one = M <= 16;
+        if (rows16) {
+            if (x01) { if (one) go(I1{}, std::true_type{}, std::true_type{}); else go(I2{}, std::true_type{}, std::true_type{}); }
+            else { if (one) go(I1{}, std::true_type{}, std::false_type{}); else go(I2{}, std::true_type{}, std::false_type{}); }
+        } else {
+            if (x01) { if (one) go(I1{}, std::false_type{}, std::true_type{}); else go(I2{}, std::false_type{}, std::true_type{}); }
+            else { if (one) go(I1{}, std::false_type{}, std::false_type{}); else go(I2{}, std::false_type{}, std::false_type{}); }
+        }
+    } else if (arm == BNN_ARM_VALU_XOR) {
         const int tm = g_binx_valu_tm.load();
         if (rows16) {
-            if (tm == 8) launch_binx_valu_tm<8, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            if (tm == 1) launch_binx_valu_tm<1, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else if (tm == 2) launch_binx_valu_tm<2, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else if (tm == 4) launch_binx_valu_tm<4, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else if (tm == 8) launch_binx_valu_tm<8, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
             else if (tm == 32) launch_binx_valu_tm<32, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
             else launch_binx_valu_tm<16, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         } else {
@@ -518,11 +555,15 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
             g_default_arm.store(value);
             return BNN_OK;
         case BNN_OPT_REALX_TM:
-            if (value != 8 && value != 16 && value != 32) return BNN_EINVAL;
+            if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16 && value != 32) return BNN_EINVAL;
             g_realx_tm.store(value);
             return BNN_OK;
+        case BNN_OPT_STREAM_MAX_FRAMES:
+            if (value < 0 || value > 4096) return BNN_EINVAL;
+            g_stream_max_frames.store(value);
+            return BNN_OK;
         case BNN_OPT_BINX_VALU_TM:
-            if (value != 8 && value != 16 && value != 32) return BNN_EINVAL;
+            if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16 && value != 32) return BNN_EINVAL;
             g_binx_valu_tm.store(value);
             return BNN_OK;
         case BNN_OPT_MFMA_WM:
@@ -696,7 +737,7 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
             } else if (d.x_is_binary) {
                 rc = run_binx(in, d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o, BNN_ARM_AUTO, st,
                               d.x_is_binary == 2);
-            } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load()) {
+            } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load() && M > g_stream_max_frames.load()) {
                 rc = run_realx_sign_mfma(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
                                          o, st);
             } else {

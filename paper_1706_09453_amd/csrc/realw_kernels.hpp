@@ -13,23 +13,22 @@
 
 namespace bnn {
 
-constexpr int kRealwTM = 16;     // frames per workgroup
 constexpr int kRealwKC = 16;     // k per chunk
 constexpr int kRealwLD = 20;     // LDS row pitch in floats: 16-byte aligned rows, 8 consecutive lanes cover all 32 banks
 
-// Lanes <-> outputs n (4 waves x 64), TM = 16 frames per workgroup.  Per chunk of 16 k:
+// Lanes <-> outputs n (4 waves x 64), TM frames per workgroup.  Per chunk of 16 k:
 //   - the workgroup copies W[n0 .. n0+255][kc .. kc+15] to LDS with 16-byte loads (4 threads per row piece of 64
 //     bytes; fetched into registers before the products of the current chunk, stored after them: two LDS stages,
 //     one barrier per chunk), and a lane reads its own row back (4 x ds_read_b128);
 //   - lane l holds x[m][kc + (l mod 16)] for each frame (the same in each row of 16 lanes) and the fmac takes
 //     x[m][k] by the DPP row broadcast, as in realx_valu_kernel<., ., true>.
 // The k past the last whole chunk (fewer than 16) are done with element loads.
-// Grid: x = ceil(M / 16), y = ceil(N / 256).
-template <int ACT>
+// Grid: x = ceil(M / TM), y = ceil(N / 256).  TM = 16, or 2 for batches of a few frames.
+template <int TM, int ACT>
 __global__ __launch_bounds__(256) void realw_valu_kernel(const float* __restrict__ X, const float* __restrict__ W,
                                                          const float* __restrict__ bias, int M, int K, int N,
                                                          void* __restrict__ Y, int yw32) {
-    constexpr int TM = kRealwTM, KC = kRealwKC, LD = kRealwLD, KV = 1, NP = 256 * KC / 4 / 256;   // NP pieces of W per thread
+    constexpr int KC = kRealwKC, LD = kRealwLD, KV = 1, NP = 256 * KC / 4 / 256;   // NP pieces of W per thread
     __shared__ __attribute__((aligned(16))) float wt[2][256 * LD];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
@@ -128,12 +127,11 @@ __global__ __launch_bounds__(256) void realw_valu_kernel(const float* __restrict
 }
 
 // Any K: lanes <-> outputs n, a lane walks its own weight row, the frame value is a wave-uniform (scalar) load.
-// Grid: x = ceil(M / 16), y = ceil(N / 256).
-template <int ACT>
+// Grid: x = ceil(M / TM), y = ceil(N / 256).
+template <int TM, int ACT>
 __global__ __launch_bounds__(256) void realw_valu_simple_kernel(const float* __restrict__ X, const float* __restrict__ W,
                                                                 const float* __restrict__ bias, int M, int K, int N,
                                                                 void* __restrict__ Y, int yw32) {
-    constexpr int TM = kRealwTM;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     const int n0 = ((int)blockIdx.y * 4 + wave) * kWave;

@@ -202,7 +202,10 @@ __global__ __launch_bounds__(256) void realx_valu_kernel(const float* __restrict
 // dot[m][n] = K - 2 * sum_w popcount(x[m][w] XOR w[n][w]): v_xor_b32 with the frame word as SGPR
 // operand, then v_bcnt_u32_b32, whose second operand is the running count (the add is free).
 // VEC4: rows are 16-byte aligned and a multiple of 4 words long, so a lane fetches 4 words per load.
-template <int TM, int ACT, bool VEC4>
+// X01:  the input bits are read as 0/1 (paper Sec. 3.2): dot = 2 * sum_w popcount(x AND w) - sum_w popcount(x).
+// With TM = 1, 2 or 4 this is also the small-batch (streaming) kernel: ceil(M / TM) x N / 64 waves, each of which
+// walks whole weight rows, so a layer takes one memory round trip however few frames there are.
+template <int TM, int ACT, bool VEC4, bool X01 = false>
 __global__ __launch_bounds__(256) void binx_valu_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
                                                         const float* __restrict__ scale, const float* __restrict__ bias,
                                                         int M, int K, int N, int w32, void* __restrict__ Y, int yw32) {
@@ -219,25 +222,35 @@ __global__ __launch_bounds__(256) void binx_valu_kernel(const uint32_t* __restri
     for (int i = 0; i < TM; ++i) xr[i] = Xp + (size_t)(m0 + i < M ? m0 + i : M - 1) * w32;
 
     uint32_t cnt[TM];
+    int ones[TM];   // X01: popcount of the frame's own bits (wave-uniform)
 #pragma unroll
-    for (int i = 0; i < TM; ++i) cnt[i] = 0;
+    for (int i = 0; i < TM; ++i) cnt[i] = 0, ones[i] = 0;
 
+    auto step = [&](uint32_t b, int i, int kw) {
+        const uint32_t x = xr[i][kw];
+        if constexpr (X01) {
+            cnt[i] += __builtin_popcount(b & x);
+            ones[i] += __builtin_popcount(x);
+        } else {
+            cnt[i] += __builtin_popcount(b ^ x);
+        }
+    };
     if constexpr (VEC4) {
         for (int kw = 0; kw < w32; kw += 4) {
             const uint4 b = *reinterpret_cast<const uint4*>(wrow + kw);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                cnt[i] += __builtin_popcount(b.x ^ xr[i][kw + 0]);
-                cnt[i] += __builtin_popcount(b.y ^ xr[i][kw + 1]);
-                cnt[i] += __builtin_popcount(b.z ^ xr[i][kw + 2]);
-                cnt[i] += __builtin_popcount(b.w ^ xr[i][kw + 3]);
+                step(b.x, i, kw + 0);
+                step(b.y, i, kw + 1);
+                step(b.z, i, kw + 2);
+                step(b.w, i, kw + 3);
             }
         }
     } else {
         for (int kw = 0; kw < w32; ++kw) {
             const uint32_t b = wrow[kw];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) cnt[i] += __builtin_popcount(b ^ xr[i][kw]);
+            for (int i = 0; i < TM; ++i) step(b, i, kw);
         }
     }
 
@@ -245,7 +258,7 @@ __global__ __launch_bounds__(256) void binx_valu_kernel(const uint32_t* __restri
     int vi[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        vi[i] = K - 2 * (int)cnt[i];
+        vi[i] = X01 ? 2 * (int)cnt[i] - ones[i] : K - 2 * (int)cnt[i];
         v[i] = (float)vi[i];
     }
     epilogue_lanes_n<TM, ACT>(v, vi, scale, bias, m0, M, n0, n, N, Y, yw32);

@@ -26,8 +26,25 @@ def G():
 
 @pytest.fixture(scope="module")
 def bnn():
+    """The library with the small-batch (streaming) dispatch switched off, so that batches of a few frames exercise the
+    large-batch kernels too; the streaming tests switch it on themselves."""
     import paper_1706_09453_amd as b
-    return b
+    b.bnn_set_option(b.BNN_OPT_STREAM_MAX_FRAMES, 0)
+    yield b
+    b.bnn_set_option(b.BNN_OPT_STREAM_MAX_FRAMES, 64)
+
+
+class _streaming:
+    """Batches of at most `frames` frames take the streaming kernels for the duration of a test."""
+
+    def __init__(self, bnn, frames=64):
+        self.bnn, self.frames = bnn, frames
+
+    def __enter__(self):
+        self.bnn.bnn_set_option(self.bnn.BNN_OPT_STREAM_MAX_FRAMES, self.frames)
+
+    def __exit__(self, *exc):
+        self.bnn.bnn_set_option(self.bnn.BNN_OPT_STREAM_MAX_FRAMES, 0)
 
 
 def _close(got: np.ndarray, want: np.ndarray, what=""):
@@ -190,9 +207,60 @@ def test_binx01_layer(G, bnn, oracle, M, K, N, act, wb):
         assert np.array_equal(Y.cpu().numpy(), want)     # exact integer, then one fma: identical bits
 
 
+# ----------------------------------------------------------------------------- batches of a few frames (streaming)
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("act", ["raw", "sign", "linear", "logsoftmax", "sigmoid"])
+@pytest.mark.parametrize("x01", [False, True])
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (1, 2048, 2048), (2, 31, 5), (3, 440, 3307), (16, 2048, 300), (17, 33, 65),
+                                   (33, 1024, 200), (64, 2048, 512)])
+def test_streaming_binary_layer(G, bnn, oracle, M, K, N, act, x01, wb):
+    """Default arm, at most 64 frames: the vector-ALU kernel with 1 or 2 frames per workgroup; same bits as ever."""
+    aw, bw = _bin_operands(oracle, 11 * M + K + N, M, K, N, wb)
+    _, _, scale, bias = _rand_layer(M + N, 1, 1, N)
+    if act == "sigmoid":
+        scale = scale / np.float32(np.sqrt(K))
+    layer = G.layer_binx01 if x01 else G.layer_binx
+    with _streaming(bnn):
+        Y = layer(G.to_dev(aw), G.to_dev(bw), G.to_dev(scale), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], wb)
+        torch.cuda.synchronize()
+    if x01:
+        want = oracle.layer_binw_binx01(aw, bw, K, scale, bias, act, wb, form="and")
+    else:
+        want = oracle.layer_binw_binx(aw, bw, K, scale, bias, act, wb, form="xor")
+    if act == "sign":
+        assert np.array_equal(G.words_to_host(Y, wb), want)
+    elif act in ("logsoftmax", "sigmoid"):
+        _close(Y.cpu().numpy(), want, act)
+    else:
+        assert np.array_equal(Y.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("cfg_id", [1, 3, 8, 9, 10])
+@pytest.mark.parametrize("M", [1, 4, 16, 40, 64])
+def test_streaming_forward(G, bnn, oracle, cfg_id, M):
+    """bnn_forward on a few frames at a time (every layer on the streaming kernels), all of them compared."""
+    with _streaming(bnn):
+        _net_parity(G, bnn, oracle, workloads.CONFIGS[cfg_id], M)
+
+
+def test_streaming_forward_equals_large_batch_forward(G, bnn, oracle):
+    """The same 48 frames through the streaming kernels (16 at a time) and through the large-batch kernels: the
+    log-posteriors agree within the tolerance of the two log-Softmax kernels, their arg max exactly."""
+    cfg = workloads.CONFIGS[3]
+    Ws, bs = workloads.make_net_params(cfg)
+    model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
+    X = G.to_dev(workloads.make_frames(cfg, 48))
+    big = model.forward(X).cpu().numpy()
+    with _streaming(bnn):
+        small = np.concatenate([model.forward(X[i:i + 16].contiguous()).cpu().numpy() for i in range(0, 48, 16)])
+    _close(small, big, "streaming vs batch")
+    assert np.array_equal(small.argmax(1), big.argmax(1))
+
+
 # ----------------------------------------------------------------------------- real x binary
 
-@pytest.mark.parametrize("tm", [8, 16, 32])
+@pytest.mark.parametrize("tm", [1, 2, 4, 8, 16, 32])
 @pytest.mark.parametrize("wb", [32, 64])
 @pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax", "sigmoid"])
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (64, 440, 512), (130, 440, 200),
@@ -284,6 +352,23 @@ def test_realw_layer(G, bnn, oracle, M, K, N, act, wb):
             assert np.array_equal(Y.cpu().numpy(), want), "same order of fp32 operations on both sides: identical bits"
     finally:
         bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
+
+
+@pytest.mark.parametrize("act", ["sign", "linear", "logsoftmax", "sigmoid"])
+@pytest.mark.parametrize("M,K,N", [(1, 440, 2048), (2, 31, 5), (5, 16, 257), (16, 452, 260), (33, 2048, 300), (64, 100, 3307)])
+def test_streaming_real_weight_layer(G, bnn, oracle, M, K, N, act):
+    """At most 64 frames: the real-weight kernels with 2 frames per workgroup; the same ascending-k chain, identical bits."""
+    X, W, bias = _rand_realw(M * 13 + K + N, M, K, N)
+    with _streaming(bnn):
+        Y = G.layer_realw(G.to_dev(X), G.to_dev(W), G.to_dev(bias), K, N, bnn.ACT_BY_NAME[act], 32)
+        torch.cuda.synchronize()
+    want = oracle.layer_realw(X, W, bias, act, 32)
+    if act == "sign":
+        assert np.array_equal(G.words_to_host(Y, 32), want)
+    elif act in ("logsoftmax", "sigmoid"):
+        _close(Y.cpu().numpy(), want, act)
+    else:
+        assert np.array_equal(Y.cpu().numpy(), want)
 
 
 def test_realw_layer_with_pm1_weights_equals_binary_weight_layer(G, bnn, oracle):
