@@ -95,6 +95,36 @@ def all_configs(args, bnn, workloads, G, torch) -> int:
     return 0
 
 
+def streaming(args, bnn, workloads, G, torch) -> int:
+    """Latency of one bnn_forward on a few frames at a time (the paper's on-device use): one JSON line per batch size."""
+    for kv in args.opt:
+        key, val = kv.split("=")
+        bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
+    only = [int(v) for v in args.only.split(",")] if args.only else [3, 10]
+    for cid in only:
+        cfg = workloads.CONFIGS[cid]
+        Ws, bs = workloads.make_net_params(cfg)
+        model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits, real_weight_layers=cfg.real_weight_layers)
+        for M in (1, 4, 16, 64):
+            X = G.to_dev(workloads.make_frames(cfg, M))
+            out = torch.empty((M, model.N_out), dtype=torch.float32, device=G.DEV)
+            for _ in range(10):
+                model.forward(X, out)
+            torch.cuda.synchronize()
+            steps = 500
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                model.forward(X, out)
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) * 1e6 / steps
+            print(json.dumps({"workload": cfg.name.split(" M=")[0] + f" M={M} (streaming)", "batch_frames": M,
+                              "latency_us": round(us, 1), "frames_per_s": round(M / (us * 1e-6), 1),
+                              "kernel_launches": model.n_layers + 1}), flush=True)
+        del model, Ws, bs
+        torch.cuda.empty_cache()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +136,8 @@ def main() -> int:
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
     ap.add_argument("--copy-calibration", action="store_true", help="run 10 plain 256 MiB device copies (counter calibration)")
     ap.add_argument("--only", default="", help="with --all-configs: comma-separated configuration numbers to run")
+    ap.add_argument("--streaming", action="store_true",
+                    help="latency of bnn_forward on 1, 4, 16 and 64 frames (Configs 3 and 10, or --only)")
     ap.add_argument("--all-configs", action="store_true",
                     help="time bnn_forward on Configs 1-4 instead (one JSON line each; the default run is Config 3 only)")
     ap.add_argument("--gemm-sweep", action="store_true", help="time the isolated binary GEMM sweep (Config 5) instead")
@@ -128,6 +160,8 @@ def main() -> int:
         return gemm_sweep(args, bnn, workloads, G, torch)
     if args.all_configs:
         return all_configs(args, bnn, workloads, G, torch)
+    if args.streaming:
+        return streaming(args, bnn, workloads, G, torch)
     if args.copy_calibration:
         # A plain device-to-device copy of known size: the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by.
         nbytes = 256 << 20

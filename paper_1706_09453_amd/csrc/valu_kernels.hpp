@@ -236,7 +236,40 @@ __global__ __launch_bounds__(256) void binx_valu_kernel(const uint32_t* __restri
         }
     };
     if constexpr (VEC4) {
-        for (int kw = 0; kw < w32; kw += 4) {
+        // Pieces of 32 words (8 loads of 16 bytes per lane), the next piece in flight while the current one is counted:
+        // with few frames per workgroup the kernel's time is the number of memory round trips, and this makes it
+        // about one per 64 words instead of one per 4.
+        constexpr int PW = 32;
+        const int npieces = w32 / PW;
+        auto fetch = [&](uint4 (&b)[PW / 4], int p) {
+#pragma unroll
+            for (int q = 0; q < PW / 4; ++q) b[q] = *reinterpret_cast<const uint4*>(wrow + p * PW + 4 * q);
+        };
+        auto count = [&](const uint4 (&b)[PW / 4], int p) {
+#pragma unroll
+            for (int q = 0; q < PW / 4; ++q)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    step(b[q].x, i, p * PW + 4 * q + 0);
+                    step(b[q].y, i, p * PW + 4 * q + 1);
+                    step(b[q].z, i, p * PW + 4 * q + 2);
+                    step(b[q].w, i, p * PW + 4 * q + 3);
+                }
+        };
+        if (npieces > 0) {
+            uint4 ba[PW / 4], bb[PW / 4];
+            const int last = npieces - 1;
+            fetch(ba, 0);
+            int p = 0;
+            for (; p + 1 < npieces; p += 2) {   // every fetch unconditional (past the end: the last piece again, unused)
+                fetch(bb, p + 1);
+                count(ba, p);
+                fetch(ba, p + 2 < last ? p + 2 : last);
+                count(bb, p + 1);
+            }
+            if (p < npieces) count(ba, p);
+        }
+        for (int kw = npieces * PW; kw < w32; kw += 4) {
             const uint4 b = *reinterpret_cast<const uint4*>(wrow + kw);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
