@@ -25,7 +25,7 @@ using namespace bnn;
 
 // Tuning knobs (bnn_set_option).  Plain atomics: set from the host thread that benchmarks.
 std::atomic<int> g_default_arm{BNN_ARM_MFMA};
-std::atomic<int> g_realx_tm{16};
+std::atomic<int> g_realx_tm{0};
 std::atomic<int> g_binx_valu_tm{16};
 std::atomic<int> g_mfma_wm{4};
 std::atomic<int> g_realx_sign_mfma{1};
@@ -162,6 +162,20 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
     }
     // batches of a few frames (streaming): 1 or 2 frames per workgroup spread the layer over the chip
     const int tm = M <= g_stream_max_frames.load() ? (M <= 16 ? 1 : 2) : g_realx_tm.load();
+    if (tm == 0 && (K & 3) == 0 && aligned(X, 16)) {
+        // large batch, aligned rows: frames through LDS, every fma on three VGPRs
+        constexpr int TM = 16, TNN = 4;
+        const int Mi = (int)M, Ki = (int)K, Ni = (int)N;
+        const dim3 grid((unsigned)((M + TM - 1) / TM), (unsigned)((N + 256 * TNN - 1) / (256 * TNN))), block(256);
+        switch (act) {
+            case BNN_ACT_SIGN: realx_valu_lds_kernel<TM, TNN, ACT_SIGN><<<grid, block, 0, st>>>(X, W, scale, bias, Mi, Ki, Ni, w32, Y, yw32); break;
+            case BNN_ACT_HARDTANH: realx_valu_lds_kernel<TM, TNN, ACT_HARDTANH><<<grid, block, 0, st>>>(X, W, scale, bias, Mi, Ki, Ni, w32, Y, yw32); break;
+            case BNN_ACT_SIGMOID: realx_valu_lds_kernel<TM, TNN, ACT_SIGMOID><<<grid, block, 0, st>>>(X, W, scale, bias, Mi, Ki, Ni, w32, Y, yw32); break;
+            default: realx_valu_lds_kernel<TM, TNN, ACT_LINEAR><<<grid, block, 0, st>>>(X, W, scale, bias, Mi, Ki, Ni, w32, Y, yw32); break;
+        }
+        if (act == BNN_ACT_LOGSOFTMAX) launch_log_softmax(static_cast<float*>(Y), Mi, Ni, st);
+        return launch_status();
+    }
     switch (tm) {
         case 1: launch_realx_tm<1>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
         case 2: launch_realx_tm<2>(X, W, scale, bias, (int)M, (int)K, (int)N, w32, act, Y, yw32, st); break;
@@ -555,7 +569,7 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
             g_default_arm.store(value);
             return BNN_OK;
         case BNN_OPT_REALX_TM:
-            if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16 && value != 32) return BNN_EINVAL;
+            if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16 && value != 32) return BNN_EINVAL;
             g_realx_tm.store(value);
             return BNN_OK;
         case BNN_OPT_STREAM_MAX_FRAMES:

@@ -199,6 +199,116 @@ __global__ __launch_bounds__(256) void realx_valu_kernel(const float* __restrict
     epilogue_lanes_n<TM, ACT>(acc, dummy, scale, bias, m0, M, n0, n, N, Y, yw32);
 }
 
+// The same product for large batches, built so that every fma has three VGPR operands: on this chip such an fp32 fma
+// issues every 2.5-2.9 clocks when two or more waves share a SIMD, against 3.8-4.4 with an SGPR or DPP operand
+// (measured).  A workgroup stages x[16 frames][64 k] in LDS (two stages, one barrier per 64 k); a wave reads
+// x[m][k..k+3] with one broadcast ds_read_b128 (all lanes the same address) and uses each value for TNN = 4 outputs per
+// lane (n = n0 + lane + 64 j), so there is one LDS read per 16 fmas and the 2 sign-building instructions per k and
+// output are shared by 16 frames (TM = 16, TNN = 4; measured: 8 x 8 is 14 % slower, 16 x 2 7 %, 8 x 4 8 %).  Columns of a partial last chunk are staged as 0: fma(w, 0, acc) returns acc (an
+// accumulator that starts at +0 is never -0), so the sum over k < K is unchanged.
+// K a multiple of 4, X 16-byte aligned.  Grid: x = ceil(M / TM), y = ceil(N / (256 TNN)).
+constexpr int kRealxLdsKC = 64;
+template <int TM, int TNN, int ACT>
+__global__ __launch_bounds__(256, 3) void realx_valu_lds_kernel(const float* __restrict__ X, const uint32_t* __restrict__ Wp,
+                                                             const float* __restrict__ scale, const float* __restrict__ bias,
+                                                             int M, int K, int N, int w32, void* __restrict__ Y, int yw32) {
+    constexpr int KC = kRealxLdsKC;
+    static_assert(TM <= 16, "one 16-byte piece of the frame tile per thread");
+    __shared__ __attribute__((aligned(16))) float xs[2][TM][KC];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = lane_id();
+    const int n0 = ((int)blockIdx.y * 4 + wave) * (kWave * TNN);
+    const bool active = n0 < N;   // wave-uniform; an inactive wave still stages its share of x and meets the barriers
+    const int m0 = (int)blockIdx.x * TM;
+    const uint32_t* wrow[TNN];
+#pragma unroll
+    for (int j = 0; j < TNN; ++j) {
+        const int n = n0 + 64 * j + lane;
+        wrow[j] = Wp + (size_t)(n < N ? n : N - 1) * w32;
+    }
+    // this thread's piece of the x tile: row t / 16, floats 4 (t % 16) .. + 3 (threads past TM x 16 have none)
+    const int prow = (int)threadIdx.x >> 4, pcol = ((int)threadIdx.x & 15) * 4;
+    const bool has_piece = prow < TM;
+    const float* xsrc = X + (size_t)(m0 + prow < M ? m0 + prow : M - 1) * K + pcol;
+
+    float acc[TNN][TM];
+#pragma unroll
+    for (int j = 0; j < TNN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) acc[j][i] = 0.0f;
+
+    const int nchunks = (K + KC - 1) / KC;
+    const int wlast = w32 - 1;
+    float pre[4];
+    uint32_t wa[TNN][2], wb[TNN][2];
+    auto fetch = [&](uint32_t (&wv)[TNN][2], int c) {
+        const int k = c * KC + pcol;
+        const bool in = k < K;   // K % 4 == 0: all four values or none; past K re-read the row's first four, unused
+        const float4 t = *reinterpret_cast<const float4*>(in ? xsrc + c * KC : xsrc - pcol);
+        pre[0] = in ? t.x : 0.0f, pre[1] = in ? t.y : 0.0f, pre[2] = in ? t.z : 0.0f, pre[3] = in ? t.w : 0.0f;
+#pragma unroll
+        for (int j = 0; j < TNN; ++j) {   // words past the row's end belong to zero columns: any value will do
+            wv[j][0] = wrow[j][2 * c < wlast ? 2 * c : wlast];
+            wv[j][1] = wrow[j][2 * c + 1 < wlast ? 2 * c + 1 : wlast];
+        }
+    };
+    auto stash = [&](int stage) {
+        if (has_piece) *reinterpret_cast<float4*>(&xs[stage][prow][pcol]) = make_float4(pre[0], pre[1], pre[2], pre[3]);
+    };
+    auto products = [&](const uint32_t (&wv)[TNN][2], int stage) {
+        uint32_t inv[TNN][2];
+#pragma unroll
+        for (int j = 0; j < TNN; ++j) inv[j][0] = ~wv[j][0], inv[j][1] = ~wv[j][1];
+        // 8 steps of 4 k per weight word; the step loop stays a loop (fully unrolled, the three copies of a chunk are
+        // 50 KiB of code and no faster)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll 1
+        for (int q8 = 0; q8 < 8; ++q8) {
+            const int q = 8 * h + q8;
+            float xv[TM][4];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const float4 t = *reinterpret_cast<const float4*>(&xs[stage][i][4 * q]);
+                xv[i][0] = t.x, xv[i][1] = t.y, xv[i][2] = t.z, xv[i][3] = t.w;
+            }
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                float w[TNN];
+#pragma unroll
+                for (int j = 0; j < TNN; ++j) w[j] = pm1_from_inverted_bit(inv[j][h], 4 * q8 + kk);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TNN; ++j) acc[j][i] = __builtin_fmaf(w[j], xv[i][kk], acc[j][i]);
+            }
+        }
+    };
+
+    const int last = nchunks - 1;
+    fetch(wa, 0);
+    stash(0);
+    __syncthreads();
+    int c = 0;
+    for (; c + 1 < nchunks; c += 2) {   // every fetch unconditional (past the end: the last chunk again, unused)
+        fetch(wb, c + 1);
+        if (active) products(wa, 0);
+        stash(1);   // stage 1 was last read before the previous barrier
+        __syncthreads();
+        fetch(wa, c + 2 < last ? c + 2 : last);
+        if (active) products(wb, 1);
+        stash(0);
+        __syncthreads();
+    }
+    if (c < nchunks && active) products(wa, 0);
+    if (!active) return;
+    int dummy[TM];
+#pragma unroll
+    for (int j = 0; j < TNN; ++j)
+        if (n0 + 64 * j < N)
+            epilogue_lanes_n<TM, ACT>(acc[j], dummy, scale, bias, m0, M, n0 + 64 * j, n0 + 64 * j + lane, N, Y, yw32);
+}
+
 // dot[m][n] = K - 2 * sum_w popcount(x[m][w] XOR w[n][w]): v_xor_b32 with the frame word as SGPR
 // operand, then v_bcnt_u32_b32, whose second operand is the running count (the add is free).
 // VEC4: rows are 16-byte aligned and a multiple of 4 words long, so a lane fetches 4 words per load.

@@ -135,7 +135,7 @@ def test_set_option_validation(bnn):
     assert _status(bnn.bnn_set_option, bnn.BNN_OPT_REALX_TM, 5) == bnn.BNN_EINVAL
     assert _status(bnn.bnn_set_option, bnn.BNN_OPT_BINX_ARM, 0) == bnn.BNN_EINVAL
     assert bnn.bnn_set_option(bnn.BNN_OPT_BINX_ARM, bnn.BNN_ARM_MFMA) == 0
-    assert bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, 16) == 0
+    assert bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, 0) == 0
 
 
 def _chain(bnn, dims, acts, wb=32, first_binary=False, Wp=Q):

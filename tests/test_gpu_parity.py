@@ -260,7 +260,7 @@ def test_streaming_forward_equals_large_batch_forward(G, bnn, oracle):
 
 # ----------------------------------------------------------------------------- real x binary
 
-@pytest.mark.parametrize("tm", [1, 2, 4, 8, 16, 32])
+@pytest.mark.parametrize("tm", [0, 1, 2, 4, 8, 16, 32])
 @pytest.mark.parametrize("wb", [32, 64])
 @pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "logsoftmax", "sigmoid"])
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (64, 440, 512), (130, 440, 200),
@@ -285,7 +285,7 @@ def test_realx_layer(G, bnn, oracle, M, K, N, act, wb, tm):
             _close(got, want, act)
             assert np.array_equal(got, want), "same order of fp32 additions on both sides: identical bits"
     finally:
-        bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, 16)
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_TM, 0)
         bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
 
 
