@@ -188,23 +188,38 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
     return launch_status();
 }
 
-template <int TM, int ACT>
+template <int TM, int ACT, int KC>
 void launch_realw_valu_tm(const float* X, const float* W, const float* bias, int M, int K, int N, void* Y, int yw32,
                           hipStream_t st) {
     const dim3 grid((M + TM - 1) / TM, (N + 255) / 256), block(256);
-    if ((K & 3) == 0 && aligned(X, 16) && aligned(W, 16))
-        realw_valu_kernel<TM, ACT><<<grid, block, 0, st>>>(X, W, bias, M, K, N, Y, yw32);
-    else
+    if ((K & 3) == 0 && aligned(X, 16) && aligned(W, 16)) {
+        constexpr unsigned lds = realw_lds_bytes(KC);
+        if (lds > 64 * 1024) {   // LDS above 64 KiB has to be allowed once per kernel and device
+            static std::atomic<uint64_t> allowed{0};
+            int dev = 0;
+            (void)hipGetDevice(&dev);
+            const uint64_t bit = 1ull << (dev & 63);
+            if (!(allowed.load() & bit)) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&realw_valu_kernel<TM, ACT, KC>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                allowed.fetch_or(bit);
+            }
+        }
+        realw_valu_kernel<TM, ACT, KC><<<grid, block, lds, st>>>(X, W, bias, M, K, N, Y, yw32);
+    } else {
         realw_valu_simple_kernel<TM, ACT><<<grid, block, 0, st>>>(X, W, bias, M, K, N, Y, yw32);
+    }
 }
 
 // batches of a few frames (streaming): 2 frames per workgroup, so that the layer is spread over ceil(M / 2) x N / 256
-// workgroups; otherwise 16
+// workgroups (up to 16 frames with chunks of 64 k: fewer memory round trips, but 136 KiB of LDS, one workgroup per CU;
+// measured at 64 frames: 134 us with chunks of 16 k, 151 us with 64); otherwise 16 frames per workgroup
 template <int ACT>
 void launch_realw_valu(const float* X, const float* W, const float* bias, int M, int K, int N, void* Y, int yw32,
                        hipStream_t st) {
-    if (M <= g_stream_max_frames.load()) launch_realw_valu_tm<2, ACT>(X, W, bias, M, K, N, Y, yw32, st);
-    else launch_realw_valu_tm<16, ACT>(X, W, bias, M, K, N, Y, yw32, st);
+    if (M <= g_stream_max_frames.load() && M <= 16) launch_realw_valu_tm<2, ACT, 64>(X, W, bias, M, K, N, Y, yw32, st);
+    else if (M <= g_stream_max_frames.load()) launch_realw_valu_tm<2, ACT, 16>(X, W, bias, M, K, N, Y, yw32, st);
+    else launch_realw_valu_tm<16, ACT, 16>(X, W, bias, M, K, N, Y, yw32, st);
 }
 
 template <int ACT>
@@ -222,7 +237,14 @@ int run_realw(const float* X, const float* W, const float* bias, int64_t M, int6
     if (M == 0) return BNN_OK;
     const int yw32 = (int)row_w32(N, wb);
     const int f32_mfma = g_realx_f32_mfma.load();
-    if (act != BNN_ACT_SIGN && M >= 128 && (f32_mfma == 1 || (f32_mfma == 0 && act == BNN_ACT_LOGSOFTMAX))) {
+    if (act == BNN_ACT_LOGSOFTMAX && f32_mfma != 2 && M <= 64 && M <= g_stream_max_frames.load() && (K & 3) == 0 &&
+        aligned(X, 16) && aligned(W, 16)) {
+        // a few frames in front of the log-Softmax: K split over the lanes, so that N / 4 waves pull the weights
+        float* Yf = static_cast<float*>(Y);
+        const unsigned nb = (unsigned)((N + 15) / 16);
+        if (M <= 4) realw_gemv_kernel<4><<<dim3(nb, (unsigned)((M + 3) / 4)), 256, 0, st>>>(X, W, bias, (int)M, (int)K, (int)N, Yf);
+        else realw_gemv_kernel<8><<<dim3(nb, (unsigned)((M + 7) / 8)), 256, 0, st>>>(X, W, bias, (int)M, (int)K, (int)N, Yf);
+    } else if (act != BNN_ACT_SIGN && M >= 128 && (f32_mfma == 1 || (f32_mfma == 0 && act == BNN_ACT_LOGSOFTMAX))) {
         float* Yf = static_cast<float*>(Y);
         if (act == BNN_ACT_HARDTANH) launch_realw_mfma<ACT_HARDTANH>(X, W, bias, (int)M, (int)K, (int)N, Yf, st);
         else if (act == BNN_ACT_SIGMOID) launch_realw_mfma<ACT_SIGMOID>(X, W, bias, (int)M, (int)K, (int)N, Yf, st);
