@@ -84,7 +84,7 @@ __device__ __forceinline__ void fmac_row_bcast(float& acc, float x, float w) {
 // from the lane's weight bit (2 VALU ops per k, shared by the TM frames).
 //   BCAST  (K a multiple of 4, X 16-byte aligned): lane l holds x[m][kc + KV (l mod 16) .. + KV - 1] of a chunk of
 //          16 KV k (one load per frame and chunk, the same in each row of 16 lanes); the fmac takes x[m][k] by a
-//          row broadcast.  The k of the last, partial chunk go the way of !BCAST.
+//          row broadcast.
 //   !BCAST x[m][k] is a wave-uniform load and arrives through the scalar cache as an SGPR operand (61 % of the
 //          4-cycle VALU issue rate measured; BCAST reaches 73 % with TM = 16, where 16 of 18 instructions are fmas).
 // Grid: x = ceil(M / TM), y = ceil(N / 256) (4 waves x 64 outputs).
@@ -112,18 +112,21 @@ __global__ __launch_bounds__(256) void realx_valu_kernel(const float* __restrict
         // KV floats per lane and chunk: a chunk is 16 KV k; two register sets of TM x KV values
         constexpr int KV = TM <= 8 ? 4 : (TM <= 16 ? 2 : 1);
         constexpr int KC = 16 * KV;
-        const int nchunks = K / KC;
+        const int nchunks = K / KC;          // whole chunks
         const int lk = (lane & 15) * KV;
         constexpr int NW = KV == 4 ? 2 : 1;   // weight words a chunk touches
-        auto fetch = [&](float (&v)[TM][KV], uint32_t (&wv)[NW], int c) {
+        // fetch of chunk c; `in` = this lane's KV values lie inside the row (K is a multiple of 4, so they lie wholly
+        // inside or wholly past it); past it the row's first values and its last weight word are read again
+        auto fetch = [&](float (&v)[TM][KV], uint32_t (&wv)[NW], int c, bool in = true) {
+            const int wlast = w32 - 1;
             if constexpr (KV == 4) {
-                wv[0] = wrow[2 * c], wv[1] = wrow[2 * c + 1];
+                wv[0] = wrow[2 * c < wlast ? 2 * c : wlast], wv[1] = wrow[2 * c + 1 < wlast ? 2 * c + 1 : wlast];
             } else {
                 wv[0] = wrow[(c * KC) >> 5];
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const float* p = xr[i] + c * KC + lk;
+                const float* p = xr[i] + (in ? c * KC + lk : 0);
                 if constexpr (KV == 4) {
                     const float4 t = *reinterpret_cast<const float4*>(p);
                     v[i][0] = t.x, v[i][1] = t.y, v[i][2] = t.z, v[i][3] = t.w;
@@ -135,6 +138,14 @@ __global__ __launch_bounds__(256) void realx_valu_kernel(const float* __restrict
                 }
             }
         };
+        // The partial chunk after the whole ones (if any) is requested first and used last.  Its columns past K are taken
+        // as 0: fma(w, 0, acc) returns acc (an accumulator that starts at +0 is never -0), so the sum over k < K is
+        // unchanged.
+        const bool has_tail = nchunks * KC < K;
+        const bool tail_in = nchunks * KC + lk < K;
+        float vt[TM][KV];
+        uint32_t wt[NW];
+        fetch(vt, wt, has_tail ? nchunks : 0, has_tail && tail_in);
         auto products = [&](const float (&v)[TM][KV], const uint32_t (&wv)[NW], int c) {
             // bit (KV J + q) of inv[.] is the complement of the weight of the chunk's k number KV J + q
             uint32_t inv[NW];
@@ -168,10 +179,17 @@ __global__ __launch_bounds__(256) void realx_valu_kernel(const float* __restrict
             }
             if (c < nchunks) products(va, wa, c);
         }
-        for (int k = nchunks * KC; k < K; ++k) {   // fewer than 16 KV of them
-            const float w = pm1_from_inverted_bit(~wrow[k >> 5], k & 31);
+        if (has_tail) {
+            // The selects are vector instructions and their results feed DPP reads: every value passes through an
+            // "s_nop 1" of its own (two wait states), which the data dependence keeps between the two.
 #pragma unroll
-            for (int i = 0; i < TM; ++i) acc[i] = __builtin_fmaf(w, xr[i][k], acc[i]);
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int q = 0; q < KV; ++q) {
+                    vt[i][q] = tail_in ? vt[i][q] : 0.0f;
+                    asm volatile("s_nop 1" : "+v"(vt[i][q]));
+                }
+            products(vt, wt, nchunks);
         }
     } else {
         const int kfull = K >> 5;

@@ -38,12 +38,16 @@ def test_dpp_fmac_sources_are_not_fresh_valu_results(tmp_path):
             continue
         n_dpp += 1
         src = int(re.match(r"v_fmac_f32_dpp v\d+, v(\d+),", ins).group(1))
-        for back in range(1, 6):
+        states, back = 0, 1          # wait states between the instruction `back` places earlier and this one
+        while states < 5:
             prev = code[i - back]
-            if back <= 2 and prev.startswith("v_") and src in _written_vgprs(prev):
+            if states < 2 and prev.startswith("v_") and src in _written_vgprs(prev):
                 bad.append((prev, ins))
             dst = prev.split(",")[0]
             if re.search(r"\bexec", dst) and (prev.startswith("s_") or prev.startswith("v_cmpx")):
                 bad.append((prev, ins))
+            m = re.match(r"s_nop\s+(\d+)", prev)
+            states += int(m.group(1)) + 1 if m else 1
+            back += 1
     assert n_dpp > 0, "the kernel no longer uses the DPP fmac: delete this test"
     assert not bad, bad[:5]
