@@ -367,8 +367,9 @@ __global__ __launch_bounds__(256) void binx_valu_kernel(const uint32_t* __restri
         // Pieces of 32 words (8 loads of 16 bytes per lane), the next piece in flight while the current one is counted:
         // with few frames per workgroup the kernel's time is the number of memory round trips, and this makes it
         // about one per 64 words instead of one per 4.
+        // (For TM > 4 the frames' words of one such piece would not fit the scalar registers: 4 words at a time, as below.)
         constexpr int PW = 32;
-        const int npieces = w32 / PW;
+        const int npieces = TM <= 4 ? w32 / PW : 0;
         auto fetch = [&](uint4 (&b)[PW / 4], int p) {
 #pragma unroll
             for (int q = 0; q < PW / 4; ++q) b[q] = *reinterpret_cast<const uint4*>(wrow + p * PW + 4 * q);
