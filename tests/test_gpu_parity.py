@@ -731,3 +731,44 @@ def test_forward_twice_same_result_and_other_stream(G, bnn, oracle):
         b = model.forward(X)
     s.synchronize()
     assert torch.equal(a, b)
+
+
+# ----------------------------------------------------------------------------- seeded random shapes, every layer kind
+
+def _random_shapes(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        M = int(rng.choice([1, 2, 3, 15, 16, 17, 63, 64, 65, 127, 129, 200, 300]))
+        K = int(rng.choice([4, 8, 12, 60, 64, 68, 100, 252, 256, 260, 440, 1000, 1024, 1028, 37, 129]))
+        N = int(rng.choice([1, 31, 32, 33, 63, 64, 65, 255, 256, 257, 1000, 1025]))
+        out.append((M, K, N))
+    return out
+
+
+@pytest.mark.parametrize("stream_frames", [0, 64])
+@pytest.mark.parametrize("M,K,N", _random_shapes(2024, 40))
+def test_random_shapes_all_layer_kinds(G, bnn, oracle, M, K, N, stream_frames):
+    """Binary-weight and real-weight layers on real input, binary layers in both readings, Sign and fp32 outputs, with
+    the small-batch dispatch off and on; every kernel here keeps the oracle's order, so fp32 outputs are identical bits."""
+    X, W, scale, bias = _rand_layer(M * 31 + K * 7 + N, M, K, N)
+    Wr = (W * np.float32(np.sqrt(3.0 / K))).astype(np.float32)
+    Wp = oracle.pack_sign(W, 32)
+    aw = oracle.pack_sign(X, 32)
+    dX, dWp, dWr, dsc, dbi, daw = (G.to_dev(a) for a in (X, Wp, Wr, scale, bias, aw))
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 2)
+    try:
+        with _streaming(bnn, stream_frames):
+            for act in ("sign", "linear"):
+                a = bnn.ACT_BY_NAME[act]
+                got = [G.layer_realx(dX, dWp, dsc, dbi, K, N, a, 32), G.layer_realw(dX, dWr, dbi, K, N, a, 32),
+                       G.layer_binx(daw, dWp, dsc, dbi, K, N, a, 32), G.layer_binx01(daw, dWp, dsc, dbi, K, N, a, 32)]
+                torch.cuda.synchronize()
+                want = [oracle.layer_binw_realx(X, Wp, K, scale, bias, act, 32), oracle.layer_realw(X, Wr, bias, act, 32),
+                        oracle.layer_binw_binx(aw, Wp, K, scale, bias, act, 32, form="xor"),
+                        oracle.layer_binw_binx01(aw, Wp, K, scale, bias, act, 32, form="and")]
+                for i, (g_, w_) in enumerate(zip(got, want)):
+                    g_ = G.words_to_host(g_, 32) if act == "sign" else g_.cpu().numpy()
+                    assert np.array_equal(g_, w_), (act, i)
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
