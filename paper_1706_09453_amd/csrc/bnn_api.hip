@@ -104,8 +104,9 @@ void launch_realx_tm(const float* X, const uint32_t* Wp, const float* scale, con
 }
 
 // The fp32 matrix-core kernel runs one workgroup per CU: two that share a CU evict each other's operand rows from
-// the L1 (measured: 1.06 ms against 0.54 ms on 432 workgroups).  Its registers would admit two, so the launch asks
-// for dynamic LDS that it never touches, enough that two workgroups do not fit the CU's 160 KiB together.
+// the L1 (measured: 1.06 ms against 0.54 ms on 432 workgroups).  Its register count (140 + 128 accumulation registers)
+// admits only one at present; so that this does not hang on a compiler's register allocation, the launch also asks
+// for dynamic LDS that the kernel never touches, enough that two workgroups do not fit the CU's 160 KiB together.
 constexpr unsigned kF32MfmaPadLds = 48 * 1024;   // + 34 KiB of static LDS > 80 KiB
 template <int ACT, bool VEC, bool WREAL>
 void launch_f32_mfma(dim3 grid, dim3 block, hipStream_t st, const float* X, const void* W, const float* scale,

@@ -26,7 +26,7 @@ typedef float v16f32 __attribute__((ext_vector_type(16)));
 //        aligned too if VEC), fetched exactly like the frames; otherwise Wv is packed bits [N][w32].
 // Grid: x = ceil(M / 256), y = ceil(N / 128); block = 256 threads.  ACT: ACT_LINEAR, ACT_HARDTANH or ACT_SIGMOID.
 template <int ACT, bool VEC, bool WREAL = false>
-__global__ __launch_bounds__(256, 2) void realx_f32_mfma_kernel(const float* __restrict__ X, const void* __restrict__ Wv,
+__global__ __launch_bounds__(256, 1) void realx_f32_mfma_kernel(const float* __restrict__ X, const void* __restrict__ Wv,
                                                                const float* __restrict__ scale, const float* __restrict__ bias,
                                                                int M, int K, int N, int w32, float* __restrict__ Y) {
     const uint32_t* Wp = static_cast<const uint32_t*>(Wv);
@@ -127,6 +127,7 @@ __global__ __launch_bounds__(256, 2) void realx_f32_mfma_kernel(const float* __r
     };
     Set s0, s1;
     // Both fetches of a round are unconditional: a fetch whose only use sits behind a branch is moved behind it.
+    // (A third set, fetched two rounds ahead, measured the same time: the kernel does not wait for memory.)
     fetch(s0, 0);
     int c = 0;
     for (; c + 1 < nC; c += 2) {
