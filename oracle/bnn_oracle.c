@@ -226,6 +226,43 @@ ORC_API void orc_bits_to_real(const void* words, int64_t M, int64_t K, int word_
         }
 }
 
+/* ---------------------------------------------------------------------------------------------------------------
+ * Training side (Alg. 1 and Alg. 2, backward propagation and update; Sec. 2.1-2.3).  The two matrix products of the
+ * backward pass, g_{h_{l-1}} = g_{h^_l} w_l^b and g_{w_l} = g_{h^_l} h_{l-1}, are the products above with the operands'
+ * roles exchanged (orc_realx_acc with the transposed weight signs, orc_realw_acc with both operands transposed), so
+ * they are composed in oracle/train_oracle.py; what follows are the remaining steps.
+ * ------------------------------------------------------------------------------------------------------------- */
+
+/* Alg. 1/2 backward, g_{r_l} = g_{h^_l} summed over the frames of the minibatch: out[n] = sum_m g[m][n], fp32,
+ * ascending m, one accumulator per output (reading: the same order rule as every other sum here). */
+ORC_API void orc_colsum_f32(const float* g, int64_t M, int64_t N, float* out) {
+    for (int64_t n = 0; n < N; ++n) {
+        float s = 0.0f;
+        for (int64_t m = 0; m < M; ++m) s = s + g[m * N + n];
+        out[n] = s;
+    }
+}
+
+/* Alg. 1 Update: w <- Clip(w - eta g) (Clip of Sec. 2.1: to [-1, +1]); with clip == 0 the plain update of Alg. 2 and
+ * of the bias.  w - eta g is ONE fused multiply-add in fp32. */
+ORC_API void orc_update_clip(float* w, const float* g, int64_t count, float eta, int clip) {
+    for (int64_t i = 0; i < count; ++i) {
+        float v = fmaf(-eta, g[i], w[i]);
+        if (clip) {
+            if (v > 1.0f) v = 1.0f;
+            if (v < -1.0f) v = -1.0f;
+        }
+        w[i] = v;
+    }
+}
+
+/* Sec. 2.3, gradient-norm clipping: the squared l2 norm of a gradient matrix, fp64 running sum in index order. */
+ORC_API double orc_sumsq_f64(const float* g, int64_t count) {
+    double s = 0.0;
+    for (int64_t i = 0; i < count; ++i) s += (double)g[i] * (double)g[i];
+    return s;
+}
+
 /*
  * Eq. 1 with the per-layer scale: h^[m][n] = scale[n] * v[m][n] + bias[n] as one
  * fp32 fused multiply-add (single rounding).  scale == NULL means 1, bias == NULL means 0.

@@ -32,6 +32,8 @@ def _L():
         lib.orc_words_per_row.argtypes = [c_int64, c_int]
         lib.orc_mean_abs.restype = c_float
         lib.orc_mean_abs.argtypes = [c_void_p, c_int64]
+        lib.orc_sumsq_f64.restype = ctypes.c_double
+        lib.orc_sumsq_f64.argtypes = [c_void_p, c_int64]
         for name, args in {
             "orc_pack_sign": [c_void_p, c_int64, c_int64, c_int, c_void_p],
             "orc_unpack_pm1": [c_void_p, c_int64, c_int64, c_int, c_void_p],
@@ -42,6 +44,8 @@ def _L():
             "orc_realx_acc": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p],
             "orc_realw_acc": [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p],
             "orc_bits_to_real": [c_void_p, c_int64, c_int64, c_int, c_int, c_void_p],
+            "orc_colsum_f32": [c_void_p, c_int64, c_int64, c_void_p],
+            "orc_update_clip": [c_void_p, c_void_p, c_int64, c_float, c_int],
             "orc_affine_f32": [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p],
             "orc_affine_f64": [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_void_p],
             "orc_i32_to_f32": [c_void_p, c_int64, c_void_p],
