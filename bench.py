@@ -125,6 +125,105 @@ def streaming(args, bnn, workloads, G, torch) -> int:
     return 0
 
 
+def train_step(args, bnn, workloads, G, torch) -> int:
+    """One minibatch of Alg. 1 + Alg. 2 (binary weights and activations, Config 3's layer sizes): forward with the
+    pre-activations kept, backward, gradient-norm clipping, clipped update, re-binarisation.  One JSON line per
+    minibatch size with the time of each phase."""
+    import numpy as np
+    for kv in args.opt:
+        key, val = kv.split("=")
+        bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
+    cfg = workloads.CONFIGS[3]
+    Ws, rs = workloads.make_net_params(cfg)
+    L, wb, st = len(Ws), 32, G.stream()
+    dev = G.DEV
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
+    for M in (256, 4096):
+        X = G.to_dev(workloads.make_frames(cfg, M))
+        labels = G.to_dev(np.random.default_rng(0).integers(0, cfg.dims[-1], M).astype(np.int32))
+        W = [G.to_dev(w) for w in Ws]
+        r = [G.to_dev(b) for b in rs]
+        Wp = [G.word_tensor(w.shape[0], w.shape[1], wb) for w in Ws]
+        WpT = [G.word_tensor(w.shape[1], w.shape[0], wb) for w in Ws]
+        hhat = [f32(M, w.shape[0]) for w in Ws]
+        bits = [G.word_tensor(M, w.shape[0], wb) for w in Ws[:-1]]
+        xreal = [None] + [f32(M, w.shape[1]) for w in Ws[1:]]
+        gbuf = [f32(M, w.shape[0]) for w in Ws]
+        gin = [f32(M, w.shape[1]) for w in Ws]
+        gt = [f32(w.shape[0], M) for w in Ws]
+        ht = [f32(w.shape[1], M) for w in Ws]
+        gw = [f32(*w.shape) for w in Ws]
+        gr = [f32(w.shape[0]) for w in Ws]
+        ws = torch.empty(4096, dtype=torch.uint8, device=dev)
+        norm = f32(1)
+        P = G.ptr
+
+        def binarise():
+            for l in range(L):
+                N, K = Ws[l].shape
+                bnn.bnn_pack_weights(P(W[l]), N, K, wb, P(Wp[l]), 0, st)
+                bnn.bnn_pack_weights_transposed(P(W[l]), N, K, wb, P(WpT[l]), st)
+
+        def forward():
+            for l in range(L):
+                N, K = Ws[l].shape
+                src = X if l == 0 else bits[l - 1]
+                fn = bnn.bnn_layer_binw_realx if l == 0 else bnn.bnn_layer_binw_binx
+                act = bnn.BNN_ACT_LINEAR if l < L - 1 else bnn.BNN_ACT_LOGSOFTMAX
+                fn(P(src), P(Wp[l]), 0, P(r[l]), M, K, N, act, wb, P(hhat[l]), st)
+                if l < L - 1:
+                    bnn.bnn_pack_activations(P(hhat[l]), M, N, wb, P(bits[l]), st)
+
+        def backward():
+            bnn.bnn_softmax_xent_grad(P(hhat[-1]), P(labels), M, cfg.dims[-1], P(gbuf[-1]), st)
+            for l in range(L - 1, -1, -1):
+                N, K = Ws[l].shape
+                g = gbuf[l]
+                if l < L - 1:
+                    bnn.bnn_mask_grad(P(g), P(hhat[l]), M * N, 1.0, P(g), st)
+                if l == 0:
+                    h = X
+                else:
+                    bnn.bnn_unpack_activations(P(bits[l - 1]), M, K, wb, 0, P(xreal[l]), st)
+                    h = xreal[l]
+                bnn.bnn_transpose_f32(P(g), M, N, P(gt[l]), st)
+                bnn.bnn_transpose_f32(P(h), M, K, P(ht[l]), st)
+                bnn.bnn_backward_weight(P(gt[l]), P(ht[l]), N, K, M, P(gw[l]), st)
+                bnn.bnn_bias_grad(P(g), M, N, P(gr[l]), st)
+                if l > 0:
+                    bnn.bnn_backward_input_binw(P(g), P(WpT[l]), M, N, K, wb, P(gbuf[l - 1]), st)
+
+        def update():
+            for l in range(L):
+                N, K = Ws[l].shape
+                bnn.bnn_grad_norm_clip(P(gw[l]), N * K, 15.0, P(ws), P(norm), st)
+                bnn.bnn_update_clip(P(W[l]), P(gw[l]), N * K, 1e-3, 1, st)
+                bnn.bnn_update_clip(P(r[l]), P(gr[l]), N, 1e-3, 0, st)
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / reps
+
+        binarise()
+        reps = 20 if M <= 256 else 5
+        ms = {"binarise": timed(binarise, reps), "forward": timed(forward, reps), "backward": timed(backward, reps),
+              "update": timed(update, reps)}
+        total = sum(ms.values())
+        flops = 3 * 2.0 * cfg.macs_per_frame() * M - 2.0 * cfg.dims[0] * cfg.dims[1] * M   # forward + two backward products
+        print(json.dumps({"workload": f"training step, {cfg.name.split(' M=')[0]}, minibatch {M}", "batch_frames": M,
+                          "ms_per_step": round(total, 3), "frames_per_s": round(M / (total * 1e-3), 1),
+                          "phase_ms": {k: round(v, 3) for k, v in ms.items()},
+                          "tflops_products": round(flops / (total * 1e-3) / 1e12, 1)}), flush=True)
+        del X, labels, W, r, Wp, WpT, hhat, bits, xreal, gbuf, gin, gt, ht, gw, gr
+        torch.cuda.empty_cache()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -136,6 +235,8 @@ def main() -> int:
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
     ap.add_argument("--copy-calibration", action="store_true", help="run 10 plain 256 MiB device copies (counter calibration)")
     ap.add_argument("--only", default="", help="with --all-configs: comma-separated configuration numbers to run")
+    ap.add_argument("--train-step", action="store_true",
+                    help="one minibatch of forward + backward + update (Alg. 1 and 2) at Config 3's sizes")
     ap.add_argument("--streaming", action="store_true",
                     help="latency of bnn_forward on 1, 4, 16 and 64 frames (Configs 3 and 10, or --only)")
     ap.add_argument("--all-configs", action="store_true",
@@ -162,6 +263,8 @@ def main() -> int:
         return all_configs(args, bnn, workloads, G, torch)
     if args.streaming:
         return streaming(args, bnn, workloads, G, torch)
+    if args.train_step:
+        return train_step(args, bnn, workloads, G, torch)
     if args.copy_calibration:
         # A plain device-to-device copy of known size: the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by.
         nbytes = 256 << 20

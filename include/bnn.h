@@ -230,6 +230,64 @@ size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, i
 int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------------------------------
+ * Training side: backward propagation and update of Alg. 1 (binary weights) and Alg. 2 (binary activations), the
+ * gradient-norm clipping of Sec. 2.3 and the semi-stochastic binarisation of Sec. 2.1.  All buffers are DEVICE memory,
+ * fp32 unless said otherwise, dense row-major; calls only enqueue on `stream`; errors as above.
+ * The paper's layers have no per-layer scale; a caller that uses one multiplies g_hhat by it before the products.
+ * ---------------------------------------------------------------------------------------------------------------- */
+
+/* Signs of W^T, packed along n: WpT[k][n / wb] bit (n % wb) = (W[n][k] > 0)  (Eq. 3), the operand of
+ * bnn_backward_input_binw.   W [N][K];  WpT out, words [K][bnn_packed_words(N, word_bits)]. */
+int bnn_pack_weights_transposed(const float* W, int64_t N, int64_t K, int word_bits, void* WpT, void* stream);
+
+/* out[c][r] = A[r][c].   A [R][C];  out [C][R] (must not overlap A). */
+int bnn_transpose_f32(const float* A, int64_t R, int64_t C, float* out, void* stream);
+
+/* Gradient of the cross entropy (Sec. 3), summed over the frames of the minibatch, through the Softmax layer (Alg. 1 and
+ * Alg. 2, first backward step at l = L): g[m][n] = exp(logp[m][n]) - (n == labels[m]).
+ *   logp [M][N] log-posteriors (the output of a LOGSOFTMAX layer);  labels int32 [M], 0 <= label < N (not checked);
+ *   g out [M][N] (may be logp itself). */
+int bnn_softmax_xent_grad(const float* logp, const int32_t* labels, int64_t M, int64_t N, float* g, void* stream);
+
+/* Gradient through a binarisation layer (Sec. 2.2, Alg. 2): g_hhat = g_h (.) Mask(hhat, k), Mask = 0 where |hhat| > k,
+ * 1 otherwise; k > 0.   g_h, hhat [count];  g_hhat out [count] (may be g_h itself). */
+int bnn_mask_grad(const float* g_h, const float* hhat, int64_t count, float k, float* g_hhat, void* stream);
+
+/* Alg. 1 backward, g_{h_{l-1}} = g_{hhat_l} w^b_l: g_h[m][k] = sum_n (WpT bit (k, n) ? +g_hhat[m][n] : -g_hhat[m][n]),
+ * fp32, ascending n, one accumulator per result (the kernels of bnn_layer_binw_realx on the transposed signs).
+ *   g_hhat [M][N];  WpT [K][bnn_packed_words(N, word_bits)] from bnn_pack_weights_transposed;  g_h out [M][K]. */
+int bnn_backward_input_binw(const float* g_hhat, const void* WpT, int64_t M, int64_t N, int64_t K, int word_bits,
+                            float* g_h, void* stream);
+
+/* The same with real-valued weights (Alg. 2, and the layers that keep their weights): g_h[m][k] = sum_n g_hhat[m][n]
+ * Wt[k][n], ascending n, one fused multiply-add per step.   Wt [K][N] = the transposed weight matrix (bnn_transpose_f32). */
+int bnn_backward_input_realw(const float* g_hhat, const float* Wt, int64_t M, int64_t N, int64_t K, float* g_h,
+                             void* stream);
+
+/* Alg. 1 and Alg. 2 backward, g_{w_l} = g_{hhat_l}^T h_{l-1}: g_w[n][k] = sum_m g_hhat_t[n][m] h_t[k][m], fp32, ascending
+ * frame m, one fused multiply-add per step (the kernels of bnn_layer_realw).
+ *   g_hhat_t [N][M] and h_t [K][M]: the transposed gradient and the transposed input of the layer (bnn_transpose_f32; a
+ *   binary input first through bnn_unpack_activations);  g_w out [N][K]. */
+int bnn_backward_weight(const float* g_hhat_t, const float* h_t, int64_t N, int64_t K, int64_t M, float* g_w, void* stream);
+
+/* Alg. 1 and Alg. 2 backward, g_{r_l} = g_{hhat_l} summed over the minibatch: g_r[n] = sum_m g_hhat[m][n], ascending m. */
+int bnn_bias_grad(const float* g_hhat, int64_t M, int64_t N, float* g_r, void* stream);
+
+/* Alg. 1 Update: w <- Clip(w - eta g), Clip to [-1, +1] (Sec. 2.1); clip = 0: w <- w - eta g (Alg. 2; the bias).
+ * w - eta g is one fused multiply-add.   w in/out [count];  g [count]. */
+int bnn_update_clip(float* w, const float* g, int64_t count, float eta, int clip, void* stream);
+
+/* Sec. 2.3: if ||g||_2 > alpha then g <- (alpha / ||g||_2) g; the norm is summed in fp64 in a fixed order.
+ *   g in/out [count];  workspace: DEVICE scratch of at least 2048 bytes, 8-byte aligned;
+ *   norm_out: DEVICE float that receives ||g||_2 (before clipping). */
+int bnn_grad_norm_clip(float* g, int64_t count, float alpha, void* workspace, float* norm_out, void* stream);
+
+/* Sec. 2.1, optional step of Alg. 1's Update (semi-stochastic binarisation): w <- Sign(w) with probability p(|w|),
+ * taken as p(|w|) = |w| (the paper gives no formula), the uniform draws in [0, 1) supplied by the caller:
+ * w[i] <- Sign(w[i]) where u[i] < |w[i]|.   w in/out [count];  u [count]. */
+int bnn_semi_stochastic_binarize(float* w, const float* u, int64_t count, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

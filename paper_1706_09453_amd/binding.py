@@ -57,6 +57,17 @@ _SIGNATURES = {
     "bnn_unpack_activations": (c_int, [c_void_p, c_int64, c_int64, c_int, c_int, c_void_p, c_void_p]),
     "bnn_layer_binw_binx_arm": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_int,
                                         c_void_p, c_int, c_void_p]),
+    "bnn_pack_weights_transposed": (c_int, [c_void_p, c_int64, c_int64, c_int, c_void_p, c_void_p]),
+    "bnn_transpose_f32": (c_int, [c_void_p, c_int64, c_int64, c_void_p, c_void_p]),
+    "bnn_softmax_xent_grad": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_void_p]),
+    "bnn_mask_grad": (c_int, [c_void_p, c_void_p, c_int64, c_float, c_void_p, c_void_p]),
+    "bnn_backward_input_binw": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_void_p, c_void_p]),
+    "bnn_backward_input_realw": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p]),
+    "bnn_backward_weight": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p]),
+    "bnn_bias_grad": (c_int, [c_void_p, c_int64, c_int64, c_void_p, c_void_p]),
+    "bnn_update_clip": (c_int, [c_void_p, c_void_p, c_int64, c_float, c_int, c_void_p]),
+    "bnn_grad_norm_clip": (c_int, [c_void_p, c_int64, c_float, c_void_p, c_void_p, c_void_p]),
+    "bnn_semi_stochastic_binarize": (c_int, [c_void_p, c_void_p, c_int64, c_void_p]),
     "bnn_forward_workspace_bytes": (c_size_t, [c_void_p, c_int, c_int64]),
     "bnn_forward": (c_int, [c_void_p, c_int, c_void_p, c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
 }
@@ -131,6 +142,52 @@ def bnn_layer_binw_binx_arm(Xp: int, Wp: int, scale: int, bias: int, M: int, K: 
                             word_bits: int, Y: int, arm: int, stream: int = 0) -> int:
     return _check(_lib.bnn_layer_binw_binx_arm(Xp, Wp, scale or None, bias or None, M, K, N, act, word_bits, Y, arm,
                                                stream or None))
+
+
+# ---- training side (argument order as in include/bnn.h)
+
+def bnn_pack_weights_transposed(W: int, N: int, K: int, word_bits: int, WpT: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_pack_weights_transposed(W, N, K, word_bits, WpT, stream or None))
+
+
+def bnn_transpose_f32(A: int, R: int, C: int, out: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_transpose_f32(A, R, C, out, stream or None))
+
+
+def bnn_softmax_xent_grad(logp: int, labels: int, M: int, N: int, g: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_softmax_xent_grad(logp, labels, M, N, g, stream or None))
+
+
+def bnn_mask_grad(g_h: int, hhat: int, count: int, k: float, g_hhat: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_mask_grad(g_h, hhat, count, k, g_hhat, stream or None))
+
+
+def bnn_backward_input_binw(g_hhat: int, WpT: int, M: int, N: int, K: int, word_bits: int, g_h: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_backward_input_binw(g_hhat, WpT, M, N, K, word_bits, g_h, stream or None))
+
+
+def bnn_backward_input_realw(g_hhat: int, Wt: int, M: int, N: int, K: int, g_h: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_backward_input_realw(g_hhat, Wt, M, N, K, g_h, stream or None))
+
+
+def bnn_backward_weight(g_hhat_t: int, h_t: int, N: int, K: int, M: int, g_w: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_backward_weight(g_hhat_t, h_t, N, K, M, g_w, stream or None))
+
+
+def bnn_bias_grad(g_hhat: int, M: int, N: int, g_r: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_bias_grad(g_hhat, M, N, g_r, stream or None))
+
+
+def bnn_update_clip(w: int, g: int, count: int, eta: float, clip: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_update_clip(w, g, count, eta, clip, stream or None))
+
+
+def bnn_grad_norm_clip(g: int, count: int, alpha: float, workspace: int, norm_out: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_grad_norm_clip(g, count, alpha, workspace, norm_out, stream or None))
+
+
+def bnn_semi_stochastic_binarize(w: int, u: int, count: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_semi_stochastic_binarize(w, u, count, stream or None))
 
 
 def make_layer_array(descs: Sequence[dict]):

@@ -15,6 +15,7 @@
 #include "pack_kernels.hpp"
 #include "realx_fused_kernel.hpp"
 #include "softmax_kernels.hpp"
+#include "train_kernels.hpp"
 #include "valu_kernels.hpp"
 
 #define BNN_EXPORT extern "C" __attribute__((visibility("default")))
@@ -162,7 +163,13 @@ int run_realx(const float* X, const void* Wp, const float* scale, const float* b
         return launch_status();
     }
     // batches of a few frames (streaming): 1 or 2 frames per workgroup spread the layer over the chip
-    const int tm = M <= g_stream_max_frames.load() ? (M <= 16 ? 1 : 2) : g_realx_tm.load();
+    int tm = M <= g_stream_max_frames.load() ? (M <= 16 ? 1 : 2) : g_realx_tm.load();
+    if (tm == 0 && ((M + 15) / 16) * ((N + 1023) / 1024) < 256) {
+        // too few frames for 16 x 1024 tiles to give every CU a workgroup: the row-broadcast kernel with the most
+        // frames per workgroup (fewest sign-building instructions per fma) that still gives 256 workgroups
+        tm = 16;
+        while (tm > 2 && ((M + tm - 1) / tm) * ((N + 255) / 256) < 256) tm >>= 1;
+    }
     if (tm == 0 && (K & 3) == 0 && aligned(X, 16)) {
         // large batch, aligned rows: frames through LDS, every fma on three VGPRs
         constexpr int TM = 16, TNN = 4;
@@ -709,6 +716,124 @@ BNN_EXPORT int bnn_unpack_activations(const void* Xp, int64_t M, int64_t K, int 
     if (!aligned(Xp, word_bits / 8) || !aligned(X, 4)) return BNN_EALIGN;
     if (overlap(Xp, (size_t)M * row_w32(K, word_bits) * 4, X, (size_t)M * K * 4)) return BNN_EINVAL;
     return run_unpack(Xp, M, K, word_bits, zero_one, X, static_cast<hipStream_t>(stream));
+}
+
+// ------------------------------------------------------------------------------------------------ training side
+
+namespace {
+unsigned elementwise_blocks(int64_t count) {
+    const int64_t b = (count + 255) / 256;
+    return (unsigned)(b < 65536 ? (b > 0 ? b : 1) : 65536);
+}
+bool dims_ok(int64_t a, int64_t b) { return a > 0 && b > 0 && a <= kMaxDim && b <= kMaxDim; }
+}  // namespace
+
+BNN_EXPORT int bnn_pack_weights_transposed(const float* W, int64_t N, int64_t K, int word_bits, void* WpT, void* stream) {
+    if (!word_bits_ok(word_bits) || !dims_ok(N, K)) return BNN_ESHAPE;
+    if (!W || !WpT) return BNN_EINVAL;
+    if (!aligned(W, 4) || !aligned(WpT, word_bits / 8)) return BNN_EALIGN;
+    const int w32t = (int)row_w32(N, word_bits);
+    if (overlap(W, (size_t)N * K * 4, WpT, (size_t)K * w32t * 4)) return BNN_EINVAL;
+    const dim3 grid((unsigned)((K + 63) / 64), (unsigned)((N + 63) / 64));
+    pack_sign_transposed_kernel<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(W, (int)N, (int)K, w32t,
+                                                                                     static_cast<uint32_t*>(WpT));
+    return launch_status();
+}
+
+BNN_EXPORT int bnn_transpose_f32(const float* A, int64_t R, int64_t C, float* out, void* stream) {
+    if (!dims_ok(R, C)) return BNN_ESHAPE;
+    if (!A || !out) return BNN_EINVAL;
+    if (!aligned(A, 4) || !aligned(out, 4)) return BNN_EALIGN;
+    if (overlap(A, (size_t)R * C * 4, out, (size_t)R * C * 4)) return BNN_EINVAL;
+    const dim3 grid((unsigned)((C + 63) / 64), (unsigned)((R + 63) / 64));
+    transpose_f32_kernel<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(A, (int)R, (int)C, out);
+    return launch_status();
+}
+
+BNN_EXPORT int bnn_softmax_xent_grad(const float* logp, const int32_t* labels, int64_t M, int64_t N, float* g, void* stream) {
+    if (M < 0 || N <= 0 || M > kMaxDim || N > kMaxDim) return BNN_ESHAPE;
+    if (M == 0) return BNN_OK;
+    if (!logp || !labels || !g) return BNN_EINVAL;
+    if (!aligned(logp, 4) || !aligned(labels, 4) || !aligned(g, 4)) return BNN_EALIGN;
+    softmax_xent_grad_kernel<<<elementwise_blocks(M * N), 256, 0, static_cast<hipStream_t>(stream)>>>(logp, labels, M, (int)N, g);
+    return launch_status();
+}
+
+BNN_EXPORT int bnn_mask_grad(const float* g_h, const float* hhat, int64_t count, float k, float* g_hhat, void* stream) {
+    if (count < 0) return BNN_ESHAPE;
+    if (!(k > 0.0f)) return BNN_EINVAL;
+    if (count == 0) return BNN_OK;
+    if (!g_h || !hhat || !g_hhat) return BNN_EINVAL;
+    if (!aligned(g_h, 4) || !aligned(hhat, 4) || !aligned(g_hhat, 4)) return BNN_EALIGN;
+    mask_grad_kernel<<<elementwise_blocks(count), 256, 0, static_cast<hipStream_t>(stream)>>>(g_h, hhat, count, k, g_hhat);
+    return launch_status();
+}
+
+BNN_EXPORT int bnn_backward_input_binw(const float* g_hhat, const void* WpT, int64_t M, int64_t N, int64_t K, int word_bits,
+                                       float* g_h, void* stream) {
+    // the forward layer with the roles exchanged: "inputs" are the N gradients of a frame, "outputs" the K inputs
+    const int rc = check_layer_args(g_hhat, WpT, M, N, K, BNN_ACT_LINEAR, word_bits, g_h, false);
+    if (rc != BNN_OK) return rc;
+    return run_realx(g_hhat, WpT, nullptr, nullptr, M, N, K, BNN_ACT_LINEAR, word_bits, g_h, static_cast<hipStream_t>(stream));
+}
+
+BNN_EXPORT int bnn_backward_input_realw(const float* g_hhat, const float* Wt, int64_t M, int64_t N, int64_t K, float* g_h,
+                                        void* stream) {
+    const int rc = check_layer_args(g_hhat, Wt, M, N, K, BNN_ACT_LINEAR, 32, g_h, false, true);
+    if (rc != BNN_OK) return rc;
+    return run_realw(g_hhat, Wt, nullptr, M, N, K, BNN_ACT_LINEAR, 32, g_h, static_cast<hipStream_t>(stream));
+}
+
+BNN_EXPORT int bnn_backward_weight(const float* g_hhat_t, const float* h_t, int64_t N, int64_t K, int64_t M, float* g_w,
+                                   void* stream) {
+    // rows of the "frame" operand are the N outputs, the sum runs over the M frames, "outputs" are the K inputs
+    if (M <= 0) return BNN_ESHAPE;
+    const int rc = check_layer_args(g_hhat_t, h_t, N, M, K, BNN_ACT_LINEAR, 32, g_w, false, true);
+    if (rc != BNN_OK) return rc;
+    return run_realw(g_hhat_t, h_t, nullptr, N, M, K, BNN_ACT_LINEAR, 32, g_w, static_cast<hipStream_t>(stream));
+}
+
+BNN_EXPORT int bnn_bias_grad(const float* g_hhat, int64_t M, int64_t N, float* g_r, void* stream) {
+    if (M < 0 || N <= 0 || M > kMaxDim || N > kMaxDim) return BNN_ESHAPE;
+    if (!g_hhat || !g_r) return BNN_EINVAL;
+    if (!aligned(g_hhat, 4) || !aligned(g_r, 4)) return BNN_EALIGN;
+    if (overlap(g_hhat, (size_t)M * N * 4, g_r, (size_t)N * 4)) return BNN_EINVAL;
+    colsum_kernel<<<(unsigned)((N + 255) / 256), 256, 0, static_cast<hipStream_t>(stream)>>>(g_hhat, (int)M, (int)N, g_r);
+    return launch_status();
+}
+
+BNN_EXPORT int bnn_update_clip(float* w, const float* g, int64_t count, float eta, int clip, void* stream) {
+    if (count < 0) return BNN_ESHAPE;
+    if (clip < 0 || clip > 1) return BNN_EINVAL;
+    if (count == 0) return BNN_OK;
+    if (!w || !g) return BNN_EINVAL;
+    if (!aligned(w, 4) || !aligned(g, 4)) return BNN_EALIGN;
+    if (overlap(w, (size_t)count * 4, g, (size_t)count * 4)) return BNN_EINVAL;
+    update_clip_kernel<<<elementwise_blocks(count), 256, 0, static_cast<hipStream_t>(stream)>>>(w, g, count, eta, clip);
+    return launch_status();
+}
+
+BNN_EXPORT int bnn_grad_norm_clip(float* g, int64_t count, float alpha, void* workspace, float* norm_out, void* stream) {
+    if (count < 0) return BNN_ESHAPE;
+    if (!(alpha > 0.0f)) return BNN_EINVAL;
+    if (!g || !workspace || !norm_out) return BNN_EINVAL;
+    if (!aligned(g, 4) || !aligned(workspace, 8) || !aligned(norm_out, 4)) return BNN_EALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    double* partial = static_cast<double*>(workspace);
+    sumsq_partial_kernel<<<kSumsqBlocks, 256, 0, st>>>(g, count, partial);
+    sumsq_final_kernel<<<1, 256, 0, st>>>(partial, norm_out);
+    if (count > 0) scale_if_above_kernel<<<elementwise_blocks(count), 256, 0, st>>>(g, count, alpha, norm_out);
+    return launch_status();
+}
+
+BNN_EXPORT int bnn_semi_stochastic_binarize(float* w, const float* u, int64_t count, void* stream) {
+    if (count < 0) return BNN_ESHAPE;
+    if (count == 0) return BNN_OK;
+    if (!w || !u) return BNN_EINVAL;
+    if (!aligned(w, 4) || !aligned(u, 4)) return BNN_EALIGN;
+    if (overlap(w, (size_t)count * 4, u, (size_t)count * 4)) return BNN_EINVAL;
+    semi_stochastic_kernel<<<elementwise_blocks(count), 256, 0, static_cast<hipStream_t>(stream)>>>(w, u, count);
+    return launch_status();
 }
 
 // Workspace layout of bnn_forward: two ping-pong buffers of `half` bytes, then `unpacked` bytes for the fp32 copy of

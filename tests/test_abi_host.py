@@ -119,6 +119,37 @@ def test_real_weight_layers_in_a_chain(bnn):
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 0
 
 
+def test_training_argument_validation(bnn):
+    E, S, A = bnn.BNN_EINVAL, bnn.BNN_ESHAPE, bnn.BNN_EALIGN
+    assert _status(bnn.bnn_pack_weights_transposed, 0, 4, 64, 32, Q, 0) == E
+    assert _status(bnn.bnn_pack_weights_transposed, P, 0, 64, 32, Q, 0) == S
+    assert _status(bnn.bnn_pack_weights_transposed, P, 4, 64, 48, Q, 0) == S
+    assert _status(bnn.bnn_pack_weights_transposed, P, 4, 64, 64, Q + 4, 0) == A
+    assert _status(bnn.bnn_transpose_f32, P, 4, 0, Q, 0) == S
+    assert _status(bnn.bnn_transpose_f32, P, 4, 64, 0, 0) == E
+    assert _status(bnn.bnn_transpose_f32, P, 4, 64, P + 16, 0) == E                 # overlapping
+    assert _status(bnn.bnn_softmax_xent_grad, P, 0, 4, 64, R, 0) == E                # null labels
+    assert _status(bnn.bnn_softmax_xent_grad, P, Q, 4, 0, R, 0) == S
+    assert bnn.bnn_softmax_xent_grad(0, 0, 0, 64, 0, 0) == 0                          # no frames: nothing to do
+    assert _status(bnn.bnn_mask_grad, P, Q, 16, 0.0, R, 0) == E                      # k must be positive
+    assert _status(bnn.bnn_mask_grad, P, Q, -1, 1.0, R, 0) == S
+    assert _status(bnn.bnn_mask_grad, P, 0, 16, 1.0, R, 0) == E
+    assert _status(bnn.bnn_backward_input_binw, P, 0, 4, 64, 64, 32, R, 0) == E
+    assert _status(bnn.bnn_backward_input_binw, P, Q, 4, 64, 64, 16, R, 0) == S
+    assert _status(bnn.bnn_backward_input_realw, P, Q + 2, 4, 64, 64, R, 0) == A
+    assert _status(bnn.bnn_backward_weight, P, Q, 64, 64, 0, R, 0) == S              # an empty minibatch has no gradient
+    assert _status(bnn.bnn_backward_weight, P, Q, 64, 64, 8, P, 0) == E              # output aliases an operand
+    assert _status(bnn.bnn_bias_grad, 0, 4, 64, R, 0) == E
+    assert _status(bnn.bnn_update_clip, P, Q, 16, 0.1, 2, 0) == E                    # clip is 0 or 1
+    assert _status(bnn.bnn_update_clip, P, P, 16, 0.1, 1, 0) == E                    # w and g overlap
+    assert bnn.bnn_update_clip(0, 0, 0, 0.1, 1, 0) == 0
+    assert _status(bnn.bnn_grad_norm_clip, P, 16, 0.0, Q, R, 0) == E                 # alpha must be positive
+    assert _status(bnn.bnn_grad_norm_clip, P, 16, 15.0, 0, R, 0) == E                # no workspace
+    assert _status(bnn.bnn_grad_norm_clip, P, 16, 15.0, Q + 4, R, 0) == A
+    assert _status(bnn.bnn_semi_stochastic_binarize, P, 0, 16, 0) == E
+    assert _status(bnn.bnn_semi_stochastic_binarize, P, P + 8, 16, 0) == E
+
+
 def test_pack_argument_validation(bnn):
     assert _status(bnn.bnn_pack_weights, 0, 4, 64, 32, Q, 0, 0) == bnn.BNN_EINVAL
     assert _status(bnn.bnn_pack_weights, P, 0, 64, 32, Q, 0, 0) == bnn.BNN_ESHAPE

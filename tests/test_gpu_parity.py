@@ -466,8 +466,9 @@ def _first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, use_mfma):
     ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=G.DEV)
     out = G.word_tensor(M, N, wb)
     bnn.bnn_set_option(bnn.BNN_OPT_REALX_SIGN_MFMA, 1 if use_mfma else 0)
+    dX = G.to_dev(X)
     try:
-        bnn.bnn_forward(arr, 1, G.ptr(G.to_dev(X)), M, G.ptr(out), G.ptr(ws), nbytes, G.stream())
+        bnn.bnn_forward(arr, 1, G.ptr(dX), M, G.ptr(out), G.ptr(ws), nbytes, G.stream())
         torch.cuda.synchronize()
     finally:
         bnn.bnn_set_option(bnn.BNN_OPT_REALX_SIGN_MFMA, 1)

@@ -1,0 +1,261 @@
+"""GPU parity of the training-side entry points (Alg. 1 / Alg. 2 backward and update, Sec. 2.1-2.3) against the CPU
+oracle, through the C ABI.  The sums of the backward products run in the oracle's order, so they are compared bit
+for bit; steps that go through an fp64 library function (exp, sqrt of a sum in another order) within 1e-6."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+@pytest.fixture(scope="module")
+def bnn():
+    import paper_1706_09453_amd as b
+    return b
+
+
+@pytest.fixture(scope="module")
+def T():
+    from oracle import train_oracle
+    return train_oracle
+
+
+def _f32(M, N, fill=float("nan")):
+    return torch.full((M, N), fill, dtype=torch.float32, device="cuda:0")
+
+
+SHAPES = [(1, 1, 1), (3, 5, 7), (17, 33, 65), (64, 100, 257), (130, 440, 200), (70, 2048, 96), (300, 260, 1028)]
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("N,K", [(1, 1), (5, 3), (31, 64), (64, 65), (65, 33), (100, 257), (2048, 440), (1000, 2048)])
+def test_pack_weights_transposed(G, bnn, oracle, N, K, wb):
+    W = np.random.default_rng(N + K).standard_normal((N, K)).astype(np.float32)
+    W[::3, ::5] = 0.0                                                   # Sign(0) = -1: bit 0
+    out = G.word_tensor(K, N, wb)
+    dW = G.to_dev(W)
+    bnn.bnn_pack_weights_transposed(G.ptr(dW), N, K, wb, G.ptr(out), G.stream())
+    assert np.array_equal(G.words_to_host(out, wb), oracle.pack_sign(np.ascontiguousarray(W.T), wb))
+
+
+@pytest.mark.parametrize("R,C", [(1, 1), (3, 70), (64, 64), (65, 63), (130, 2048), (4096, 100)])
+def test_transpose(G, bnn, R, C):
+    A = np.random.default_rng(R * C).standard_normal((R, C)).astype(np.float32)
+    out = _f32(C, R)
+    dA = G.to_dev(A)
+    bnn.bnn_transpose_f32(G.ptr(dA), R, C, G.ptr(out), G.stream())
+    assert np.array_equal(out.cpu().numpy(), A.T)
+
+
+@pytest.mark.parametrize("M,N", [(1, 1), (7, 10), (64, 3307), (300, 1000)])
+def test_softmax_xent_grad(G, bnn, T, M, N):
+    rng = np.random.default_rng(M + N)
+    z = rng.standard_normal((M, N)) * 3
+    logp = (z - np.log(np.exp(z).sum(1, keepdims=True))).astype(np.float32)
+    labels = rng.integers(0, N, M).astype(np.int32)
+    g = _f32(M, N)
+    dlogp, dlabels = G.to_dev(logp), G.to_dev(labels)
+    bnn.bnn_softmax_xent_grad(G.ptr(dlogp), G.ptr(dlabels), M, N, G.ptr(g), G.stream())
+    assert np.max(np.abs(g.cpu().numpy() - T.softmax_xent_grad(logp, labels))) <= 1e-6
+
+
+@pytest.mark.parametrize("k", [0.5, 1.0, 3.0])
+def test_mask_grad(G, bnn, T, k):
+    rng = np.random.default_rng(7)
+    g = rng.standard_normal(100003).astype(np.float32)
+    hh = (rng.standard_normal(100003) * 2).astype(np.float32)
+    hh[:4] = [k, -k, np.nextafter(np.float32(k), np.float32(9)), np.nan]
+    dg, dhh = G.to_dev(g), G.to_dev(hh)
+    out = torch.full((g.size,), float("nan"), dtype=torch.float32, device="cuda:0")
+    bnn.bnn_mask_grad(G.ptr(dg), G.ptr(dhh), g.size, k, G.ptr(out), G.stream())
+    assert np.array_equal(out.cpu().numpy(), T.mask_grad(g, hh, k), equal_nan=True)
+    bnn.bnn_mask_grad(G.ptr(dg), G.ptr(dhh), g.size, k, G.ptr(dg), G.stream())      # in place
+    assert np.array_equal(dg.cpu().numpy(), T.mask_grad(g, hh, k), equal_nan=True)
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_backward_input_binw(G, bnn, oracle, T, M, N, K, wb):
+    """g_h = g_hhat w^b through the transposed packed signs: the same ascending-n chain as the oracle's, identical bits."""
+    rng = np.random.default_rng(M + N + K)
+    g = rng.standard_normal((M, N)).astype(np.float32)
+    W = rng.uniform(-1, 1, (N, K)).astype(np.float32)
+    WpT = G.word_tensor(K, N, wb)
+    dW, dg = G.to_dev(W), G.to_dev(g)
+    bnn.bnn_pack_weights_transposed(G.ptr(dW), N, K, wb, G.ptr(WpT), G.stream())
+    out = _f32(M, K)
+    bnn.bnn_backward_input_binw(G.ptr(dg), G.ptr(WpT), M, N, K, wb, G.ptr(out), G.stream())
+    want = T.backward_input_binw(g, np.where(W > 0, 1, -1).astype(np.int8))
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_backward_input_realw_and_weight_gradient(G, bnn, T, M, N, K):
+    rng = np.random.default_rng(3 * M + N + K)
+    g = rng.standard_normal((M, N)).astype(np.float32)
+    W = (rng.standard_normal((N, K)) / np.sqrt(N)).astype(np.float32)
+    h = rng.standard_normal((M, K)).astype(np.float32)
+    dg, dW, dh = G.to_dev(g), G.to_dev(W), G.to_dev(h)
+    Wt, gt, ht = _f32(K, N), _f32(N, M), _f32(K, M)
+    bnn.bnn_transpose_f32(G.ptr(dW), N, K, G.ptr(Wt), G.stream())
+    bnn.bnn_transpose_f32(G.ptr(dg), M, N, G.ptr(gt), G.stream())
+    bnn.bnn_transpose_f32(G.ptr(dh), M, K, G.ptr(ht), G.stream())
+    gh, gw, gr = _f32(M, K), _f32(N, K), torch.full((N,), float("nan"), dtype=torch.float32, device="cuda:0")
+    bnn.bnn_backward_input_realw(G.ptr(dg), G.ptr(Wt), M, N, K, G.ptr(gh), G.stream())
+    bnn.bnn_backward_weight(G.ptr(gt), G.ptr(ht), N, K, M, G.ptr(gw), G.stream())
+    bnn.bnn_bias_grad(G.ptr(dg), M, N, G.ptr(gr), G.stream())
+    assert np.array_equal(gh.cpu().numpy(), T.backward_input_realw(g, W))
+    assert np.array_equal(gw.cpu().numpy(), T.backward_weight(g, h))
+    assert np.array_equal(gr.cpu().numpy(), T.bias_grad(g))
+
+
+def test_weight_gradient_of_a_binary_input(G, bnn, oracle, T):
+    """g_w = g_hhat^T h with h the bits of a binary layer, read as -1/+1 and as 0/1 (unpacked, transposed, multiplied)."""
+    M, N, K = 200, 96, 130
+    rng = np.random.default_rng(11)
+    g = rng.standard_normal((M, N)).astype(np.float32)
+    words = oracle.pack_sign(rng.standard_normal((M, K)).astype(np.float32), 32)
+    gt = _f32(N, M)
+    dg, dwords = G.to_dev(g), G.to_dev(words)
+    bnn.bnn_transpose_f32(G.ptr(dg), M, N, G.ptr(gt), G.stream())
+    for zero_one in (False, True):
+        hX = G.unpack_activations(dwords, K, 32, zero_one)
+        ht, gw = _f32(K, M), _f32(N, K)
+        bnn.bnn_transpose_f32(G.ptr(hX), M, K, G.ptr(ht), G.stream())
+        bnn.bnn_backward_weight(G.ptr(gt), G.ptr(ht), N, K, M, G.ptr(gw), G.stream())
+        assert np.array_equal(gw.cpu().numpy(), T.backward_weight(g, oracle.bits_to_real(words, K, 32, zero_one)))
+
+
+@pytest.mark.parametrize("clip", [0, 1])
+def test_update_clip(G, bnn, T, clip):
+    rng = np.random.default_rng(5)
+    w = rng.uniform(-1, 1, 300001).astype(np.float32)
+    g = (rng.standard_normal(300001) * 30).astype(np.float32)
+    dw, dg = G.to_dev(w), G.to_dev(g)
+    bnn.bnn_update_clip(G.ptr(dw), G.ptr(dg), w.size, 0.008, clip, G.stream())
+    want = T.update_clip(w, g, 0.008, bool(clip))
+    assert np.array_equal(dw.cpu().numpy(), want)
+    if clip:
+        assert np.abs(want).max() == 1.0 and (np.abs(want) == 1.0).mean() > 0.01
+
+
+@pytest.mark.parametrize("alpha", [15.0, 1e6])
+@pytest.mark.parametrize("count", [1, 1000, 2048 * 440, 2048 * 2048 + 3])
+def test_grad_norm_clip(G, bnn, T, count, alpha):
+    g = (np.random.default_rng(count).standard_normal(count) * 0.05).astype(np.float32)
+    dg = G.to_dev(g)
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda:0")
+    norm = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda:0")
+    bnn.bnn_grad_norm_clip(G.ptr(dg), count, alpha, G.ptr(ws), G.ptr(norm), G.stream())
+    want, want_norm = T.grad_norm_clip(g, alpha)
+    got_norm = float(norm.cpu().numpy()[0])
+    assert abs(got_norm - float(want_norm)) <= 1e-6 * float(want_norm) + 1e-30
+    got = dg.cpu().numpy()
+    if float(want_norm) <= alpha:
+        assert np.array_equal(got, g)                      # at or below the threshold: untouched
+    else:
+        assert np.max(np.abs(got - want)) <= 1e-6 * np.max(np.abs(want))
+        assert abs(np.linalg.norm(got.astype(np.float64)) - alpha) <= 1e-4 * alpha
+
+
+def test_semi_stochastic_binarize(G, bnn, T):
+    rng = np.random.default_rng(9)
+    w = rng.uniform(-1, 1, 500003).astype(np.float32)
+    w[:3] = [0.0, 1.0, -1.0]
+    u = rng.uniform(0, 1, w.size).astype(np.float32)
+    dw, du = G.to_dev(w), G.to_dev(u)
+    bnn.bnn_semi_stochastic_binarize(G.ptr(dw), G.ptr(du), w.size, G.stream())
+    assert np.array_equal(dw.cpu().numpy(), T.semi_stochastic_binarize(w, u))
+
+
+def test_one_training_step_of_a_binary_network(G, bnn, oracle, T):
+    """Alg. 1 + Alg. 2 on a small (sign, sign, softmax) network with binary weights: forward with pre-activations kept,
+    backward and update through the C ABI, every gradient and the updated weights against the oracle's."""
+    import workloads
+    cfg = workloads.NetConfig(21, "train", (40, 96, 64, 30), 70, "sign", 32)
+    Ws, rs = workloads.make_net_params(cfg)
+    X = workloads.make_frames(cfg)
+    labels = np.random.default_rng(1).integers(0, 30, cfg.M).astype(np.int32)
+    M, k_mask, eta, alpha = cfg.M, 1.0, 0.001, 15.0
+    L = len(Ws)
+    # ---- oracle (no per-layer scale: the paper's layer)
+    hs, hhats = [X], []
+    for l, (W, r) in enumerate(zip(Ws, rs)):
+        Wb = np.where(W > 0, 1, -1).astype(np.int8)
+        x_real = hs[-1] if l == 0 else oracle.bits_to_real(hs[-1], W.shape[1], 32, False)
+        hhat = oracle.affine_f32(oracle.realx_acc(x_real, Wb, want64=False)[0], None, r)
+        hhats.append(hhat)
+        hs.append(oracle.pack_sign(hhat, 32) if l < L - 1 else oracle.log_softmax(hhat)[0])
+    want_gw, want_gr = [None] * L, [None] * L
+    g = T.softmax_xent_grad(hs[-1], labels)
+    for l in range(L - 1, -1, -1):
+        if l < L - 1:
+            g = T.mask_grad(g, hhats[l], k_mask)
+        x_real = hs[l] if l == 0 else oracle.bits_to_real(hs[l], Ws[l].shape[1], 32, False)
+        want_gw[l], want_gr[l] = T.backward_weight(g, x_real), T.bias_grad(g)
+        if l > 0:
+            g = T.backward_input_binw(g, np.where(Ws[l] > 0, 1, -1).astype(np.int8))
+    # ---- GPU, through the C ABI
+    st = G.stream()
+    dX, dlab = G.to_dev(X), G.to_dev(labels)
+    dW = [G.to_dev(W) for W in Ws]
+    dr = [G.to_dev(r) for r in rs]
+    acts, hh = [dX], []
+    for l in range(L):
+        N, K = Ws[l].shape
+        Wp = G.word_tensor(N, K, 32)
+        bnn.bnn_pack_weights(G.ptr(dW[l]), N, K, 32, G.ptr(Wp), 0, st)
+        z = _f32(M, N)
+        if l == 0:
+            bnn.bnn_layer_binw_realx(G.ptr(acts[-1]), G.ptr(Wp), 0, G.ptr(dr[l]), M, K, N, bnn.BNN_ACT_LINEAR, 32, G.ptr(z), st)
+        else:
+            bnn.bnn_layer_binw_binx(G.ptr(acts[-1]), G.ptr(Wp), 0, G.ptr(dr[l]), M, K, N, bnn.BNN_ACT_LINEAR, 32, G.ptr(z), st)
+        hh.append(z)
+        if l < L - 1:
+            acts.append(G.pack_activations(z, 32))
+    assert all(np.array_equal(a.cpu().numpy(), b) for a, b in zip(hh, hhats))
+    logp = _f32(M, 30)
+    N, K = Ws[-1].shape
+    Wp = G.word_tensor(N, K, 32)
+    bnn.bnn_pack_weights(G.ptr(dW[-1]), N, K, 32, G.ptr(Wp), 0, st)
+    bnn.bnn_layer_binw_binx(G.ptr(acts[-1]), G.ptr(Wp), 0, G.ptr(dr[-1]), M, K, N, bnn.BNN_ACT_LOGSOFTMAX, 32, G.ptr(logp), st)
+    dg = _f32(M, 30)
+    bnn.bnn_softmax_xent_grad(G.ptr(logp), G.ptr(dlab), M, 30, G.ptr(dg), st)
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda:0")
+    norm = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    for l in range(L - 1, -1, -1):
+        N, K = Ws[l].shape
+        if l < L - 1:
+            bnn.bnn_mask_grad(G.ptr(dg), G.ptr(hh[l]), M * N, k_mask, G.ptr(dg), st)
+        x_real = acts[l] if l == 0 else G.unpack_activations(acts[l], K, 32, False)
+        gt, ht, gw = _f32(N, M), _f32(K, M), _f32(N, K)
+        gr = torch.empty(N, dtype=torch.float32, device="cuda:0")
+        bnn.bnn_transpose_f32(G.ptr(dg), M, N, G.ptr(gt), st)
+        bnn.bnn_transpose_f32(G.ptr(x_real), M, K, G.ptr(ht), st)
+        bnn.bnn_backward_weight(G.ptr(gt), G.ptr(ht), N, K, M, G.ptr(gw), st)
+        bnn.bnn_bias_grad(G.ptr(dg), M, N, G.ptr(gr), st)
+        tol = 2e-6 * float(np.max(np.abs(want_gw[l])))      # the Softmax gradient goes through exp: not bit for bit
+        assert np.max(np.abs(gw.cpu().numpy() - want_gw[l])) <= tol, l
+        assert np.max(np.abs(gr.cpu().numpy() - want_gr[l])) <= 2e-6 * float(np.max(np.abs(want_gr[l]))), l
+        if l > 0:
+            WpT = G.word_tensor(K, N, 32)
+            bnn.bnn_pack_weights_transposed(G.ptr(dW[l]), N, K, 32, G.ptr(WpT), st)
+            gh = _f32(M, K)
+            bnn.bnn_backward_input_binw(G.ptr(dg), G.ptr(WpT), M, N, K, 32, G.ptr(gh), st)
+            dg = gh
+        # update: norm clip, Clip(w - eta g), bias
+        bnn.bnn_grad_norm_clip(G.ptr(gw), N * K, alpha, G.ptr(ws), G.ptr(norm), st)
+        bnn.bnn_update_clip(G.ptr(dW[l]), G.ptr(gw), N * K, eta, 1, st)
+        bnn.bnn_update_clip(G.ptr(dr[l]), G.ptr(gr), N, eta, 0, st)
+        want_w = T.update_clip(Ws[l], T.grad_norm_clip(want_gw[l], alpha)[0], eta, True)
+        got_w = dW[l].cpu().numpy()
+        assert np.max(np.abs(got_w - want_w)) <= 1e-6 and np.abs(got_w).max() <= 1.0
+        assert np.mean(np.sign(got_w) == np.sign(want_w)) > 0.9999
