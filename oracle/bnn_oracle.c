@@ -1,6 +1,7 @@
 /*
  * CPU oracle for the forward pass of a feedforward acoustic model with binary
- * (+1/-1) weights and, optionally, binary activations.
+ * (+1/-1) weights and, optionally, binary activations, and for the steps of its
+ * backward pass and update (second half of this file and oracle/train_oracle.py).
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
  * GPU library must compute.  It shares no code, header, table or helper with the

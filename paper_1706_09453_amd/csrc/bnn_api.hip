@@ -798,7 +798,7 @@ BNN_EXPORT int bnn_bias_grad(const float* g_hhat, int64_t M, int64_t N, float* g
     if (!g_hhat || !g_r) return BNN_EINVAL;
     if (!aligned(g_hhat, 4) || !aligned(g_r, 4)) return BNN_EALIGN;
     if (overlap(g_hhat, (size_t)M * N * 4, g_r, (size_t)N * 4)) return BNN_EINVAL;
-    colsum_kernel<<<(unsigned)((N + 255) / 256), 256, 0, static_cast<hipStream_t>(stream)>>>(g_hhat, (int)M, (int)N, g_r);
+    colsum_kernel<<<(unsigned)((N + 63) / 64), 64, 0, static_cast<hipStream_t>(stream)>>>(g_hhat, (int)M, (int)N, g_r);
     return launch_status();
 }
 

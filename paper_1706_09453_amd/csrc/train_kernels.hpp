@@ -70,19 +70,19 @@ __global__ __launch_bounds__(256) void mask_grad_kernel(const float* __restrict_
         out[e] = __builtin_fabsf(hhat[e]) > k ? 0.0f : g_h[e];
 }
 
-// g_r[n] = sum_m g[m][n] in fp32, ascending m, one accumulator per n (lanes <-> n: every row is read coalesced; eight
-// rows are requested at a time).  Grid: x = ceil(N / 256).
-__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ g, int M, int N, float* __restrict__ out) {
-    const int n = (int)blockIdx.x * 256 + (int)threadIdx.x;
+// g_r[n] = sum_m g[m][n] in fp32, ascending m, one accumulator per n (lanes <-> n: every row is read coalesced; 32
+// rows are requested at a time, the additions stay in order).  Grid: x = ceil(N / 64), one wave per workgroup.
+__global__ __launch_bounds__(64) void colsum_kernel(const float* __restrict__ g, int M, int N, float* __restrict__ out) {
+    const int n = (int)blockIdx.x * 64 + (int)threadIdx.x;
     if (n >= N) return;
     float s = 0.0f;
     int m = 0;
-    for (; m + 8 <= M; m += 8) {
-        float v[8];
+    for (; m + 32 <= M; m += 32) {
+        float v[32];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = g[(size_t)(m + i) * N + n];
+        for (int i = 0; i < 32; ++i) v[i] = g[(size_t)(m + i) * N + n];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) s = s + v[i];
+        for (int i = 0; i < 32; ++i) s = s + v[i];
     }
     for (; m < M; ++m) s = s + g[(size_t)m * N + n];
     out[n] = s;
