@@ -147,7 +147,7 @@ def train_step(args, bnn, workloads, G, torch) -> int:
         WpT = [G.word_tensor(w.shape[1], w.shape[0], wb) for w in Ws]
         hhat = [f32(M, w.shape[0]) for w in Ws]
         bits = [G.word_tensor(M, w.shape[0], wb) for w in Ws[:-1]]
-        xreal = [None] + [f32(M, w.shape[1]) for w in Ws[1:]]
+        hbT = [None] + [G.word_tensor(w.shape[1], M, wb) for w in Ws[1:]]
         gbuf = [f32(M, w.shape[0]) for w in Ws]
         gin = [f32(M, w.shape[1]) for w in Ws]
         gt = [f32(w.shape[0], M) for w in Ws]
@@ -181,14 +181,13 @@ def train_step(args, bnn, workloads, G, torch) -> int:
                 g = gbuf[l]
                 if l < L - 1:
                     bnn.bnn_mask_grad(P(g), P(hhat[l]), M * N, 1.0, P(g), st)
-                if l == 0:
-                    h = X
-                else:
-                    bnn.bnn_unpack_activations(P(bits[l - 1]), M, K, wb, 0, P(xreal[l]), st)
-                    h = xreal[l]
                 bnn.bnn_transpose_f32(P(g), M, N, P(gt[l]), st)
-                bnn.bnn_transpose_f32(P(h), M, K, P(ht[l]), st)
-                bnn.bnn_backward_weight(P(gt[l]), P(ht[l]), N, K, M, P(gw[l]), st)
+                if l == 0:          # real input frames
+                    bnn.bnn_transpose_f32(P(X), M, K, P(ht[l]), st)
+                    bnn.bnn_backward_weight(P(gt[l]), P(ht[l]), N, K, M, P(gw[l]), st)
+                else:               # the input is Sign(hhat of the layer below): its transposed bits, add/subtract
+                    bnn.bnn_pack_weights_transposed(P(hhat[l - 1]), M, K, wb, P(hbT[l]), st)
+                    bnn.bnn_backward_weight_binh(P(gt[l]), P(hbT[l]), N, K, M, wb, P(gw[l]), st)
                 bnn.bnn_bias_grad(P(g), M, N, P(gr[l]), st)
                 if l > 0:
                     bnn.bnn_backward_input_binw(P(g), P(WpT[l]), M, N, K, wb, P(gbuf[l - 1]), st)
@@ -219,7 +218,7 @@ def train_step(args, bnn, workloads, G, torch) -> int:
                           "ms_per_step": round(total, 3), "frames_per_s": round(M / (total * 1e-3), 1),
                           "phase_ms": {k: round(v, 3) for k, v in ms.items()},
                           "tflops_products": round(flops / (total * 1e-3) / 1e12, 1)}), flush=True)
-        del X, labels, W, r, Wp, WpT, hhat, bits, xreal, gbuf, gin, gt, ht, gw, gr
+        del X, labels, W, r, Wp, WpT, hhat, bits, hbT, gbuf, gin, gt, ht, gw, gr
         torch.cuda.empty_cache()
     return 0
 

@@ -271,6 +271,14 @@ int bnn_backward_input_realw(const float* g_hhat, const float* Wt, int64_t M, in
  *   binary input first through bnn_unpack_activations);  g_w out [N][K]. */
 int bnn_backward_weight(const float* g_hhat_t, const float* h_t, int64_t N, int64_t K, int64_t M, float* g_w, void* stream);
 
+/* The same gradient when the layer's input is the output of Sign units (Alg. 2: h_{l-1} in {-1, +1}): every product is
+ * an add or a subtract, g_w[n][k] = sum_m (HpT bit (k, m) ? +g_hhat_t[n][m] : -g_hhat_t[n][m]), ascending m: the kernels of
+ * bnn_layer_binw_realx with the frames as the summed index.  Same results as bnn_backward_weight on the unpacked input.
+ *   HpT words [K][bnn_packed_words(M, word_bits)]: the bits of h_{l-1}^T packed along the frames, e.g. from
+ *   bnn_pack_weights_transposed(hhat_{l-1}, M, K, ...), since h_{l-1} = Sign(hhat_{l-1}). */
+int bnn_backward_weight_binh(const float* g_hhat_t, const void* HpT, int64_t N, int64_t K, int64_t M, int word_bits,
+                             float* g_w, void* stream);
+
 /* Alg. 1 and Alg. 2 backward, g_{r_l} = g_{hhat_l} summed over the minibatch: g_r[n] = sum_m g_hhat[m][n], ascending m. */
 int bnn_bias_grad(const float* g_hhat, int64_t M, int64_t N, float* g_r, void* stream);
 

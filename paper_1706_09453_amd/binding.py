@@ -64,6 +64,7 @@ _SIGNATURES = {
     "bnn_backward_input_binw": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_void_p, c_void_p]),
     "bnn_backward_input_realw": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p]),
     "bnn_backward_weight": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p]),
+    "bnn_backward_weight_binh": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_void_p, c_void_p]),
     "bnn_bias_grad": (c_int, [c_void_p, c_int64, c_int64, c_void_p, c_void_p]),
     "bnn_update_clip": (c_int, [c_void_p, c_void_p, c_int64, c_float, c_int, c_void_p]),
     "bnn_grad_norm_clip": (c_int, [c_void_p, c_int64, c_float, c_void_p, c_void_p, c_void_p]),
@@ -172,6 +173,10 @@ def bnn_backward_input_realw(g_hhat: int, Wt: int, M: int, N: int, K: int, g_h: 
 
 def bnn_backward_weight(g_hhat_t: int, h_t: int, N: int, K: int, M: int, g_w: int, stream: int = 0) -> int:
     return _check(_lib.bnn_backward_weight(g_hhat_t, h_t, N, K, M, g_w, stream or None))
+
+
+def bnn_backward_weight_binh(g_hhat_t: int, HpT: int, N: int, K: int, M: int, word_bits: int, g_w: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_backward_weight_binh(g_hhat_t, HpT, N, K, M, word_bits, g_w, stream or None))
 
 
 def bnn_bias_grad(g_hhat: int, M: int, N: int, g_r: int, stream: int = 0) -> int:

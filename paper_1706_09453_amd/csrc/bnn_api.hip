@@ -793,6 +793,14 @@ BNN_EXPORT int bnn_backward_weight(const float* g_hhat_t, const float* h_t, int6
     return run_realw(g_hhat_t, h_t, nullptr, N, M, K, BNN_ACT_LINEAR, 32, g_w, static_cast<hipStream_t>(stream));
 }
 
+BNN_EXPORT int bnn_backward_weight_binh(const float* g_hhat_t, const void* HpT, int64_t N, int64_t K, int64_t M, int word_bits,
+                                        float* g_w, void* stream) {
+    if (M <= 0) return BNN_ESHAPE;
+    const int rc = check_layer_args(g_hhat_t, HpT, N, M, K, BNN_ACT_LINEAR, word_bits, g_w, false);
+    if (rc != BNN_OK) return rc;
+    return run_realx(g_hhat_t, HpT, nullptr, nullptr, N, M, K, BNN_ACT_LINEAR, word_bits, g_w, static_cast<hipStream_t>(stream));
+}
+
 BNN_EXPORT int bnn_bias_grad(const float* g_hhat, int64_t M, int64_t N, float* g_r, void* stream) {
     if (M < 0 || N <= 0 || M > kMaxDim || N > kMaxDim) return BNN_ESHAPE;
     if (!g_hhat || !g_r) return BNN_EINVAL;

@@ -134,6 +134,23 @@ def test_weight_gradient_of_a_binary_input(G, bnn, oracle, T):
         assert np.array_equal(gw.cpu().numpy(), T.backward_weight(g, oracle.bits_to_real(words, K, 32, zero_one)))
 
 
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("M,N,K", SHAPES + [(4096, 64, 300)])
+def test_weight_gradient_of_sign_units_by_add_and_subtract(G, bnn, oracle, T, M, N, K, wb):
+    """g_w = g_hhat^T h for h = Sign(hhat_prev) from the bits of h^T packed along the frames: same bits as the product
+    with the unpacked input."""
+    rng = np.random.default_rng(M + 2 * N + K)
+    g = rng.standard_normal((M, N)).astype(np.float32)
+    hhat_prev = rng.standard_normal((M, K)).astype(np.float32)
+    dg, dhh = G.to_dev(g), G.to_dev(hhat_prev)
+    gt, HpT, gw = _f32(N, M), G.word_tensor(K, M, wb), _f32(N, K)
+    bnn.bnn_transpose_f32(G.ptr(dg), M, N, G.ptr(gt), G.stream())
+    bnn.bnn_pack_weights_transposed(G.ptr(dhh), M, K, wb, G.ptr(HpT), G.stream())
+    bnn.bnn_backward_weight_binh(G.ptr(gt), G.ptr(HpT), N, K, M, wb, G.ptr(gw), G.stream())
+    want = T.backward_weight(g, np.where(hhat_prev > 0, 1.0, -1.0).astype(np.float32))
+    assert np.array_equal(gw.cpu().numpy(), want)
+
+
 @pytest.mark.parametrize("clip", [0, 1])
 def test_update_clip(G, bnn, T, clip):
     rng = np.random.default_rng(5)
