@@ -254,6 +254,12 @@ int bnn_softmax_xent_grad(const float* logp, const int32_t* labels, int64_t M, i
  * 1 otherwise; k > 0.   g_h, hhat [count];  g_hhat out [count] (may be g_h itself). */
 int bnn_mask_grad(const float* g_h, const float* hhat, int64_t count, float k, float* g_hhat, void* stream);
 
+/* Gradient through a Sigmoid layer (Alg. 1, "gradients through f_l"; the real hidden layers of Sec. 3):
+ * g_hhat = g_h * (h * (1 - h)), h = the layer's OUTPUT; fp32, each operation rounded.  A hard-tanh layer's derivative is
+ * bnn_mask_grad with k = 1 on its pre-activation; a linear layer's is the identity.
+ *   g_h, h [count];  g_hhat out [count] (may be g_h itself). */
+int bnn_sigmoid_grad(const float* g_h, const float* h, int64_t count, float* g_hhat, void* stream);
+
 /* Alg. 1 backward, g_{h_{l-1}} = g_{hhat_l} w^b_l: g_h[m][k] = sum_n (WpT bit (k, n) ? +g_hhat[m][n] : -g_hhat[m][n]),
  * fp32, ascending n, one accumulator per result (the kernels of bnn_layer_binw_realx on the transposed signs).
  *   g_hhat [M][N];  WpT [K][bnn_packed_words(N, word_bits)] from bnn_pack_weights_transposed;  g_h out [M][K]. */

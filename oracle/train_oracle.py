@@ -39,6 +39,15 @@ def mask_grad(g_h: np.ndarray, hhat: np.ndarray, k: float) -> np.ndarray:
     return np.where(np.abs(hh) > np.float32(k), np.float32(0.0), g).astype(np.float32)
 
 
+def sigmoid_grad(g_h: np.ndarray, h: np.ndarray) -> np.ndarray:
+    """Alg. 1 backward through a Sigmoid layer (the real hidden layers of Sec. 3): g_{h^} = g_h f'(h^) with
+    f'(h^) = h (1 - h), h the layer's output; fp32, evaluated as g_h * (h * (1 - h)), every operation rounded."""
+    g = np.ascontiguousarray(g_h, dtype=np.float32)
+    hh = np.ascontiguousarray(h, dtype=np.float32)
+    one_minus = (np.float32(1.0) - hh).astype(np.float32)
+    return (g * (hh * one_minus).astype(np.float32)).astype(np.float32)
+
+
 def backward_input_binw(g_hhat: np.ndarray, w_pm1: np.ndarray) -> np.ndarray:
     """Alg. 1 backward: g_{h_{l-1}} = g_{h^_l} w^b_l, [M][N] x [N][K] -> [M][K]; sum over n ascending (add/subtract)."""
     wt = np.ascontiguousarray(np.asarray(w_pm1, dtype=np.int8).T)          # [K][N]

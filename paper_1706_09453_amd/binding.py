@@ -61,6 +61,7 @@ _SIGNATURES = {
     "bnn_transpose_f32": (c_int, [c_void_p, c_int64, c_int64, c_void_p, c_void_p]),
     "bnn_softmax_xent_grad": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_void_p]),
     "bnn_mask_grad": (c_int, [c_void_p, c_void_p, c_int64, c_float, c_void_p, c_void_p]),
+    "bnn_sigmoid_grad": (c_int, [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]),
     "bnn_backward_input_binw": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_void_p, c_void_p]),
     "bnn_backward_input_realw": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p]),
     "bnn_backward_weight": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p]),
@@ -161,6 +162,10 @@ def bnn_softmax_xent_grad(logp: int, labels: int, M: int, N: int, g: int, stream
 
 def bnn_mask_grad(g_h: int, hhat: int, count: int, k: float, g_hhat: int, stream: int = 0) -> int:
     return _check(_lib.bnn_mask_grad(g_h, hhat, count, k, g_hhat, stream or None))
+
+
+def bnn_sigmoid_grad(g_h: int, h: int, count: int, g_hhat: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_sigmoid_grad(g_h, h, count, g_hhat, stream or None))
 
 
 def bnn_backward_input_binw(g_hhat: int, WpT: int, M: int, N: int, K: int, word_bits: int, g_h: int, stream: int = 0) -> int:

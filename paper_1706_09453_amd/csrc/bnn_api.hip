@@ -769,6 +769,15 @@ BNN_EXPORT int bnn_mask_grad(const float* g_h, const float* hhat, int64_t count,
     return launch_status();
 }
 
+BNN_EXPORT int bnn_sigmoid_grad(const float* g_h, const float* h, int64_t count, float* g_hhat, void* stream) {
+    if (count < 0) return BNN_ESHAPE;
+    if (count == 0) return BNN_OK;
+    if (!g_h || !h || !g_hhat) return BNN_EINVAL;
+    if (!aligned(g_h, 4) || !aligned(h, 4) || !aligned(g_hhat, 4)) return BNN_EALIGN;
+    sigmoid_grad_kernel<<<elementwise_blocks(count), 256, 0, static_cast<hipStream_t>(stream)>>>(g_h, h, count, g_hhat);
+    return launch_status();
+}
+
 BNN_EXPORT int bnn_backward_input_binw(const float* g_hhat, const void* WpT, int64_t M, int64_t N, int64_t K, int word_bits,
                                        float* g_h, void* stream) {
     // the forward layer with the roles exchanged: "inputs" are the N gradients of a frame, "outputs" the K inputs

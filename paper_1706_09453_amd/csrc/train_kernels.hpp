@@ -70,6 +70,17 @@ __global__ __launch_bounds__(256) void mask_grad_kernel(const float* __restrict_
         out[e] = __builtin_fabsf(hhat[e]) > k ? 0.0f : g_h[e];
 }
 
+// Alg. 1 backward through a Sigmoid layer: g_{h^} = g_h * (h * (1 - h)) with h the layer's output, every operation
+// rounded in fp32 (no contraction: the library is built with -ffp-contract=off).  out may be g_h itself.
+__global__ __launch_bounds__(256) void sigmoid_grad_kernel(const float* __restrict__ g_h, const float* __restrict__ h,
+                                                           int64_t count, float* __restrict__ out) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256) {
+        const float v = h[e];
+        const float d = v * (1.0f - v);
+        out[e] = g_h[e] * d;
+    }
+}
+
 // g_r[n] = sum_m g[m][n] in fp32, ascending m, one accumulator per n (lanes <-> n: every row is read coalesced; 32
 // rows are requested at a time, the additions stay in order).  Grid: x = ceil(N / 64), one wave per workgroup.
 __global__ __launch_bounds__(64) void colsum_kernel(const float* __restrict__ g, int M, int N, float* __restrict__ out) {

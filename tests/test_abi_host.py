@@ -134,6 +134,8 @@ def test_training_argument_validation(bnn):
     assert _status(bnn.bnn_mask_grad, P, Q, 16, 0.0, R, 0) == E                      # k must be positive
     assert _status(bnn.bnn_mask_grad, P, Q, -1, 1.0, R, 0) == S
     assert _status(bnn.bnn_mask_grad, P, 0, 16, 1.0, R, 0) == E
+    assert _status(bnn.bnn_sigmoid_grad, P, 0, 16, R, 0) == E
+    assert _status(bnn.bnn_sigmoid_grad, P, Q, -2, R, 0) == S
     assert _status(bnn.bnn_backward_input_binw, P, 0, 4, 64, 64, 32, R, 0) == E
     assert _status(bnn.bnn_backward_input_binw, P, Q, 4, 64, 64, 16, R, 0) == S
     assert _status(bnn.bnn_backward_input_realw, P, Q + 2, 4, 64, 64, R, 0) == A

@@ -81,6 +81,17 @@ def test_mask_grad(G, bnn, T, k):
     assert np.array_equal(dg.cpu().numpy(), T.mask_grad(g, hh, k), equal_nan=True)
 
 
+def test_sigmoid_grad(G, bnn, T):
+    rng = np.random.default_rng(3)
+    g = rng.standard_normal(200001).astype(np.float32)
+    h = (1.0 / (1.0 + np.exp(-rng.standard_normal(200001) * 3))).astype(np.float32)
+    h[:3] = [0.0, 1.0, 0.5]
+    dg, dh = G.to_dev(g), G.to_dev(h)
+    out = torch.full((g.size,), float("nan"), dtype=torch.float32, device="cuda:0")
+    bnn.bnn_sigmoid_grad(G.ptr(dg), G.ptr(dh), g.size, G.ptr(out), G.stream())
+    assert np.array_equal(out.cpu().numpy(), T.sigmoid_grad(g, h))
+
+
 @pytest.mark.parametrize("wb", [32, 64])
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_backward_input_binw(G, bnn, oracle, T, M, N, K, wb):

@@ -45,8 +45,7 @@ def test_backward_of_a_real_network_matches_finite_differences(oracle, T):
         gr[l] = T.bias_grad(g_hhat)
         if l > 0:
             g_h = T.backward_input_realw(g_hhat, Ws[l])
-            s = hs[l].astype(np.float64)
-            g_hhat = (g_h * s * (1.0 - s)).astype(np.float32)      # through the Sigmoid of layer l
+            g_hhat = T.sigmoid_grad(g_h, hs[l])                    # through the Sigmoid of layer l
     eps = 1e-4
     for l in range(3):
         for (n, k) in [(0, 0), (1, 2), (dims[l + 1] - 1, dims[l] - 1)]:
@@ -113,6 +112,17 @@ def test_mask_grad_hand_cases(T):
     a, b = rng.standard_normal(1000).astype(np.float32), (rng.standard_normal(1000) * 2).astype(np.float32)
     for k in (0.5, 1.0, 2.0, 3.0):
         assert np.array_equal(T.mask_grad(a, b, k), a * (np.abs(b) <= np.float32(k)))
+
+
+def test_sigmoid_grad(T):
+    h = np.array([0.5, 0.25, 1.0, 0.0, 0.75], np.float32)
+    g = np.array([4.0, -16.0, 3.0, 3.0, 1.0], np.float32)
+    assert np.array_equal(T.sigmoid_grad(g, h), np.array([1.0, -3.0, 0.0, 0.0, 0.1875], np.float32))
+    # against the derivative of scipy's expit by central differences
+    z = np.linspace(-6, 6, 49)
+    fd = (scipy.special.expit(z + 1e-6) - scipy.special.expit(z - 1e-6)) / 2e-6
+    got = T.sigmoid_grad(np.ones_like(z, dtype=np.float32), scipy.special.expit(z).astype(np.float32))
+    assert np.max(np.abs(got - fd)) <= 1e-6
 
 
 def test_update_clip(T):
