@@ -164,3 +164,41 @@ def test_semi_stochastic_binarize(T):
     assert np.array_equal(np.sign(out), np.sign(w)) and np.array_equal(out[~locked], w[~locked])
     # a weight near +-1 is locked far more often than one near 0
     assert locked[np.abs(w) > 0.9].mean() > 0.9 and locked[np.abs(w) < 0.1].mean() < 0.1
+
+
+def test_alg1_training_reduces_the_loss_of_a_binary_weight_network(oracle, T):
+    """Alg. 1 end to end with the oracle's own steps: binary weights in every layer, Sigmoid hidden units, clipped
+    updates of the real-valued weights.  Twenty minibatch steps on a fixed synthetic task lower the cross entropy:
+    a wrong sign or a transposed operand anywhere in the backward pass or the update would raise it instead."""
+    rng = _rng(11)
+    dims, M, eta = (12, 16, 16, 4), 64, 0.01
+    X = rng.standard_normal((M, dims[0])).astype(np.float32)
+    teacher = rng.standard_normal((dims[0], dims[-1]))
+    labels = np.argmax(X @ teacher, axis=1)
+    Ws = [rng.uniform(-1, 1, (n, k)).astype(np.float32) for k, n in zip(dims[:-1], dims[1:])]
+    rs = [np.zeros(n, np.float32) for n in dims[1:]]
+
+    def forward(Ws, rs):
+        hs, h = [X], X
+        for l, (W, r) in enumerate(zip(Ws, rs)):
+            Wb = np.where(W > 0, 1, -1).astype(np.int8)                       # w^b = Sign(w)
+            hhat = oracle.affine_f32(oracle.realx_acc(h, Wb, want64=False)[0], np.full(len(r), 0.25, np.float32), r)
+            h = oracle.sigmoid(hhat) if l < len(Ws) - 1 else oracle.log_softmax(hhat)[0]
+            hs.append(h)
+        return hs
+
+    losses = []
+    for step in range(20):
+        hs = forward(Ws, rs)
+        losses.append(-float(hs[-1][np.arange(M), labels].sum()))
+        g = T.softmax_xent_grad(hs[-1], labels)
+        for l in (2, 1, 0):
+            g = g * np.float32(0.25)                                          # the constant scale of this toy network
+            gW, gr = T.backward_weight(g, hs[l]), T.bias_grad(g)
+            if l > 0:
+                g = T.sigmoid_grad(T.backward_input_binw(g, np.where(Ws[l] > 0, 1, -1).astype(np.int8)), hs[l])
+            Ws[l] = T.update_clip(Ws[l], T.grad_norm_clip(gW, 15.0)[0], eta, True)
+            rs[l] = T.update_clip(rs[l], gr, eta, False)
+        assert all(np.abs(W).max() <= 1.0 for W in Ws)
+    assert losses[-1] < 0.95 * losses[0] and min(losses) < 0.95 * losses[0], losses
+    assert sum(b < a for a, b in zip(losses[:-1], losses[1:])) >= 12, losses   # most steps lower it (weights flip in jumps)
