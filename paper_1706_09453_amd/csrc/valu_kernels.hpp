@@ -1,13 +1,14 @@
-// Vector-ALU kernels: lanes <-> outputs n, frames streamed through scalar registers.
+// Vector-ALU kernels: lanes <-> outputs n.
 //
-//   realx_valu_kernel  binary weights x real input   (paper Alg. 1 forward: add/subtract product)
-//   binx_valu_kernel   binary weights x binary input (paper Sec. 2.3: XOR + popcount)
+//   realx_valu_lds_kernel  binary weights x real input, large batches  (paper Alg. 1 forward: add/subtract product)
+//   realx_valu_kernel      the same for batches of a few frames and for rows that are not 16-byte aligned
+//   binx_valu_kernel       binary weights x binary input (paper Sec. 2.3: XOR + popcount), -1/+1 or 0/1 reading
 //
-// Both are output-stationary: one wavefront owns 64 outputs n (one per lane) for TM frames, so every
-// output has exactly one accumulator and one writer.  What a lane needs of the weights is its own
-// packed row (vector loads); what it needs of the frames is the same for all 64 lanes, so the frame
-// operands are wave-uniform and arrive through the scalar cache as SGPR operands of the VALU
-// instruction: no LDS traffic and no cross-lane exchange in the inner loop.
+// All are output-stationary: one wavefront owns 64 outputs n per lane slot for TM frames, so every output has
+// exactly one accumulator and one writer and its sum runs in ascending k.  What a lane needs of the weights is its
+// own packed row (vector loads).  What it needs of the frames is the same for all 64 lanes; it arrives, depending
+// on the kernel, as a broadcast read of a tile staged in LDS, by the DPP row broadcast of a value held once per 16
+// lanes, or through the scalar cache as an SGPR operand (the binary kernel's frame words).
 #pragma once
 
 #include <type_traits>
