@@ -67,13 +67,14 @@ typedef enum bnn_binx_arm {
     BNN_ARM_MFMA_I8 = 3    /* +-1 expanded in registers to int8, int8 MFMA with int32 accumulate (comparison)  */
 } bnn_binx_arm;
 
-/* Kernel-selection knobs for bnn_set_option (measurement and tuning; results never change). */
+/* Kernel-selection knobs for bnn_set_option (measurement and tuning; results never change, except that
+ * BNN_OPT_REALX_F32_MFMA moves fp32 outputs within rounding, as its comment says). */
 typedef enum bnn_option {
     BNN_OPT_BINX_ARM = 1,      /* arm used for BNN_ARM_AUTO: BNN_ARM_VALU_XOR, BNN_ARM_MFMA or BNN_ARM_MFMA_I8   */
     BNN_OPT_REALX_TM = 2,      /* real-input vector-ALU kernel: 0 (default) = frames staged through LDS, 16 frames x 4
                                   outputs per lane, where K % 4 == 0 and X is 16-byte aligned; 1, 2, 4, 8, 16 or 32 =
                                   that many frames per wavefront on the row-broadcast kernel.  Same results.        */
-    BNN_OPT_BINX_VALU_TM = 3,  /* frames per wavefront of the XOR/popcount kernel: 8, 16 or 32                  */
+    BNN_OPT_BINX_VALU_TM = 3,  /* frames per wavefront of the XOR/popcount kernel: 1, 2, 4, 8, 16 (default) or 32  */
     BNN_OPT_MFMA_WM = 4,       /* 16-row accumulator fragments per wavefront of the matrix-core kernel: 2 or 4  */
     BNN_OPT_REALX_SIGN_MFMA = 5, /* bnn_forward, first layer real input -> Sign: 1 = matrix-core filter with exact
                                    resolution of uncertain outputs (default), 0 = vector-ALU kernel; same bits  */
