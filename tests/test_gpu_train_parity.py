@@ -255,7 +255,7 @@ def test_one_training_step_of_a_binary_network(G, bnn, oracle, T):
     Wp = G.word_tensor(N, K, 32)
     bnn.bnn_pack_weights(G.ptr(dW[-1]), N, K, 32, G.ptr(Wp), 0, st)
     bnn.bnn_layer_binw_binx(G.ptr(acts[-1]), G.ptr(Wp), 0, G.ptr(dr[-1]), M, K, N, bnn.BNN_ACT_LOGSOFTMAX, 32, G.ptr(logp), st)
-    dg = _f32(M, 30)
+    dg, dlab = _f32(M, 30), G.to_dev(labels)
     bnn.bnn_softmax_xent_grad(G.ptr(logp), G.ptr(dlab), M, 30, G.ptr(dg), st)
     ws = torch.empty(4096, dtype=torch.uint8, device="cuda:0")
     norm = torch.zeros(1, dtype=torch.float32, device="cuda:0")
@@ -287,3 +287,91 @@ def test_one_training_step_of_a_binary_network(G, bnn, oracle, T):
         got_w = dW[l].cpu().numpy()
         assert np.max(np.abs(got_w - want_w)) <= 1e-6 and np.abs(got_w).max() <= 1.0
         assert np.mean(np.sign(got_w) == np.sign(want_w)) > 0.9999
+
+
+def test_backward_of_the_paper_topology(G, bnn, oracle, T):
+    """(sigma, b, b, sigma, delta) with real-valued input and Softmax weights and binary weights in between (Table 2,
+    Sec. 3.1), small: the forward pass keeps pre-activations, the backward pass goes through every kind of step
+    (Sigmoid derivative, Mask, both weight-gradient forms, both input-gradient forms).  Each gradient is checked
+    against the oracle's, which is fed the GPU's own incoming gradient of that layer (layer-by-layer, so that the
+    fp64 exp of the Softmax gradient cannot make later comparisons inexact)."""
+    import workloads
+    cfg = workloads.NetConfig(22, "train paper topology", (40, 64, 96, 64, 70, 30), 130,
+                              ("sigmoid", "sign", "sign", "sigmoid"), 32, real_weight_layers=(0, 4))
+    Ws, rs = workloads.make_net_params(cfg)
+    X = workloads.make_frames(cfg)
+    M, L, st = cfg.M, 5, G.stream()
+    acts = ["sigmoid", "sign", "sign", "sigmoid", "logsoftmax"]
+    labels = np.random.default_rng(2).integers(0, 30, M).astype(np.int32)
+    # ---- forward on the GPU, keeping what the backward pass needs; checked against the oracle as it goes
+    dX = G.to_dev(X)
+    dW = [G.to_dev(W) for W in Ws]
+    dr = [G.to_dev(r) for r in rs]
+    h_real = [dX]          # real-valued input of layer l (frames, Sigmoid outputs) or None where the input is bits
+    h_bits, hhat = [None], []
+    for l in range(L):
+        N, K = Ws[l].shape
+        z = _f32(M, N)
+        if l in cfg.real_weight_layers:
+            bnn.bnn_layer_realw(G.ptr(h_real[l]), G.ptr(dW[l]), G.ptr(dr[l]), M, K, N, bnn.BNN_ACT_LINEAR, 32, G.ptr(z), st)
+        else:
+            Wp = G.word_tensor(N, K, 32)
+            bnn.bnn_pack_weights(G.ptr(dW[l]), N, K, 32, G.ptr(Wp), 0, st)
+            if h_real[l] is not None:
+                bnn.bnn_layer_binw_realx(G.ptr(h_real[l]), G.ptr(Wp), 0, G.ptr(dr[l]), M, K, N, bnn.BNN_ACT_LINEAR, 32, G.ptr(z), st)
+            else:
+                bnn.bnn_layer_binw_binx(G.ptr(h_bits[l]), G.ptr(Wp), 0, G.ptr(dr[l]), M, K, N, bnn.BNN_ACT_LINEAR, 32, G.ptr(z), st)
+        hhat.append(z)
+        zh = z.cpu().numpy()
+        if acts[l] == "sign":
+            h_bits.append(G.pack_activations(z, 32)); h_real.append(None)
+        elif acts[l] == "sigmoid":
+            h_real.append(G.to_dev(oracle.sigmoid(zh))); h_bits.append(None)     # the oracle's Sigmoid of the GPU's h^
+        else:
+            logp = G.to_dev(oracle.log_softmax(zh)[0])
+    # ---- backward
+    dg, dlab = _f32(M, 30), G.to_dev(labels)
+    bnn.bnn_softmax_xent_grad(G.ptr(logp), G.ptr(dlab), M, 30, G.ptr(dg), st)
+    assert np.max(np.abs(dg.cpu().numpy() - T.softmax_xent_grad(logp.cpu().numpy(), labels))) <= 1e-6
+    for l in range(L - 1, -1, -1):
+        N, K = Ws[l].shape
+        g_in = dg.cpu().numpy()                                  # the oracle continues from the GPU's gradient
+        if acts[l] == "sign":
+            bnn.bnn_mask_grad(G.ptr(dg), G.ptr(hhat[l]), M * N, 1.0, G.ptr(dg), st)
+            want_g = T.mask_grad(g_in, hhat[l].cpu().numpy(), 1.0)
+        elif acts[l] == "sigmoid":
+            bnn.bnn_sigmoid_grad(G.ptr(dg), G.ptr(h_real[l + 1]), M * N, G.ptr(dg), st)
+            want_g = T.sigmoid_grad(g_in, h_real[l + 1].cpu().numpy())
+        else:
+            want_g = g_in
+        assert np.array_equal(dg.cpu().numpy(), want_g), l
+        gt, gw = _f32(N, M), _f32(N, K)
+        gr = torch.empty(N, dtype=torch.float32, device="cuda:0")
+        bnn.bnn_transpose_f32(G.ptr(dg), M, N, G.ptr(gt), st)
+        if h_real[l] is not None:                                 # real input: multiply kernel
+            ht = _f32(K, M)
+            bnn.bnn_transpose_f32(G.ptr(h_real[l]), M, K, G.ptr(ht), st)
+            bnn.bnn_backward_weight(G.ptr(gt), G.ptr(ht), N, K, M, G.ptr(gw), st)
+            want_gw = T.backward_weight(want_g, h_real[l].cpu().numpy())
+        else:                                                     # input = Sign(h^ of the layer below): add/subtract kernel
+            HpT = G.word_tensor(K, M, 32)
+            bnn.bnn_pack_weights_transposed(G.ptr(hhat[l - 1]), M, K, 32, G.ptr(HpT), st)
+            bnn.bnn_backward_weight_binh(G.ptr(gt), G.ptr(HpT), N, K, M, 32, G.ptr(gw), st)
+            want_gw = T.backward_weight(want_g, np.where(hhat[l - 1].cpu().numpy() > 0, 1.0, -1.0).astype(np.float32))
+        bnn.bnn_bias_grad(G.ptr(dg), M, N, G.ptr(gr), st)
+        assert np.array_equal(gw.cpu().numpy(), want_gw), l
+        assert np.array_equal(gr.cpu().numpy(), T.bias_grad(want_g)), l
+        if l > 0:
+            gh = _f32(M, K)
+            if l in cfg.real_weight_layers:
+                Wt = _f32(K, N)
+                bnn.bnn_transpose_f32(G.ptr(dW[l]), N, K, G.ptr(Wt), st)
+                bnn.bnn_backward_input_realw(G.ptr(dg), G.ptr(Wt), M, N, K, G.ptr(gh), st)
+                want_gh = T.backward_input_realw(want_g, Ws[l])
+            else:
+                WpT = G.word_tensor(K, N, 32)
+                bnn.bnn_pack_weights_transposed(G.ptr(dW[l]), N, K, 32, G.ptr(WpT), st)
+                bnn.bnn_backward_input_binw(G.ptr(dg), G.ptr(WpT), M, N, K, 32, G.ptr(gh), st)
+                want_gh = T.backward_input_binw(want_g, np.where(Ws[l] > 0, 1, -1).astype(np.int8))
+            assert np.array_equal(gh.cpu().numpy(), want_gh), l
+            dg = gh
