@@ -19,7 +19,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 # Published MI355X peaks used as roofline denominators.
 PEAK_MFMA_FP4_TFLOPS = 10100.0          # dense fp4/fp6 MFMA
@@ -253,7 +252,7 @@ def main() -> int:
 
     import paper_1706_09453_amd as bnn
     import workloads
-    import gpu_util as G
+    import harness as G
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.gemm_sweep:
@@ -406,6 +405,10 @@ def main() -> int:
                                   "gpu_vs_oracle_max_abs_err": err,
                                   "oracle_output_scale": float(np.max(np.abs(ref)))}
     print(json.dumps(result))
+    cb = result.get("cpu_baseline")
+    if cb and not cb["gpu_vs_oracle_max_abs_err"] <= 1e-4 * cb["oracle_output_scale"]:
+        print("bench.py: the timed output disagrees with the oracle beyond 1e-4 of the output scale", file=sys.stderr)
+        return 1
     return 0
 
 

@@ -26,7 +26,7 @@
  *     here writes pad bits as 0 and every consumer assumes they are 0.  A 64-bit
  *     packed row is byte-identical to the 32-bit packed row padded to a multiple of 8 bytes.
  *   - word_bits is 32 or 64.  Packed pointers must be aligned to word_bits/8 bytes, fp32 pointers to 4.
- *   - M, K and N are at most 2^30 (K < 2^24 for a binary input).
+ *   - M and K are at most 2^30 (K < 2^24 for a binary input), N at most 2^22; beyond that: BNN_ESHAPE.
  *   - Output buffers must not overlap input buffers.
  *   - Return value: BNN_OK (0) or a negative bnn_status.  On error nothing has been
  *     enqueued.  M == 0 is valid and does nothing.

@@ -50,6 +50,7 @@ inline bool overlap(const void* a, size_t na, const void* b, size_t nb) {
 inline int launch_status() { return hipGetLastError() == hipSuccess ? BNN_OK : BNN_EDEVICE; }
 
 constexpr int64_t kMaxDim = (int64_t)1 << 30;
+constexpr int64_t kMaxN = (int64_t)1 << 22;   // outputs of a layer: the second grid dimension (65535) counts tiles of 128 or 256 of them
 
 size_t out_bytes(int64_t M, int64_t N, int act, int wb) {
     if (act == BNN_ACT_SIGN) return (size_t)M * (size_t)row_w32(N, wb) * 4;
@@ -58,7 +59,7 @@ size_t out_bytes(int64_t M, int64_t N, int act, int wb) {
 
 int check_layer_args(const void* X, const void* Wp, int64_t M, int64_t K, int64_t N, int act, int wb, const void* Y,
                      bool binx, bool realw = false) {
-    if (!word_bits_ok(wb) || M < 0 || K <= 0 || N <= 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim) return BNN_ESHAPE;
+    if (!word_bits_ok(wb) || M < 0 || K <= 0 || N <= 0 || M > kMaxDim || K > kMaxDim || N > kMaxN) return BNN_ESHAPE;
     if (binx && K >= ((int64_t)1 << 24)) return BNN_ESHAPE;
     if (act < BNN_ACT_RAW_I32 || act > BNN_ACT_SIGMOID) return BNN_EINVAL;
     if (!binx && act == BNN_ACT_RAW_I32) return BNN_EINVAL;
@@ -104,27 +105,12 @@ void launch_realx_tm(const float* X, const uint32_t* Wp, const float* scale, con
     else launch_realx_tm_b<TM, false>(X, Wp, scale, bias, M, K, N, w32, act, Y, yw32, st);
 }
 
-// The fp32 matrix-core kernel runs one workgroup per CU: two that share a CU evict each other's operand rows from
-// the L1 (measured: 1.06 ms against 0.54 ms on 432 workgroups).  Its register count (140 + 128 accumulation registers)
-// admits only one at present; so that this does not hang on a compiler's register allocation, the launch also asks
-// for dynamic LDS that the kernel never touches, enough that two workgroups do not fit the CU's 160 KiB together.
-constexpr unsigned kF32MfmaPadLds = 48 * 1024;   // + 34 KiB of static LDS > 80 KiB
+// The fp32 matrix-core kernel runs one workgroup per CU (measured: 1.06 ms with two against 0.54 ms on 432 workgroups);
+// the kernel's own occupancy attribute says so.
 template <int ACT, bool VEC, bool WREAL>
 void launch_f32_mfma(dim3 grid, dim3 block, hipStream_t st, const float* X, const void* W, const float* scale,
                      const float* bias, int M, int K, int N, int w32, float* Y) {
-    const unsigned pad = (size_t)grid.x * grid.y > 256 ? kF32MfmaPadLds : 0;   // up to 256 workgroups get a CU each anyway
-    if (pad) {   // static + dynamic LDS above 64 KiB has to be allowed once per kernel and device
-        static std::atomic<uint64_t> allowed{0};
-        int dev = 0;
-        (void)hipGetDevice(&dev);
-        const uint64_t bit = 1ull << (dev & 63);
-        if (!(allowed.load() & bit)) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&realx_f32_mfma_kernel<ACT, VEC, WREAL>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)pad);
-            allowed.fetch_or(bit);
-        }
-    }
-    realx_f32_mfma_kernel<ACT, VEC, WREAL><<<grid, block, pad, st>>>(X, W, scale, bias, M, K, N, w32, Y);
+    realx_f32_mfma_kernel<ACT, VEC, WREAL><<<grid, block, 0, st>>>(X, W, scale, bias, M, K, N, w32, Y);
 }
 
 void launch_log_softmax(float* Z, int M, int N, hipStream_t st) {
@@ -463,7 +449,8 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
         const bool pinned = g_mfma32_pipeline.load() != 2 && (size_t)M * w32 * 4 < 0x7fffffffu && (size_t)N * w32 * 4 < 0x7fffffffu;
         if (x01) {
             if (!al) launch_binx_mfma32<2, false, false, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
-            else if (wm2 || !pinned) launch_binx_mfma32<2, true, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else if (!pinned) launch_binx_mfma32<2, true, false, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);   // operands of 2 GiB or more: pointer addressing
+            else if (wm2) launch_binx_mfma32<2, true, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
             else launch_binx_mfma32<4, true, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         } else if (!al) {
             // ragged rows: bounds-checked word loads, 64-row wave tiles only
@@ -555,7 +542,7 @@ int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
     if (M < 0 || M > kMaxDim) return BNN_ESHAPE;
     for (int l = 0; l < n_layers; ++l) {
         const bnn_layer_desc& d = L[l];
-        if (!word_bits_ok(d.word_bits) || d.K <= 0 || d.N <= 0 || d.K > kMaxDim || d.N > kMaxDim) return BNN_ESHAPE;
+        if (!word_bits_ok(d.word_bits) || d.K <= 0 || d.N <= 0 || d.K > kMaxDim || d.N > kMaxN) return BNN_ESHAPE;
         if (d.act < BNN_ACT_LINEAR || d.act > BNN_ACT_SIGMOID) return BNN_EINVAL;
         if (d.w_is_real < 0 || d.w_is_real > 1 || (d.w_is_real && d.scale)) return BNN_EINVAL;
         if (d.x_is_binary < 0 || d.x_is_binary > 2) return BNN_EINVAL;

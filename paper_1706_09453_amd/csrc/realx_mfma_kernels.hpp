@@ -25,8 +25,10 @@ typedef float v16f32 __attribute__((ext_vector_type(16)));
 // WREAL: the layer keeps real-valued weights (paper Sec. 3.1: input and Softmax layer): Wv is fp32 [N][K] (16-byte
 //        aligned too if VEC), fetched exactly like the frames; otherwise Wv is packed bits [N][w32].
 // Grid: x = ceil(M / 256), y = ceil(N / 128); block = 256 threads.  ACT: ACT_LINEAR, ACT_HARDTANH or ACT_SIGMOID.
+// One wave per SIMD, i.e. one workgroup per CU, stated to the compiler (it sizes the register claim of the kernel so
+// that a second wave does not fit): two workgroups on a CU evict each other's operand rows from the L1.
 template <int ACT, bool VEC, bool WREAL = false>
-__global__ __launch_bounds__(256, 1) void realx_f32_mfma_kernel(const float* __restrict__ X, const void* __restrict__ Wv,
+__global__ __launch_bounds__(256, 1) __attribute__((amdgpu_waves_per_eu(1, 1))) void realx_f32_mfma_kernel(const float* __restrict__ X, const void* __restrict__ Wv,
                                                                const float* __restrict__ scale, const float* __restrict__ bias,
                                                                int M, int K, int N, int w32, float* __restrict__ Y) {
     const uint32_t* Wp = static_cast<const uint32_t*>(Wv);

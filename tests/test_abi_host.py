@@ -68,6 +68,8 @@ def test_layer_argument_validation(bnn):
         assert _status(fn, P, Q, 0, 0, 4, 0, 64, S, 32, R, 0) == bnn.BNN_ESHAPE         # K = 0
         assert _status(fn, P, Q, 0, 0, 4, 64, 0, S, 32, R, 0) == bnn.BNN_ESHAPE         # N = 0
         assert _status(fn, P, Q, 0, 0, 4, 64, 64, S, 16, R, 0) == bnn.BNN_ESHAPE        # word_bits
+        assert _status(fn, P, Q, 0, 0, 4, 64, (1 << 22) + 1, S, 32, R, 0) == bnn.BNN_ESHAPE   # N beyond the grid's reach
+        assert _status(fn, P, Q, 0, 0, (1 << 30) + 1, 64, 64, S, 32, R, 0) == bnn.BNN_ESHAPE  # M beyond 2^30
         assert _status(fn, P, Q, 0, 0, 4, 64, 64, 9, 32, R, 0) == bnn.BNN_EINVAL        # unknown act
         assert _status(fn, P, Q + 4, 0, 0, 4, 64, 64, S, 64, R, 0) == bnn.BNN_EALIGN    # 64-bit words at 4 mod 8
         assert _status(fn, P, Q, 0, 0, 4, 64, 64, L, 32, R + 2, 0) == bnn.BNN_EALIGN    # fp32 out at 2 mod 4

@@ -549,7 +549,14 @@ def _net_parity(G, bnn, oracle, cfg, M, frames=None, form="xor", arm=None):
     want, keep = oracle.forward(layers, X[idx], form=form, keep=True)
     got_h = got[torch.from_numpy(idx).to(G.DEV)].cpu().numpy()
     _close(got_h, want, cfg.name)
-    assert np.array_equal(got_h.argmax(1), want.argmax(1)) or np.mean(got_h.argmax(1) == want.argmax(1)) > 0.999
+    # The most likely state is the oracle's: its arg-max attains the GPU row's maximum (subtracting the row's constant
+    # is monotone, so rounding can create a tie but not reverse an order), except where the oracle's two largest
+    # log-posteriors are closer than the two sides may differ (each within TOL * scale of the other).
+    best = want.argmax(1)
+    attains = got_h[np.arange(len(best)), best] == got_h.max(1)
+    top2 = np.partition(want, -2, axis=1)[:, -2:]
+    near_tie = (top2[:, 1] - top2[:, 0]) <= 2 * TOL * float(np.max(np.abs(want)))
+    assert np.all(attains | near_tie), f"{int((~(attains | near_tie)).sum())} frames with another most likely state"
     assert np.allclose(np.exp(got_h.astype(np.float64)).sum(1), 1.0, atol=1e-4)
     return model, layers, X, keep
 
@@ -583,29 +590,48 @@ def test_forward_configs_reduced_batch_full_compare(G, bnn, oracle, cfg_id, M):
     _net_parity(G, bnn, oracle, cfg, M)
 
 
-def test_forward_config3_full_batch_sampled_frames(G, bnn, oracle):
-    """Config 3 at its full size (M = 4096, the launch configuration the benchmark times)."""
+def _hidden_bits_layer_by_layer(G, bnn, model, layers, X, keep, rows=None):
+    """Every hidden layer's packed output at the full batch, through the per-layer entry points in the launch
+    configuration of the batch, against the oracle's bits (all rows, or the rows the oracle computed)."""
+    wb = model.word_bits
+    h = G.to_dev(X)
+    sel = None if rows is None else torch.from_numpy(np.asarray(rows)).to(G.DEV)
+    for l, (ly, d) in enumerate(zip(layers[:-1], model.descs[:-1])):
+        assert d["act"] == bnn.BNN_ACT_SIGN
+        Y = G.word_tensor(X.shape[0], ly.N, wb)
+        if l == 0:   # as bnn_forward runs its first layer: a one-layer network
+            one = bnn.make_layer_array(model.descs[:1])
+            bnn.bnn_forward(one, 1, G.ptr(h), X.shape[0], G.ptr(Y), 0, 0, G.stream())
+        else:
+            fn = bnn.bnn_layer_binw_binx01 if d["x_is_binary"] == 2 else bnn.bnn_layer_binw_binx
+            fn(G.ptr(h), d["Wp"], d["scale"], d["bias"], X.shape[0], ly.K, ly.N, bnn.BNN_ACT_SIGN, wb, G.ptr(Y), G.stream())
+        torch.cuda.synchronize()
+        got = G.words_to_host(Y if sel is None else Y[sel], wb)
+        assert np.array_equal(got, keep[l]), f"hidden layer {l + 1}: {int((got != keep[l]).sum())} words differ"
+        h = Y
+
+
+def test_forward_config3_full_batch_every_frame(G, bnn, oracle):
+    """Config 3 at its full size (M = 4096, the launch configuration the benchmark times): every log-posterior of every
+    frame against the oracle, and all six hidden bit tensors bit for bit."""
     cfg = workloads.CONFIGS[3]
-    rng = np.random.default_rng(0)
-    frames = np.unique(np.concatenate([np.arange(0, 16), np.arange(cfg.M - 16, cfg.M), rng.integers(0, cfg.M, 96)]))
-    model, layers, X, keep = _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
-    # and the hidden bits of the first binary layers, full batch, bit for bit (popcount form of the oracle)
-    Xd = G.to_dev(X)
-    ly = layers[0]
-    h1 = G.layer_realx(Xd, G.to_dev(ly.w_words), G.to_dev(ly.scale), G.to_dev(ly.bias), ly.K, ly.N, bnn.BNN_ACT_SIGN, 32)
-    want1 = oracle.layer_binw_realx(X, ly.w_words, ly.K, ly.scale, ly.bias, "sign", 32)
-    assert np.array_equal(G.words_to_host(h1, 32), want1)
-    ly = layers[1]
-    h2 = G.layer_binx(h1, G.to_dev(ly.w_words), G.to_dev(ly.scale), G.to_dev(ly.bias), ly.K, ly.N, bnn.BNN_ACT_SIGN, 32)
-    want2 = oracle.layer_binw_binx(want1, ly.w_words, ly.K, ly.scale, ly.bias, "sign", 32, form="xor")
-    assert np.array_equal(G.words_to_host(h2, 32), want2)
+    model, layers, X, keep = _net_parity(G, bnn, oracle, cfg, cfg.M)
+    _hidden_bits_layer_by_layer(G, bnn, model, layers, X, keep)
+
+
+def _tile_class_frames(M, count, seed, tile=128):
+    """`count` or more frames of a batch of M: the first and last tile whole, one frame of every `tile`-row tile with the
+    position inside the tile running through all residues, and random ones."""
+    tiles = M // tile
+    per_tile = np.arange(tiles) * tile + (np.arange(tiles) * 37) % tile
+    base = np.concatenate([np.arange(0, tile), np.arange(M - tile, M), per_tile])
+    extra = np.random.default_rng(seed).integers(0, M, max(0, count - base.size))
+    return np.unique(np.concatenate([base, extra]))
 
 
 def test_forward_config2_full_batch_sampled_frames(G, bnn, oracle):
     cfg = workloads.CONFIGS[2]
-    frames = np.unique(np.concatenate([np.arange(0, 8), np.arange(cfg.M - 8, cfg.M),
-                                       np.random.default_rng(1).integers(0, cfg.M, 16)]))
-    _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
+    _net_parity(G, bnn, oracle, cfg, cfg.M, frames=_tile_class_frames(cfg.M, 320, 1))
 
 
 def test_forward_config2_matrix_cores_layer_by_layer(G, bnn, oracle):
@@ -651,10 +677,12 @@ def test_forward_sigmoid_topologies_full_batch_sampled_frames(G, bnn, oracle, cf
 
 
 def test_forward_config4_full_batch_sampled_frames(G, bnn, oracle):
+    """Config 4 at its full size (16384 frames, 64-bit words): 1200 or more frames, among them the first and the last
+    128-row tile whole and a frame of every tile, for the log-posteriors and for every hidden layer's bits."""
     cfg = workloads.CONFIGS[4]
-    frames = np.unique(np.concatenate([np.arange(0, 8), np.arange(cfg.M - 8, cfg.M),
-                                       np.random.default_rng(2).integers(0, cfg.M, 32)]))
-    _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
+    frames = _tile_class_frames(cfg.M, 1200, 2)
+    model, layers, X, keep = _net_parity(G, bnn, oracle, cfg, cfg.M, frames=frames)
+    _hidden_bits_layer_by_layer(G, bnn, model, layers, X, keep, rows=frames)
 
 
 # ----------------------------------------------------------------------------- isolated GEMM sweep (Config 5)
@@ -670,9 +698,10 @@ def test_gemm_sweep_int32(G, bnn, oracle, shape, arm):
     torch.cuda.synchronize()
     if M <= 4096:
         rows = np.arange(M)
-    else:   # the oracle computes sampled rows one by one: first and last tiles plus random rows
-        rows = np.unique(np.concatenate([np.arange(0, 160), np.arange(M - 160, M),
-                                         np.random.default_rng(M + K + N).integers(0, M, 700)]))
+    else:   # the oracle computes sampled rows one by one: first and last tiles, a row of every 128-row tile, random rows
+        tiles = np.arange(M // 128)
+        rows = np.unique(np.concatenate([np.arange(0, 160), np.arange(M - 160, M), tiles * 128 + (tiles * 37) % 128,
+                                         np.random.default_rng(M + K + N).integers(0, M, 300)]))
     got = Y[torch.from_numpy(rows).to(G.DEV)].cpu().numpy()
     want = oracle.dot_xor(A[rows], B, K, 32)
     assert np.array_equal(got, want)

@@ -341,6 +341,44 @@ def test_affine_is_one_correctly_rounded_fma(oracle):
     assert np.array_equal(oracle.affine_f32(v, None, bias), (v.astype(np.float64) + bias).astype(np.float32))
 
 
+def test_affine_f64_against_exact_rationals(oracle):
+    # Eq. 1 carried in fp64: scale[n] * v[m][n] + bias[n] with the fp32 scale and bias widened exactly.  The exact
+    # rational value is within two fp64 roundings (product, then sum) of what the function returns; a swapped scale and
+    # bias, a transposed index (scale[m] for scale[n]) or a missing term is off by far more than that.
+    rng = _rng(31)
+    M, N = 5, 48
+    scale = rng.uniform(0.3, 0.7, N).astype(np.float32)
+    scale[::7] *= -1.0
+    bias = (rng.standard_normal(N) * 3.0).astype(np.float32)
+    v = rng.standard_normal((M, N)) * 200.0
+    got = oracle.affine_f64(v, scale, bias)
+    assert got.dtype == np.float64 and got.shape == (M, N)
+    for m in range(M):
+        for n in range(N):
+            prod = Fraction(float(scale[n])) * Fraction(float(v[m, n]))
+            exact = prod + Fraction(float(bias[n]))
+            bound = (abs(prod) + abs(exact)) * Fraction(1, 2 ** 52)
+            assert abs(Fraction(float(got[m, n])) - exact) <= bound, (m, n)
+            swapped = Fraction(float(bias[n])) * Fraction(float(v[m, n])) + Fraction(float(scale[n]))
+            assert abs(swapped - exact) > 1000 * bound, "the sample must tell scale from bias"
+    # integer products (24-bit scale x |dot| <= 2048) are exact in fp64: one rounding, of the sum, is left
+    dots = rng.integers(-2048, 2049, size=(M, N)).astype(np.float64)
+    got = oracle.affine_f64(dots, scale, bias)
+    for m in range(M):
+        for n in range(N):
+            exact = Fraction(float(scale[n])) * int(dots[m, n]) + Fraction(float(bias[n]))
+            assert abs(Fraction(float(got[m, n])) - exact) <= abs(exact) * Fraction(1, 2 ** 53)
+    # NULL scale = 1, NULL bias = 0
+    assert np.array_equal(oracle.affine_f64(v, None, None), v)
+    assert np.array_equal(oracle.affine_f64(v, None, bias), v + bias.astype(np.float64)[None, :])
+    assert np.array_equal(oracle.affine_f64(v, scale, None), scale.astype(np.float64)[None, :] * v)
+    # it is the fp64 companion of the fp32 affine step: the two agree to fp32 rounding on fp32 inputs
+    v32 = v.astype(np.float32)
+    h32 = oracle.affine_f32(v32, scale, bias)
+    h64 = oracle.affine_f64(v32.astype(np.float64), scale, bias)
+    assert np.array_equal(h32, h64.astype(np.float32)) or np.max(np.abs(h32 - h64)) <= 2e-5
+
+
 def test_sign_bit_is_monotone_in_dot(oracle):
     # for fixed scale > 0 the bit (h^ > 0) switches once from 0 to 1 as dot grows; for scale < 0 once from 1 to 0
     K = 2048
