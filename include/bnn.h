@@ -231,6 +231,21 @@ size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, i
 int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * bnn_forward for callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same forward pass with the ping-pong buffers in a fixed
+ * BNN_FORWARD_STATIC_MAX_BYTES array inside the library's device image.  Calls no hipMalloc / hipFree or any other
+ * allocating routine.  Arguments, results and errors as bnn_forward, except:
+ *   - BNN_EWORKSPACE if bnn_forward_workspace_bytes(layers, n_layers, M) exceeds BNN_FORWARD_STATIC_MAX_BYTES
+ *     (16 MiB: Config-3-sized networks up to 32768 frames, 4096-unit ones up to 16384);
+ *   - BNN_EDEVICE if the array's address cannot be obtained on the current device.
+ * Every call on a GPU shares that GPU's one array: calls that overlap in time on one GPU (different streams or threads)
+ * race on it; calls on one stream are ordered and safe.  Nothing in the array has to be cleared between calls: every
+ * layer writes all of its output, pad bits included, before the next layer reads it.
+ */
+#define BNN_FORWARD_STATIC_MAX_BYTES (16u << 20)
+int bnn_forward_static(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out, void* stream);
+
 /* ------------------------------------------------------------------------------------------------------------------
  * Training side: backward propagation and update of Alg. 1 (binary weights) and Alg. 2 (binary activations), the
  * gradient-norm clipping of Sec. 2.3 and the semi-stochastic binarisation of Sec. 2.1.  All buffers are DEVICE memory,

@@ -72,6 +72,7 @@ _SIGNATURES = {
     "bnn_semi_stochastic_binarize": (c_int, [c_void_p, c_void_p, c_int64, c_void_p]),
     "bnn_forward_workspace_bytes": (c_size_t, [c_void_p, c_int, c_int64]),
     "bnn_forward": (c_int, [c_void_p, c_int, c_void_p, c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "bnn_forward_static": (c_int, [c_void_p, c_int, c_void_p, c_int64, c_void_p, c_void_p]),
 }
 for _name, (_res, _args) in _SIGNATURES.items():
     _fn = getattr(_lib, _name)
@@ -214,6 +215,13 @@ def make_layer_array(descs: Sequence[dict]):
 
 def bnn_forward_workspace_bytes(layers, n_layers: int, M: int) -> int:
     return int(_lib.bnn_forward_workspace_bytes(ctypes.cast(layers, c_void_p), n_layers, M))
+
+
+BNN_FORWARD_STATIC_MAX_BYTES = 16 << 20
+
+
+def bnn_forward_static(layers, n_layers: int, X: int, M: int, out: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_forward_static(ctypes.cast(layers, c_void_p), n_layers, X, M, out, stream or None))
 
 
 def bnn_forward(layers, n_layers: int, X: int, M: int, out: int, workspace: int, workspace_bytes: int,

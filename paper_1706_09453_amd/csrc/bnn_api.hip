@@ -866,6 +866,49 @@ BNN_EXPORT size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int 
     return 2 * ws.half + ws.unpacked;
 }
 
+// Scratch of bnn_forward_static: a fixed array in the library's device image (every GPU the library runs on holds its
+// own copy at its own address until the process ends).  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the device address that call returns.
+constexpr size_t kStaticScratchBytes = (size_t)BNN_FORWARD_STATIC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up once per device.
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
+}
+}  // namespace
+
+BNN_EXPORT int bnn_forward_static(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
+                                  void* stream) {
+    const int rc = check_chain(layers, n_layers, M);
+    if (rc != BNN_OK) return rc;
+    if (M == 0) return BNN_OK;
+    const size_t need = bnn_forward_workspace_bytes(layers, n_layers, M);
+    if (need > kStaticScratchBytes) return BNN_EWORKSPACE;
+    void* ws = nullptr;
+    if (need) {
+        ws = static_scratch();
+        if (!ws) return BNN_EDEVICE;
+    }
+    return bnn_forward(layers, n_layers, X, M, out, ws, need, stream);
+}
+
 BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
                            void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_chain(layers, n_layers, M);
