@@ -7,7 +7,10 @@ the packed model already resident in HBM.  Prints ONE JSON line with frames/s, b
 of the dominant kernel (timed live with HIP events on the launch stream) and the CPU oracle timed on the
 host cores on a bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--arm mfma|valu]
+The line also carries "configs": a short run of the other benchmark configurations (C1, C2, C4 and two corners of the
+C5 product sweep) beside C3's own figures; --no-configs leaves them out.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-configs] [--arm mfma|mfma_i8|valu]
 """
 from __future__ import annotations
 
@@ -34,32 +37,62 @@ def gemm_sweep(args, bnn, workloads, G, torch) -> int:
         key, val = kv.split("=")
         bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
     for shape in workloads.GEMM_SWEEP:
-        M, K, N = shape.M, shape.K, shape.N
-        A = G.to_dev(workloads.random_words(0, 500 + workloads.TENSOR_ABITS, M, K // 32))
-        B = G.to_dev(workloads.random_words(0, 500 + workloads.TENSOR_BBITS, N, K // 32))
-        Y = torch.empty((M, N), dtype=torch.int32, device=G.DEV)
         for arm_name, arm in (("mfma", bnn.BNN_ARM_MFMA), ("mfma_i8", bnn.BNN_ARM_MFMA_I8), ("valu", bnn.BNN_ARM_VALU_XOR)):
-            def call():
-                bnn.bnn_layer_binw_binx_arm(A.data_ptr(), B.data_ptr(), 0, 0, M, K, N, bnn.BNN_ACT_RAW_I32, 32,
-                                            Y.data_ptr(), arm, G.stream())
-            for _ in range(2):
-                call()
-            torch.cuda.synchronize()
-            reps = 10 if M * K * N < 1e12 else 3
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(reps):
-                call()
-            b.record()
-            torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / reps
-            out_gb = 4.0 * M * N / 1e9
-            print(json.dumps({"workload": f"C5 binary GEMM M={M} K={K} N={N} int32 out", "arm": arm_name,
-                              "us": round(us, 1), "binary_tops": round(2.0 * M * K * N / us / 1e6, 1),
-                              "output_GBps": round(out_gb / (us * 1e-6), 1)}))
-        del A, B, Y
-        torch.cuda.empty_cache()
+            reps = 10 if shape.M * shape.K * shape.N < 1e12 else 3
+            line = time_gemm(shape, arm, reps, bnn, workloads, G, torch)
+            line["arm"] = arm_name
+            print(json.dumps(line), flush=True)
     return 0
+
+
+def time_config(cid, steps, workloads, G, torch) -> dict:
+    """bnn_forward on one configuration: 3 warm-up steps, then `steps` timed ones (host clock around a synchronize)."""
+    cfg = workloads.CONFIGS[cid]
+    Ws, bs = workloads.make_net_params(cfg)
+    model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits, real_weight_layers=cfg.real_weight_layers)
+    X = G.to_dev(workloads.make_frames(cfg))
+    out = torch.empty((cfg.M, model.N_out), dtype=torch.float32, device=G.DEV)
+    for _ in range(3):
+        model.forward(X, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        model.forward(X, out)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    line = {"workload": cfg.name, "batch_frames": cfg.M, "steps": steps, "ms_per_step": round(ms, 4),
+            "frames_per_s": round(cfg.M / (ms * 1e-3), 1),
+            "tops_all_layers": round(2.0 * cfg.macs_per_frame() * cfg.M / (ms * 1e-3) / 1e12, 2),
+            "binbin_share_of_macs": round(cfg.binbin_macs_per_frame() / cfg.macs_per_frame(), 3)}
+    del model, X, out, Ws, bs
+    torch.cuda.empty_cache()
+    return line
+
+
+def time_gemm(shape, arm, reps, bnn, workloads, G, torch) -> dict:
+    """The isolated binary x binary product (Config 5) at one shape, int32 outputs."""
+    M, K, N = shape.M, shape.K, shape.N
+    A = G.to_dev(workloads.random_words(0, 500 + workloads.TENSOR_ABITS, M, K // 32))
+    B = G.to_dev(workloads.random_words(0, 500 + workloads.TENSOR_BBITS, N, K // 32))
+    Y = torch.empty((M, N), dtype=torch.int32, device=G.DEV)
+
+    def call():
+        bnn.bnn_layer_binw_binx_arm(A.data_ptr(), B.data_ptr(), 0, 0, M, K, N, bnn.BNN_ACT_RAW_I32, 32, Y.data_ptr(), arm,
+                                    G.stream())
+    for _ in range(2):
+        call()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        call()
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) * 1e3 / reps
+    del A, B, Y
+    torch.cuda.empty_cache()
+    return {"workload": f"C5 binary GEMM M={M} K={K} N={N} int32 out", "us": round(us, 1),
+            "binary_tops": round(2.0 * M * K * N / us / 1e6, 1), "output_GBps": round(4.0 * M * N / 1e9 / (us * 1e-6), 1)}
 
 
 def all_configs(args, bnn, workloads, G, torch) -> int:
@@ -71,26 +104,38 @@ def all_configs(args, bnn, workloads, G, torch) -> int:
     for cid in (1, 2, 3, 4, 6, 7, 8, 9, 10):
         if only and cid not in only:
             continue
-        cfg = workloads.CONFIGS[cid]
-        Ws, bs = workloads.make_net_params(cfg)
-        model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits, real_weight_layers=cfg.real_weight_layers)
-        X = G.to_dev(workloads.make_frames(cfg))
-        out = torch.empty((cfg.M, model.N_out), dtype=torch.float32, device=G.DEV)
         steps = 200 if cid == 1 else (10 if cid in (4, 9, 10) else 50)
-        for _ in range(3):
-            model.forward(X, out)
+        print(json.dumps(time_config(cid, steps, workloads, G, torch)), flush=True)
+    return 0
+
+
+def hidden_k_sweep(args, bnn, workloads, G, torch) -> int:
+    """The Sign-layer kernel of the hidden layers (4096 frames, 2048 units) with the input width K swept: what a launch
+    costs beyond its products shows as the time that does not shrink with K.  One JSON line per K."""
+    M, N = 4096, 2048
+    for K in (512, 1024, 2048, 4096, 8192):
+        A = G.to_dev(workloads.random_words(0, 1, M, K // 32))
+        B = G.to_dev(workloads.random_words(0, 2, N, K // 32))
+        sc = torch.full((N,), 0.5, device=G.DEV)
+        bi = torch.zeros(N, device=G.DEV)
+        Y = G.word_tensor(M, N, 32)
+
+        def call():
+            bnn.bnn_layer_binw_binx(A.data_ptr(), B.data_ptr(), sc.data_ptr(), bi.data_ptr(), M, K, N, bnn.BNN_ACT_SIGN, 32,
+                                    Y.data_ptr(), G.stream())
+        for _ in range(5):
+            call()
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            model.forward(X, out)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(200):
+            call()
+        b.record()
         torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / steps
-        print(json.dumps({"workload": cfg.name, "batch_frames": cfg.M, "ms_per_step": round(ms, 4),
-                          "frames_per_s": round(cfg.M / (ms * 1e-3), 1),
-                          "tops_all_layers": round(2.0 * cfg.macs_per_frame() * cfg.M / (ms * 1e-3) / 1e12, 2),
-                          "binbin_share_of_macs": round(cfg.binbin_macs_per_frame() / cfg.macs_per_frame(), 3)}), flush=True)
-        del model, X, out, Ws, bs
-        torch.cuda.empty_cache()
+        us = a.elapsed_time(b) * 1e3 / 200
+        print(json.dumps({"workload": f"Sign layer M={M} K={K} N={N}, launched back to back", "us_per_launch": round(us, 2),
+                          "tflops": round(2.0 * M * K * N / us / 1e6, 1),
+                          "frac_of_fp4_mfma_peak": round(2.0 * M * K * N / us / 1e6 / PEAK_MFMA_FP4_TFLOPS, 3)}), flush=True)
     return 0
 
 
@@ -231,6 +276,8 @@ def main() -> int:
     ap.add_argument("--arm", choices=["mfma", "mfma_i8", "valu"], default="mfma",
                     help="arm of the binary product: 4-bit-float MFMA (default), int8 MFMA, or XOR/popcount on the vector ALU")
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
+    ap.add_argument("--no-configs", action="store_true",
+                    help="leave the short runs of the other configurations (the line's \"configs\" array) out")
     ap.add_argument("--copy-calibration", action="store_true", help="run 10 plain 256 MiB device copies (counter calibration)")
     ap.add_argument("--only", default="", help="with --all-configs: comma-separated configuration numbers to run")
     ap.add_argument("--train-step", action="store_true",
@@ -239,6 +286,8 @@ def main() -> int:
                     help="latency of bnn_forward on 1, 4, 16 and 64 frames (Configs 3 and 10, or --only)")
     ap.add_argument("--all-configs", action="store_true",
                     help="time bnn_forward on Configs 1-4 instead (one JSON line each; the default run is Config 3 only)")
+    ap.add_argument("--hidden-k-sweep", action="store_true",
+                    help="time the hidden layers' Sign kernel at input widths 512 .. 8192 (fixed cost of a launch)")
     ap.add_argument("--gemm-sweep", action="store_true", help="time the isolated binary GEMM sweep (Config 5) instead")
     ap.add_argument("--opt", action="append", default=[], help="kernel option as KEY=VALUE with KEY a BNN_OPT_* name, e.g. MFMA_LDS=0")
     args = ap.parse_args()
@@ -257,6 +306,8 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.gemm_sweep:
         return gemm_sweep(args, bnn, workloads, G, torch)
+    if args.hidden_k_sweep:
+        return hidden_k_sweep(args, bnn, workloads, G, torch)
     if args.all_configs:
         return all_configs(args, bnn, workloads, G, torch)
     if args.streaming:
@@ -365,11 +416,18 @@ def main() -> int:
     traffic = None
     if args.arm == "mfma" and not args.opt:
         traffic = next(int(v) for k, v in measured_traffic.items() if dominant.startswith(k))
-    roofline = {"bound": bound, "achieved": round(achieved_tflops, 3), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved_tflops / peak, 4), "traffic": traffic, "kernel": dominant,
-                "avg_launch_us": round(avg_us, 2), "launches_per_step": launches}
-
     bin_us = sum(layer_us[1:])
+    binbin_tops = 2.0 * macs_bin / (bin_us * 1e-6) / 1e12
+    roofline = {"bound": bound, "achieved": round(achieved_tflops, 3), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved_tflops / peak, 4), "traffic": traffic,
+                "traffic_source": None if traffic is None else
+                "stored, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per dispatch, scaled by a "
+                "plain copy of known size (profiles/forward_c3_hbm_traffic.txt)",
+                "kernel": dominant, "avg_launch_us": round(avg_us, 2), "launches_per_step": launches,
+                # every binary x binary layer of the step (5 hidden + the output layer with its log-softmax), products
+                # over the sum of their launch times, against the same matrix-core peak
+                "frac_all_binbin": round(binbin_tops / peak, 4) if bound == "mfma" and not dominant.startswith("realx") else None}
+
     result = {
         "metric": "frames/sec, 6x2048 binarized DNN (binary weights and activations), batch 4096, 1xMI355X",
         "value": round(frames_per_s, 1), "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -382,7 +440,7 @@ def main() -> int:
                    "binx_arm": args.arm},
         "device_ms_per_step": round(dev_ms / args.steps, 5),
         "binary_tops_all_layers": round(2.0 * macs_all / (ms_per_step * 1e-3) / 1e12, 2),
-        "binary_tops_binbin_kernels": round(2.0 * macs_bin / (bin_us * 1e-6) / 1e12, 2),
+        "binary_tops_binbin_kernels": round(binbin_tops, 2),
         "layer_us": [round(v, 2) for v in layer_us],
         "roofline": roofline,
     }
@@ -396,14 +454,39 @@ def main() -> int:
         t0 = time.perf_counter()
         ref = orc.forward(layers, X_host[:S], form="xor")
         dt = time.perf_counter() - t0
-        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")                                # the OpenMP runtime the oracle's library uses
+        cores = int(gomp.omp_get_max_threads())
+        # the same oracle on ONE thread, on a sample sized for a few seconds
+        S1 = max(32, min(S, S // max(cores, 1)))
+        gomp.omp_set_num_threads(1)
+        t1 = time.perf_counter()
+        orc.forward(layers, X_host[:S1], form="xor")
+        dt1 = time.perf_counter() - t1
+        gomp.omp_set_num_threads(cores)
         got = out[:S].cpu().numpy()
         err = float(np.max(np.abs(got.astype(np.float64) - ref)))
         result["cpu_baseline"] = {"value": round(S / dt, 1), "unit": "frames/s", "cores": cores, "kind": "oracle",
                                   "sample": f"first {S} of the {M} frames, all 7 layers, XOR/popcount form, "
                                             f"{dt:.2f} s wall",
+                                  "single_thread": {"value": round(S1 / dt1, 1), "unit": "frames/s", "cores": 1,
+                                                    "sample": f"first {S1} frames, {dt1:.2f} s wall"},
                                   "gpu_vs_oracle_max_abs_err": err,
                                   "oracle_output_scale": float(np.max(np.abs(ref)))}
+    # ---- the other configurations, a short run each (their parity is the tests' business; these are timings only)
+    if not args.no_configs and args.arm == "mfma" and not args.opt:
+        del model, X, out, ws_bits, first_ws
+        torch.cuda.empty_cache()
+        lines = [time_config(1, 100, workloads, G, torch), time_config(2, 20, workloads, G, torch),
+                 {"workload": cfg.name, "batch_frames": M, "steps": args.steps, "ms_per_step": round(ms_per_step, 4),
+                  "frames_per_s": round(frames_per_s, 1),
+                  "tops_all_layers": round(2.0 * macs_all / (ms_per_step * 1e-3) / 1e12, 2),
+                  "binbin_share_of_macs": round(macs_bin / macs_all, 3)},
+                 time_config(4, 10, workloads, G, torch)]
+        corners = [workloads.GEMM_SWEEP[0], workloads.GEMM_SWEEP[-1]]
+        lines += [time_gemm(sh, bnn.BNN_ARM_MFMA, 10 if sh.M * sh.K * sh.N < 1e12 else 3, bnn, workloads, G, torch)
+                  for sh in corners]
+        result["configs"] = lines
     print(json.dumps(result))
     cb = result.get("cpu_baseline")
     if cb and not cb["gpu_vs_oracle_max_abs_err"] <= 1e-4 * cb["oracle_output_scale"]:
