@@ -125,7 +125,12 @@ size_t bnn_packed_words(int64_t K, int word_bits);
 /* Static, never-freed description of a status code.  HOST helper. */
 const char* bnn_status_string(int status);
 
-/* Set a kernel-selection knob (bnn_option) process-wide; BNN_EINVAL for an unknown option or value.  HOST helper. */
+/* Set a kernel-selection knob (bnn_option); BNN_EINVAL for an unknown option or value.  HOST helper.
+ * The knobs are process-wide state (one atomic integer each, shared by every thread, stream and device): a call takes
+ * effect for every layer call that STARTS after it, in any thread.  Setting one while another thread is inside a layer
+ * or forward call is safe (no torn state: each entry point reads each knob once per kernel choice) but which of the
+ * two values that call sees is unspecified; a multi-layer bnn_forward may then pick its kernels from both.  Results do
+ * not depend on the knobs beyond what bnn_option documents; callers that tune set them once, before serving. */
 int bnn_set_option(int option, int value);
 
 /*

@@ -776,6 +776,43 @@ def _random_shapes(seed, count):
     return out
 
 
+@pytest.fixture()
+def bnn_defaults(bnn):
+    """The library as a caller finds it: every option at its default, the small-batch dispatch (64 frames) included."""
+    bnn.bnn_set_option(bnn.BNN_OPT_STREAM_MAX_FRAMES, 64)
+    yield bnn
+    bnn.bnn_set_option(bnn.BNN_OPT_STREAM_MAX_FRAMES, 0)
+
+
+@pytest.mark.parametrize("act", ["sign", "linear", "logsoftmax", "sigmoid"])
+@pytest.mark.parametrize("M,K,N", [(1, 440, 2048), (40, 2048, 300), (64, 440, 512), (65, 33, 65), (130, 440, 200),
+                                   (300, 2048, 2048), (257, 512, 3307)])
+def test_layers_with_every_option_at_its_default(G, bnn_defaults, oracle, M, K, N, act):
+    """One pass over the four layer kinds through whatever kernels the default dispatch picks, on both sides of the
+    small-batch boundary.  Sign bits and the binary layers' fp32 outputs are exact; fp32 outputs of the real-input
+    layers may come from the matrix-core kernel (its own order of additions) and are held to the tolerance."""
+    bnn = bnn_defaults
+    X, W, scale, bias = _rand_layer(M * 17 + K * 3 + N, M, K, N)
+    Wr = (W * np.float32(np.sqrt(3.0 / K))).astype(np.float32)
+    Wp, aw = oracle.pack_sign(W, 32), oracle.pack_sign(X, 32)
+    dX, dWp, dWr, dsc, dbi, daw = (G.to_dev(a) for a in (X, Wp, Wr, scale, bias, aw))
+    a = bnn.ACT_BY_NAME[act]
+    got = [G.layer_realx(dX, dWp, dsc, dbi, K, N, a, 32), G.layer_realw(dX, dWr, dbi, K, N, a, 32),
+           G.layer_binx(daw, dWp, dsc, dbi, K, N, a, 32), G.layer_binx01(daw, dWp, dsc, dbi, K, N, a, 32)]
+    torch.cuda.synchronize()
+    want = [oracle.layer_binw_realx(X, Wp, K, scale, bias, act, 32), oracle.layer_realw(X, Wr, bias, act, 32),
+            oracle.layer_binw_binx(aw, Wp, K, scale, bias, act, 32, form="xor"),
+            oracle.layer_binw_binx01(aw, Wp, K, scale, bias, act, 32, form="and")]
+    for i, (g_, w_) in enumerate(zip(got, want)):
+        kind = ("realx", "realw", "binx", "binx01")[i]
+        if act == "sign":
+            assert np.array_equal(G.words_to_host(g_, 32), w_), kind
+        elif act == "linear" and i >= 2:
+            assert np.array_equal(g_.cpu().numpy(), w_), kind      # one fma on an exact integer
+        else:
+            _close(g_.cpu().numpy(), w_, f"{kind} {act}")
+
+
 @pytest.mark.parametrize("stream_frames", [0, 64])
 @pytest.mark.parametrize("M,K,N", _random_shapes(2024, 40))
 def test_random_shapes_all_layer_kinds(G, bnn, oracle, M, K, N, stream_frames):
