@@ -276,6 +276,8 @@ def main() -> int:
     ap.add_argument("--arm", choices=["mfma", "mfma_i8", "valu"], default="mfma",
                     help="arm of the binary product: 4-bit-float MFMA (default), int8 MFMA, or XOR/popcount on the vector ALU")
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
+    ap.add_argument("--no-cooperative", action="store_true",
+                    help="leave BNN_OPT_COOPERATIVE off: the output layer then runs as product kernel + row kernel")
     ap.add_argument("--no-configs", action="store_true",
                     help="leave the short runs of the other configurations (the line's \"configs\" array) out")
     ap.add_argument("--copy-calibration", action="store_true", help="run 10 plain 256 MiB device copies (counter calibration)")
@@ -333,6 +335,10 @@ def main() -> int:
     out = torch.empty((M, model.N_out), dtype=torch.float32, device=G.DEV)
     arm = {"mfma": bnn.BNN_ARM_MFMA, "mfma_i8": bnn.BNN_ARM_MFMA_I8, "valu": bnn.BNN_ARM_VALU_XOR}[args.arm]
     bnn.bnn_set_option(bnn.BNN_OPT_BINX_ARM, arm)
+    # This process runs one stream and nothing else on the GPU, which is what BNN_OPT_COOPERATIVE asks of its caller: the
+    # output layer then finishes its log-Softmax inside the product kernel.
+    cooperative = not args.no_cooperative
+    bnn.bnn_set_option(bnn.BNN_OPT_COOPERATIVE, 1 if cooperative else 0)
     for kv in args.opt:
         key, val = kv.split("=")
         bnn.bnn_set_option(getattr(bnn, "BNN_OPT_" + key), int(val))
@@ -412,7 +418,7 @@ def main() -> int:
     # HBM bytes per launch of each kernel group from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
     # (profiles/forward_c3_hbm_traffic.txt); measured for this workload with the matrix-core arm only
     measured_traffic = {"realx": (8.19 + 1.00) * 2 ** 20, "binx hidden": (5.35 + 1.00) * 2 ** 20,
-                        "binx output": (8.09 + 26.81 + 27.27 + 53.13) * 2 ** 20}
+                        "binx output": (8.09 + 26.81 + 27.27 + 53.13) * 2 ** 20}   # (output layer: the two-kernel path)
     traffic = None
     if args.arm == "mfma" and not args.opt:
         traffic = next(int(v) for k, v in measured_traffic.items() if dominant.startswith(k))
@@ -437,7 +443,7 @@ def main() -> int:
                   "valu": "b1 (xor+popcount u32) + f32"}[args.arm],
         "data": "synthetic",
         "config": {"workload": cfg.name, "dims": list(cfg.dims), "batch_frames": M, "word_bits": cfg.word_bits,
-                   "binx_arm": args.arm},
+                   "binx_arm": args.arm, "options": {"BNN_OPT_COOPERATIVE": int(cooperative)}},
         "device_ms_per_step": round(dev_ms / args.steps, 5),
         "binary_tops_all_layers": round(2.0 * macs_all / (ms_per_step * 1e-3) / 1e12, 2),
         "binary_tops_binbin_kernels": round(binbin_tops, 2),
@@ -487,7 +493,12 @@ def main() -> int:
         lines += [time_gemm(sh, bnn.BNN_ARM_MFMA, 10 if sh.M * sh.K * sh.N < 1e12 else 3, bnn, workloads, G, torch)
                   for sh in corners]
         result["configs"] = lines
+    if cooperative:
+        result["cooperative_timeouts"] = bnn.bnn_cooperative_timeouts()
     print(json.dumps(result))
+    if result.get("cooperative_timeouts"):
+        print("bench.py: a cooperative kernel's bounded wait ran out", file=sys.stderr)
+        return 1
     cb = result.get("cpu_baseline")
     if cb and not cb["gpu_vs_oracle_max_abs_err"] <= 1e-4 * cb["oracle_output_scale"]:
         print("bench.py: the timed output disagrees with the oracle beyond 1e-4 of the output scale", file=sys.stderr)

@@ -98,10 +98,20 @@ typedef enum bnn_option {
                                    0 or 1 = two register sets, the fetch of the next piece of K pinned ahead of
                                    the products of the current one (default), 2 = one set, order left to the
                                    compiler (kept for comparison)                                                */
-    BNN_OPT_STREAM_MAX_FRAMES = 12  /* batches of at most this many frames (streaming; the paper's motivation is on-device,
+    BNN_OPT_STREAM_MAX_FRAMES = 12, /* batches of at most this many frames (streaming; the paper's motivation is on-device,
                                        frame-by-frame inference) run every layer on the vector-ALU kernels with 1 or 2 frames
                                        per workgroup, so that a layer is spread over the whole chip and takes one pass
                                        over its weight rows; 0 = never.  Default 64.  Same results either way.          */
+    BNN_OPT_COOPERATIVE = 13        /* 1 = kernels whose workgroups wait for each other may be used: a binary-input
+                                       LOGSOFTMAX layer on the matrix-core arm then finishes its rows inside the product
+                                       kernel (the tiles of a row exchange their maxima and sums of exponentials through
+                                       memory) instead of running a second kernel over the rows.  Such a kernel needs all its
+                                       workgroups resident at once: the library sizes it for an otherwise idle device, so
+                                       the caller promises that nothing else runs on that device beside it (one stream, or
+                                       streams the caller serialises).  The waits are bounded: a launch that could not
+                                       get its workgroups resident ends anyway, with wrong rows, and is counted
+                                       (bnn_cooperative_timeouts).  0 = never (default).  Results within the same
+                                       tolerance as the two-kernel path (sums of exponentials taken in another order).   */
 } bnn_option;
 
 /* One layer of a network for bnn_forward.  HOST struct; the three pointers are DEVICE pointers. */
@@ -132,6 +142,12 @@ const char* bnn_status_string(int status);
  * two values that call sees is unspecified; a multi-layer bnn_forward may then pick its kernels from both.  Results do
  * not depend on the knobs beyond what bnn_option documents; callers that tune set them once, before serving. */
 int bnn_set_option(int option, int value);
+
+/* *count = number of workgroups, since the library was loaded, whose bounded wait inside a cooperative kernel
+ * (BNN_OPT_COOPERATIVE) ran out on the current device; 0 means every such launch was complete.  Waits for the device to
+ * be idle first (hipDeviceSynchronize).  BNN_EINVAL for a NULL pointer, BNN_EDEVICE if the device cannot be read.
+ * HOST helper; count is a host pointer. */
+int bnn_cooperative_timeouts(uint64_t* count);
 
 /*
  * Binarise real-valued weights (Eq. 3; Alg. 1 forward, first step): Wp[n][k-bit] = (W[n][k] > 0).

@@ -24,6 +24,7 @@ BNN_OPT_MFMA32_PIPELINE = 9
 BNN_OPT_REALX_F32_MFMA = 10
 BNN_OPT_MFMA32_XCD_ORDER = 11
 BNN_OPT_STREAM_MAX_FRAMES = 12
+BNN_OPT_COOPERATIVE = 13
 
 ACT_BY_NAME = {"raw": BNN_ACT_RAW_I32, "linear": BNN_ACT_LINEAR, "hardtanh": BNN_ACT_HARDTANH,
                "sign": BNN_ACT_SIGN, "step01": BNN_ACT_SIGN, "logsoftmax": BNN_ACT_LOGSOFTMAX,
@@ -45,6 +46,7 @@ _SIGNATURES = {
     "bnn_packed_words": (c_size_t, [c_int64, c_int]),
     "bnn_status_string": (c_char_p, [c_int]),
     "bnn_set_option": (c_int, [c_int, c_int]),
+    "bnn_cooperative_timeouts": (c_int, [ctypes.POINTER(ctypes.c_uint64)]),
     "bnn_pack_weights": (c_int, [c_void_p, c_int64, c_int64, c_int, c_void_p, c_void_p, c_void_p]),
     "bnn_pack_activations": (c_int, [c_void_p, c_int64, c_int64, c_int, c_void_p, c_void_p]),
     "bnn_layer_binw_realx": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_int,
@@ -104,6 +106,12 @@ def bnn_status_string(status: int) -> str:
 
 def bnn_set_option(option: int, value: int) -> int:
     return _check(_lib.bnn_set_option(option, value))
+
+
+def bnn_cooperative_timeouts() -> int:
+    count = ctypes.c_uint64(0)
+    _check(_lib.bnn_cooperative_timeouts(ctypes.byref(count)))
+    return int(count.value)
 
 
 def bnn_pack_weights(W: int, N: int, K: int, word_bits: int, Wp: int, scale_out: int = 0, stream: int = 0) -> int:

@@ -20,6 +20,16 @@
 
 #define BNN_EXPORT extern "C" __attribute__((visibility("default")))
 
+// Hand-over area of the cooperative log-Softmax epilogue (BNN_OPT_COOPERATIVE): a fixed array in the library's device
+// image, kCoopSlots launches' worth, handed out round-robin, so that the tail of one launch and the head of the next
+// on another stream do not share a slot.  In host code the array's name is only a handle for hipGetSymbolAddress.
+constexpr int kCoopSlots = 4;
+constexpr int kCoopMaxTiles = 1024;                                         // workgroups of one cooperative launch, at most
+constexpr size_t kCoopFlagBytes = (size_t)kCoopMaxTiles * 8;
+constexpr size_t kCoopPairBytes = (size_t)kCoopMaxTiles * 256 * 8;         // 256 rows per tile, 8 bytes per (max, sum) pair
+constexpr size_t kCoopSlotBytes = kCoopFlagBytes + kCoopPairBytes;
+static __device__ __align__(256) unsigned char coop_area[256 + kCoopSlots * kCoopSlotBytes];   // [0, 4): timeouts
+
 namespace {
 
 using namespace bnn;
@@ -37,6 +47,29 @@ std::atomic<int> g_mfma32_pipeline{0};
 std::atomic<int> g_realx_f32_mfma{0};
 std::atomic<int> g_mfma32_xcd_order{0};
 std::atomic<int> g_stream_max_frames{64};
+std::atomic<int> g_cooperative{0};
+std::atomic<unsigned long long> g_coop_launches{0};
+constexpr int kCoopMaxDevices = 64;
+std::atomic<void*> g_coop_ptr[kCoopMaxDevices];
+std::atomic<int> g_coop_capacity[kCoopMaxDevices][2];   // resident workgroups of the cooperative kernel, [0/1 input]
+
+// Device address of coop_area on the current device (looked up once per device); *dev_out = that device.
+unsigned char* coop_base(int* dev_out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kCoopMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    *dev_out = dev;
+    void* p = g_coop_ptr[dev].load(std::memory_order_acquire);
+    if (p) return static_cast<unsigned char*>(p);
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(coop_area)) != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_coop_ptr[dev].store(p, std::memory_order_release);
+    return static_cast<unsigned char*>(p);
+}
 
 inline bool word_bits_ok(int wb) { return wb == 32 || wb == 64; }
 inline int64_t words_per_row(int64_t K, int wb) { return (K + wb - 1) / wb; }
@@ -313,7 +346,7 @@ void launch_binx_mfma_wm(const uint32_t* Xp, const uint32_t* Wp, const float* sc
 
 template <int WM, bool AL, bool PP = false, bool X01 = false>
 void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* scale, const float* bias, int M, int K, int N,
-                        int w32, int act, void* Y, int yw32, hipStream_t st) {
+                        int w32, int act, void* Y, int yw32, hipStream_t st, const CoopLsm& coop = CoopLsm{}) {
     constexpr int WN = 2;
     // XCD-aware tile order pays when the default order thrashes the per-XCD L2s (a frames operand of more than
     // 8 x 4 MiB) or scatters a large packed output with long rows over many passes; it costs 5-15 % on mid-size
@@ -324,23 +357,27 @@ void launch_binx_mfma32(const uint32_t* Xp, const uint32_t* Wp, const float* sca
     const unsigned int ab = (unsigned int)((size_t)M * w32 * 4), bb = (unsigned int)((size_t)N * w32 * 4);   // used by the PP variants only
     const dim3 grid((M + 64 * WM - 1) / (64 * WM), (N + 64 * WN - 1) / (64 * WN)), block(256);
     switch (act) {
+        case ACT_LSM_COOP:
+            if constexpr (WM == 4 && AL && PP)
+                binx_mfma32_kernel<WM, WN, ACT_LSM_COOP, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo, coop);
+            break;
         case ACT_DOT_I16:
-            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_DOT_I16, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo, coop);
             break;
         case BNN_ACT_RAW_I32:
-            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_RAW_I32, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo, coop);
             break;
         case BNN_ACT_SIGN:
-            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_SIGN, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo, coop);
             break;
         case BNN_ACT_HARDTANH:
-            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_HARDTANH, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo, coop);
             break;
         case BNN_ACT_SIGMOID:
-            binx_mfma32_kernel<WM, WN, ACT_SIGMOID, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_SIGMOID, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo, coop);
             break;
         default:
-            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo);
+            binx_mfma32_kernel<WM, WN, ACT_LINEAR, AL, PP, X01><<<grid, block, 0, st>>>(Xp, Wp, scale, bias, M, K, N, w32, Y, yw32, ab, bb, xo, coop);
             break;
     }
 }
@@ -439,6 +476,7 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
         const bool i16 = act == BNN_ACT_LOGSOFTMAX && K < 32768 && N % 4 == 0 && N <= 8192 && aligned(Y, 16) &&
                          (!scale || aligned(scale, 16)) && (!bias || aligned(bias, 16));
         if (i16) act = ACT_DOT_I16;
+        const int64_t tiles_n4 = (N + 127) / 128, tiles4 = ((M + 255) / 256) * tiles_n4;
         // 128-row wave tiles expand fewer operand words per MAC; 64-row ones give twice the workgroups, which
         // matters more while the 128-row grid leaves CUs without a workgroup (measured on MI355X: 64-row tiles win
         // up to 2048 frames x 2048 outputs, 128-row tiles from 4096 x 2048 on)
@@ -447,11 +485,39 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
         const bool wm2 = wm32 == 2 || (wm32 == 0 && blocks4 < 200);
         // fetch pinned ahead of the products: faster on every shape measured; buffer addressing needs operands below 2 GiB
         const bool pinned = g_mfma32_pipeline.load() != 2 && (size_t)M * w32 * 4 < 0x7fffffffu && (size_t)N * w32 * 4 < 0x7fffffffu;
+        // Cooperative log-Softmax (opt-in): the product kernel finishes the rows itself.  Its workgroups wait for each
+        // other, so all of them have to be resident at once.
+        CoopLsm coop{};
+        if ((act == BNN_ACT_LOGSOFTMAX || act == ACT_DOT_I16) && g_cooperative.load() && al && pinned && !wm2 && tiles_n4 <= 64 &&
+            tiles4 <= kCoopMaxTiles) {
+            int dev = -1;
+            unsigned char* base = coop_base(&dev);
+            int cap = base ? g_coop_capacity[dev][x01 ? 1 : 0].load() : 0;
+            if (base && cap == 0) {
+                int per_cu = 0, cus = 0;
+                const hipError_t e1 = x01 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, binx_mfma32_kernel<4, 2, ACT_LSM_COOP, true, true, true>, 256, 0)
+                                          : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, binx_mfma32_kernel<4, 2, ACT_LSM_COOP, true, true, false>, 256, 0);
+                const hipError_t e2 = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+                if (e1 != hipSuccess || e2 != hipSuccess) (void)hipGetLastError();
+                cap = (e1 == hipSuccess && e2 == hipSuccess && per_cu > 0 && cus > 0) ? per_cu * cus : -1;
+                g_coop_capacity[dev][x01 ? 1 : 0].store(cap);
+            }
+            if (base && tiles4 <= cap) {
+                const unsigned long long launch = ++g_coop_launches;
+                unsigned char* slot = base + 256 + (size_t)(launch % kCoopSlots) * kCoopSlotBytes;
+                coop.flags = reinterpret_cast<unsigned long long*>(slot);
+                coop.partials = reinterpret_cast<float2*>(slot + kCoopFlagBytes);
+                coop.stamp = launch;
+                coop.timeouts = reinterpret_cast<unsigned int*>(base);
+                coop.spin_limit = 1 << 20;
+                act = ACT_LSM_COOP;
+            }
+        }
         if (x01) {
             if (!al) launch_binx_mfma32<2, false, false, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
             else if (!pinned) launch_binx_mfma32<2, true, false, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);   // operands of 2 GiB or more: pointer addressing
             else if (wm2) launch_binx_mfma32<2, true, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
-            else launch_binx_mfma32<4, true, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            else launch_binx_mfma32<4, true, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st, coop);
         } else if (!al) {
             // ragged rows: bounds-checked word loads, 64-row wave tiles only
             launch_binx_mfma32<2, false>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
@@ -459,7 +525,7 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
             if (pinned) launch_binx_mfma32<2, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
             else launch_binx_mfma32<2, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         } else {
-            if (pinned) launch_binx_mfma32<4, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+            if (pinned) launch_binx_mfma32<4, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st, coop);
             else launch_binx_mfma32<4, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
         }
     } else {
@@ -629,8 +695,26 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
             if (value != 0 && value != 1) return BNN_EINVAL;
             g_realx_sign_mfma.store(value);
             return BNN_OK;
+        case BNN_OPT_COOPERATIVE:
+            if (value != 0 && value != 1) return BNN_EINVAL;
+            g_cooperative.store(value);
+            return BNN_OK;
         default: return BNN_EINVAL;
     }
+}
+
+BNN_EXPORT int bnn_cooperative_timeouts(uint64_t* count) {
+    if (!count) return BNN_EINVAL;
+    int dev = -1;
+    unsigned char* base = coop_base(&dev);
+    if (!base) return BNN_EDEVICE;
+    unsigned int v = 0;
+    if (hipDeviceSynchronize() != hipSuccess || hipMemcpy(&v, base, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return BNN_EDEVICE;
+    }
+    *count = v;
+    return BNN_OK;
 }
 
 BNN_EXPORT int bnn_pack_weights(const float* W, int64_t N, int64_t K, int word_bits, void* Wp, float* scale_out,

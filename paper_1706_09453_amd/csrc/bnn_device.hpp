@@ -14,6 +14,21 @@ enum : int { ACT_RAW_I32 = 0, ACT_LINEAR = 1, ACT_HARDTANH = 2, ACT_SIGN = 3, AC
 // Kernel-internal: the integer product as int16 in the first 2 N bytes of each fp32 output row (|dot| <= K < 2^15);
 // the log-Softmax row kernel turns the row into fp32 log-posteriors in place.
 enum : int { ACT_DOT_I16 = 100 };
+// Kernel-internal: log-Softmax finished inside the product kernel.  The workgroups that share rows of frames hand each
+// other their share of every row's maximum and sum of exponentials through memory (see CoopLsm); needs every workgroup
+// of the launch resident at once.
+enum : int { ACT_LSM_COOP = 101 };
+
+// Hand-over area of ACT_LSM_COOP.  Tile (tm, tn) of the launch writes partials[(tm * n_tiles + tn) * rows_per_tile + row]
+// = (max, sum of exp(h - max)) of `row` over its columns, then flags[tm * n_tiles + tn] = stamp.  Stamps are unique per
+// launch, so what an earlier launch left in the area never reads as this launch's.
+struct CoopLsm {
+    float2* partials;
+    unsigned long long* flags;
+    unsigned long long stamp;
+    unsigned int* timeouts;   // incremented by a workgroup whose bounded wait ran out (its rows are then wrong)
+    int spin_limit;           // polls of the flags before a workgroup gives up
+};
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
 

@@ -92,7 +92,8 @@ template <int WM, int WN, int ACT, bool ALIGNED, bool PINGPONG = false, bool X01
 __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
                                                           const float* __restrict__ scale, const float* __restrict__ bias,
                                                           int M, int K, int N, int w32, void* __restrict__ Y, int yw32,
-                                                          unsigned int a_bytes, unsigned int b_bytes, int xcd_order) {
+                                                          unsigned int a_bytes, unsigned int b_bytes, int xcd_order,
+                                                          const CoopLsm coop) {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     const int r = lane & 31;   // row of the operand fragment / column of the accumulator fragment
@@ -111,7 +112,11 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
     }
     const int m_base = (tile_m * 2 + (wave >> 1)) * (WM * 32);
     const int n_base = (tile_n * 2 + (wave & 1)) * (WN * 32);
-    if (m_base >= M || n_base >= N) return;   // wave-uniform
+    // (the cooperative epilogue has workgroup barriers: there a wave without rows or columns of its own runs along on
+    // clamped rows and contributes nothing)
+    if constexpr (ACT != ACT_LSM_COOP) {
+        if (m_base >= M || n_base >= N) return;   // wave-uniform
+    }
 
     const uint32_t* arow[WM];
     const uint32_t* brow[WN];
@@ -400,6 +405,156 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
                     if (m < M && wcol < yw32) Yw[(size_t)m * yw32 + wcol] = (uint32_t)words;
                 }
             }
+        }
+    } else if constexpr (ACT == ACT_LSM_COOP) {
+        // log-Softmax of whole rows without a second kernel.  The rows of this workgroup's tile continue in the other
+        // tiles of the same frames (grid row tile_m): every workgroup reduces its 128 columns of each row to
+        // (max, sum of exp(h - max)), publishes the pair, waits for the other tiles of its grid row, combines the pairs
+        // to max + log sum exp and only then writes its share of the rows, normalised, straight from the accumulators.
+        // Publishing: write-through stores (sc1), wait until they are acknowledged, then the flag.  Readers poll the
+        // flags with loads that bypass the non-coherent caches (sc1) and then read the pairs with plain loads: no
+        // cache of this launch can hold an older copy of a pair, because nothing reads a pair before its flag is up
+        // and what earlier launches left in the caches is dropped at the kernel boundary.  The wait is bounded.
+        static_assert(WN == 2, "the transposing epilogue is written for 64-column wave tiles");
+        constexpr int LDW = 32 * WN + 4;
+        constexpr int ROWS = 32 * WM;                          // rows of a wave; the workgroup has 2 ROWS
+        __shared__ __attribute__((aligned(16))) uint32_t stage[4][32 * LDW];
+        __shared__ float2 wave_part[4][ROWS];
+        __shared__ float lse_s[2 * ROWS];
+        uint32_t* st = stage[wave];
+        const int c4 = (lane & 15) * 4;
+        const int T = (int)gridDim.y;
+        const float ninf = -__builtin_inff();
+        // (a) pre-activations, in place; columns past N count as -inf (no share in any maximum or sum)
+#pragma unroll
+        for (int fm = 0; fm < WM; ++fm)
+#pragma unroll
+            for (int fn = 0; fn < WN; ++fn) {
+                const bool col = n_base + fn * 32 + r < N;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float h = affine(sc[fn], dot_of(acc[fm][fn][v], fn), bi[fn]);
+                    acc[fm][fn][v] = col ? h : ninf;
+                }
+            }
+        // (b) this wave's 64 columns of each of its rows: through its LDS slice, 32 rows at a time, so that lane
+        //     (row = lane % 32, half = lane / 32) holds 32 consecutive columns of one row in registers: the maximum and
+        //     the sum are then taken inside a lane, with a single exchange between the two halves of a row for each
+        //     (8 consecutive lanes read 16 bytes each from rows 68 words apart: 32 different banks)
+#pragma unroll
+        for (int fm = 0; fm < WM; ++fm) {
+#pragma unroll
+            for (int fn = 0; fn < WN; ++fn)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    st[(8 * (v >> 2) + 4 * g + (v & 3)) * LDW + fn * 32 + r] = __float_as_uint(acc[fm][fn][v]);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+            float hv[32];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint4 q = *reinterpret_cast<const uint4*>(st + r * LDW + g * 32 + j * 4);
+                hv[4 * j] = __uint_as_float(q.x); hv[4 * j + 1] = __uint_as_float(q.y);
+                hv[4 * j + 2] = __uint_as_float(q.z); hv[4 * j + 3] = __uint_as_float(q.w);
+            }
+            float m4[4] = {hv[0], hv[1], hv[2], hv[3]};        // four chains: the maximum does not care about order
+#pragma unroll
+            for (int j = 4; j < 32; ++j) m4[j & 3] = __builtin_fmaxf(m4[j & 3], hv[j]);
+            float mx = __builtin_fmaxf(__builtin_fmaxf(m4[0], m4[1]), __builtin_fmaxf(m4[2], m4[3]));
+            mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (mx != ninf) {
+#pragma unroll
+                for (int j = 0; j < 32; ++j) s4[j & 3] += __expf(hv[j] - mx);
+            }
+            float s = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+            s += __shfl_xor(s, 32, kWave);
+            if (g == 0) wave_part[wave][fm * 32 + r] = make_float2(mx, s);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        }
+        __syncthreads();
+        // (c) the two waves that share a row, then out to memory
+        const int trow = (int)threadIdx.x;                     // row of the workgroup tile (threads below 2 ROWS)
+        if (trow < 2 * ROWS) {
+            const float2 pa = wave_part[2 * (trow / ROWS)][trow % ROWS], pb = wave_part[2 * (trow / ROWS) + 1][trow % ROWS];
+            const float mx = __builtin_fmaxf(pa.x, pb.x);
+            float s = 0.0f;
+            if (pa.x != ninf) s += pa.y * __expf(pa.x - mx);
+            if (pb.x != ninf) s += pb.y * __expf(pb.x - mx);
+            const unsigned long long pair = (unsigned long long)__float_as_uint(mx) | ((unsigned long long)__float_as_uint(s) << 32);
+            __hip_atomic_store(reinterpret_cast<unsigned long long*>(coop.partials + ((size_t)tile_m * T + tile_n) * (2 * ROWS) + trow), pair,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the pairs have arrived ...
+        __syncthreads();
+        if (threadIdx.x == 0)                                  // ... before the flag says so
+            __hip_atomic_store(coop.flags + (size_t)tile_m * T + tile_n, coop.stamp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (wave == 0) {
+            const unsigned long long* f = coop.flags + (size_t)tile_m * T;
+            bool ok = false;
+            for (int spin = 0; spin < coop.spin_limit; ++spin) {
+                unsigned long long v = coop.stamp;
+                if (lane < T) v = __hip_atomic_load(f + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (__builtin_amdgcn_ballot_w64(v == coop.stamp) == ~0ull) { ok = true; break; }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (!ok && lane == 0) atomicAdd(coop.timeouts, 1u);
+        }
+        __syncthreads();
+        // (d) max + log sum exp of each row over all tiles of the grid row
+        if (trow < 2 * ROWS) {
+            // (consecutive lanes read consecutive rows of one tile's pairs: whole cache lines per request; 32 requests in
+            // flight before the first pair is used)
+            const unsigned long long* src = reinterpret_cast<const unsigned long long*>(coop.partials + (size_t)tile_m * T * (2 * ROWS) + trow);
+            float mx = ninf, s = 0.0f;
+            for (int t0 = 0; t0 < T; t0 += 32) {
+                unsigned long long pr[32];
+#pragma unroll
+                for (int i = 0; i < 32; ++i)                    // (clamped: the same pair again, skipped below)
+                    pr[i] = src[(size_t)(t0 + i < T ? t0 + i : T - 1) * (2 * ROWS)];
+#pragma unroll
+                for (int i = 0; i < 32; ++i) {
+                    const float pm = __uint_as_float((uint32_t)pr[i]), ps = __uint_as_float((uint32_t)(pr[i] >> 32));
+                    if (t0 + i < T && pm != ninf) {
+                        if (pm > mx) { s = s * __expf(mx - pm) + ps; mx = pm; }   // (mx = -inf: s = 0, exp gives 0)
+                        else s += ps * __expf(pm - mx);
+                    }
+                }
+            }
+            lse_s[trow] = mx + __logf(s);
+        }
+        __syncthreads();
+        // (e) normalise and write: rows leave as contiguous 256-byte pieces, as in the plain fp32 epilogue
+        const bool rows_vec = ((N & 3) == 0) && ((reinterpret_cast<uintptr_t>(Y) & 15) == 0);
+#pragma unroll
+        for (int fm = 0; fm < WM; ++fm) {
+#pragma unroll
+            for (int fn = 0; fn < WN; ++fn)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    st[(8 * (v >> 2) + 4 * g + (v & 3)) * LDW + fn * 32 + r] = __float_as_uint(acc[fm][fn][v]);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int row = it * 4 + (lane >> 4);
+                const int m = m_base + fm * 32 + row;
+                const int n = n_base + c4;
+                const uint4 q = *reinterpret_cast<const uint4*>(st + row * LDW + c4);
+                const float l = lse_s[(wave >> 1) * ROWS + fm * 32 + row];
+                float4 o;
+                o.x = __uint_as_float(q.x) - l; o.y = __uint_as_float(q.y) - l; o.z = __uint_as_float(q.z) - l; o.w = __uint_as_float(q.w) - l;
+                if (m < M) {
+                    float* y = (float*)Y + (size_t)m * N + n;
+                    if (rows_vec && n + 3 < N) {
+                        *reinterpret_cast<float4*>(y) = o;
+                    } else {
+                        if (n + 0 < N) y[0] = o.x;
+                        if (n + 1 < N) y[1] = o.y;
+                        if (n + 2 < N) y[2] = o.z;
+                        if (n + 3 < N) y[3] = o.w;
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         }
     } else {
         // 32-bit outputs: the accumulator layout gives a lane one column and 16 scattered rows, which would

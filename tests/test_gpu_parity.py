@@ -619,6 +619,57 @@ def test_forward_config3_full_batch_every_frame(G, bnn, oracle):
     _hidden_bits_layer_by_layer(G, bnn, model, layers, X, keep)
 
 
+class _cooperative:
+    """BNN_OPT_COOPERATIVE for the duration of a test (the test process runs one stream at a time, as the option asks)."""
+
+    def __init__(self, bnn):
+        self.bnn = bnn
+
+    def __enter__(self):
+        self.before = self.bnn.bnn_cooperative_timeouts()
+        self.bnn.bnn_set_option(self.bnn.BNN_OPT_COOPERATIVE, 1)
+
+    def __exit__(self, *exc):
+        self.bnn.bnn_set_option(self.bnn.BNN_OPT_COOPERATIVE, 0)
+        assert self.bnn.bnn_cooperative_timeouts() == self.before, "a bounded wait of a cooperative kernel ran out"
+
+
+@pytest.mark.parametrize("x01", [False, True])
+@pytest.mark.parametrize("M,K,N", [(4096, 2048, 3400), (4096, 512, 2048), (3333, 1024, 3307), (2100, 512, 4001),
+                                   (2048, 2048, 8192), (257, 512, 129)])
+def test_cooperative_logsoftmax_layer(G, bnn, oracle, M, K, N, x01):
+    """The LOGSOFTMAX layer finished inside the product kernel (rows exchanged between workgroups through memory):
+    every log-posterior against the oracle, ragged frames and outputs included; the last shapes are ones the
+    cooperative kernel does not take (too many tiles to be resident at once, too few to use 128-row tiles), which
+    must fall back to the two-kernel path unharmed."""
+    aw, bw = _bin_operands(oracle, 3 * M + K + N, M, K, N, 32)
+    _, _, scale, bias = _rand_layer(M + N + 1, 1, 1, N)
+    scale = scale / np.float32(np.sqrt(K))                 # log-posteriors of a plausible spread
+    dA, dB, dsc, dbi = (G.to_dev(a) for a in (aw, bw, scale, bias))
+    fn = G.layer_binx01 if x01 else G.layer_binx
+    with _cooperative(bnn):
+        Y = fn(dA, dB, dsc, dbi, K, N, bnn.BNN_ACT_LOGSOFTMAX, 32)
+        torch.cuda.synchronize()
+        Y2 = fn(dA, dB, dsc, dbi, K, N, bnn.BNN_ACT_LOGSOFTMAX, 32)   # the hand-over area is reused: same result again
+        torch.cuda.synchronize()
+    got = Y.cpu().numpy()
+    want = (oracle.layer_binw_binx01(aw, bw, K, scale, bias, "logsoftmax", 32, form="and") if x01 else
+            oracle.layer_binw_binx(aw, bw, K, scale, bias, "logsoftmax", 32, form="xor"))
+    _close(got, want, "cooperative logsoftmax")
+    assert np.allclose(np.exp(got.astype(np.float64)).sum(1), 1.0, atol=1e-4)
+    assert np.array_equal(got, Y2.cpu().numpy())
+    plain = fn(dA, dB, dsc, dbi, K, N, bnn.BNN_ACT_LOGSOFTMAX, 32).cpu().numpy()
+    _close(got, plain, "cooperative against the two-kernel path")
+
+
+def test_forward_config3_full_batch_cooperative(G, bnn, oracle):
+    """Config 3 at its full size with the cooperative output layer, the configuration the benchmark times: every
+    log-posterior of every frame against the oracle."""
+    cfg = workloads.CONFIGS[3]
+    with _cooperative(bnn):
+        _net_parity(G, bnn, oracle, cfg, cfg.M)
+
+
 def _tile_class_frames(M, count, seed, tile=128):
     """`count` or more frames of a batch of M: the first and last tile whole, one frame of every `tile`-row tile with the
     position inside the tile running through all residues, and random ones."""
