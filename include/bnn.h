@@ -102,6 +102,10 @@ typedef enum bnn_option {
                                        frame-by-frame inference) run every layer on the vector-ALU kernels with 1 or 2 frames
                                        per workgroup, so that a layer is spread over the whole chip and takes one pass
                                        over its weight rows; 0 = never.  Default 64.  Same results either way.          */
+    BNN_OPT_MFMA32_SPLITK = 14,     /* Sign layers on the 128-row 32x32x64 kernel with K % 1024 == 0: 1 = a workgroup of 8
+                                       waves, the second four taking the second half of K and handing their sums over
+                                       through LDS (two waves per SIMD from a grid of one workgroup per CU); 0 = no
+                                       (default: measured 12.4 against 9.9 us at 4096 x 2048 x 2048).  Same bits.       */
     BNN_OPT_COOPERATIVE = 13        /* 1 = kernels whose workgroups wait for each other may be used: a binary-input
                                        LOGSOFTMAX layer on the matrix-core arm then finishes its rows inside the product
                                        kernel (the tiles of a row exchange their maxima and sums of exponentials through

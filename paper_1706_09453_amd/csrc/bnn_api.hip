@@ -48,6 +48,8 @@ std::atomic<int> g_realx_f32_mfma{0};
 std::atomic<int> g_mfma32_xcd_order{0};
 std::atomic<int> g_stream_max_frames{64};
 std::atomic<int> g_cooperative{0};
+std::atomic<int> g_mfma32_splitk{0};
+
 std::atomic<unsigned long long> g_coop_launches{0};
 constexpr int kCoopMaxDevices = 64;
 std::atomic<void*> g_coop_ptr[kCoopMaxDevices];
@@ -524,6 +526,15 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
         } else if (wm2) {
             if (pinned) launch_binx_mfma32<2, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
             else launch_binx_mfma32<2, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
+        } else if (act == BNN_ACT_SIGN && pinned && K % 1024 == 0 && g_mfma32_splitk.load() == 1) {
+            // two waves per SIMD from a grid of one workgroup per CU, by splitting K inside the workgroup (comparison
+            // arm: measured slower at Config 3's size, see the option)
+            const int xsel = g_mfma32_xcd_order.load();
+            const int xo = xsel == 1 || (xsel == 0 && ((size_t)M * w32 * 4 > ((size_t)32 << 20) ||
+                                                      (N >= 4096 && (size_t)M * N / 8 >= ((size_t)32 << 20))));
+            const dim3 grid((Mi + 255) / 256, (Ni + 127) / 128), block(512);
+            binx_mfma32_kernel<4, 2, ACT_SIGN, true, true, false, true><<<grid, block, 0, st>>>(
+                A, B, scale, bias, Mi, Ki, Ni, w32, Y, yw32, (unsigned int)((size_t)M * w32 * 4), (unsigned int)((size_t)N * w32 * 4), xo, CoopLsm{});
         } else {
             if (pinned) launch_binx_mfma32<4, true, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st, coop);
             else launch_binx_mfma32<4, true>(A, B, scale, bias, Mi, Ki, Ni, w32, act, Y, yw32, st);
@@ -698,6 +709,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_COOPERATIVE:
             if (value != 0 && value != 1) return BNN_EINVAL;
             g_cooperative.store(value);
+            return BNN_OK;
+        case BNN_OPT_MFMA32_SPLITK:
+            if (value != 0 && value != 1) return BNN_EINVAL;
+            g_mfma32_splitk.store(value);
             return BNN_OK;
         default: return BNN_EINVAL;
     }

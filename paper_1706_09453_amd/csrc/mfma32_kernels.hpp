@@ -87,14 +87,22 @@ __device__ __forceinline__ uint32_t word_of(const Raw8& v, int j) {
 // bits, h = (a + 1) / 2 and h.w = (a.w + sum_k w_k) / 2: the product runs unchanged, every lane counts the 1 bits of
 // the weight words it fetches anyway (the two lanes that share a row add theirs up), and the epilogue forms
 // 0.5 (a.w) + (popcount(w) - K/2), exact in fp32.
-// Grid: x = ceil(M / (64*WM)), y = ceil(N / (64*WN)); block = 256 threads.
-template <int WM, int WN, int ACT, bool ALIGNED, bool PINGPONG = false, bool X01 = false>
-__global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
+// SPLITK (128-row pinned variant only, K a multiple of 1024): the workgroup has 8 waves; waves 4..7 own the same four
+// wave tiles as waves 0..3 and take the second half of K, so that a grid of one workgroup per CU still puts TWO waves
+// on every SIMD (a single wave per SIMD cannot cover its own operand latencies: measured 28 ns per MFMA against 17-19
+// with two).  Their partial sums (small integers, exact in fp32 in any order) go to waves 0..3 through LDS, 64
+// accumulator registers at a time; waves 0..3 run the epilogue.
+// Grid: x = ceil(M / (64*WM)), y = ceil(N / (64*WN)); block = 256 threads (512 with SPLITK).
+template <int WM, int WN, int ACT, bool ALIGNED, bool PINGPONG = false, bool X01 = false, bool SPLITK = false>
+__global__ __launch_bounds__(SPLITK ? 512 : 256, SPLITK ? 1 : 2) void binx_mfma32_kernel(const uint32_t* __restrict__ Xp, const uint32_t* __restrict__ Wp,
                                                           const float* __restrict__ scale, const float* __restrict__ bias,
                                                           int M, int K, int N, int w32, void* __restrict__ Y, int yw32,
                                                           unsigned int a_bytes, unsigned int b_bytes, int xcd_order,
                                                           const CoopLsm coop) {
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    static_assert(!SPLITK || (WM == 4 && PINGPONG && !X01 && ACT != ACT_LSM_COOP), "split K: 128-row pinned variant, -1/+1 inputs");
+    const int wave_all = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int wave = SPLITK ? (wave_all & 3) : wave_all;   // which wave tile of the workgroup
+    const int khalf = SPLITK ? (wave_all >> 2) : 0;        // which half of K
     const int lane = lane_id();
     const int r = lane & 31;   // row of the operand fragment / column of the accumulator fragment
     const int g = lane >> 5;   // k-group of the operand fragment / row-group of the accumulator fragment
@@ -206,7 +214,13 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
             // Three sets in rotation, fetched two half-steps ahead: with one wave per SIMD (4096 x 2048 outputs fill the
             // chip exactly once) nothing else covers the memory latency, and one half-step of products is shorter.
             uint4 a0[WM], b0[WN], a1[WM], b1[WN], a2[WM], b2[WN];
-            const int H = 2 * nS;   // half-steps
+            const int H = SPLITK ? nS : 2 * nS;   // half-steps of this wave (split K: nS is even, each half has nS / 2 super-steps)
+            if constexpr (SPLITK) {
+#pragma unroll
+                for (int f = 0; f < WM; ++f) arow[f] += khalf * (nS >> 1) * 16;
+#pragma unroll
+                for (int f = 0; f < WN; ++f) brow[f] += khalf * (nS >> 1) * 16;
+            }
             // (plain pointer loads here: buffer addressing saves the address arithmetic but measured 3 % slower on
             //  this variant, as did a peeled first round with zero addends: more code to fetch for four rounds)
             auto fetch = [&](uint4 (&a)[WM], uint4 (&b)[WN], int h) {
@@ -367,6 +381,41 @@ __global__ __launch_bounds__(256, 2) void binx_mfma32_kernel(const uint32_t* __r
 #pragma unroll
             for (int f = 0; f < WN; ++f) braw[f] = bnext[f];
         }
+    }
+
+    if constexpr (SPLITK) {
+        // the second half of K joins the first: 64 accumulator registers per round through 64 KiB of LDS
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        __shared__ f32x4 xch[4][16][kWave];   // [wave tile][four registers][lane]
+#pragma unroll
+        for (int round = 0; round < 2; ++round) {
+            if (khalf == 1) {
+#pragma unroll
+                for (int fmh = 0; fmh < 2; ++fmh)
+#pragma unroll
+                    for (int fn = 0; fn < WN; ++fn)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const v16f& c = acc[2 * round + fmh][fn];
+                            xch[wave][(fmh * 2 + fn) * 4 + q][lane] = f32x4{c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]};
+                        }
+            }
+            __syncthreads();
+            if (khalf == 0) {
+#pragma unroll
+                for (int fmh = 0; fmh < 2; ++fmh)
+#pragma unroll
+                    for (int fn = 0; fn < WN; ++fn)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x4 p = xch[wave][(fmh * 2 + fn) * 4 + q][lane];
+                            v16f& c = acc[2 * round + fmh][fn];
+                            c[4 * q] += p[0]; c[4 * q + 1] += p[1]; c[4 * q + 2] += p[2]; c[4 * q + 3] += p[3];
+                        }
+            }
+            if (round == 0) __syncthreads();   // everything read before the second round overwrites it
+        }
+        if (khalf == 1) return;   // wave-uniform; no barrier follows
     }
 
     // ---- epilogue.  Accumulator fragment (fm, fn), register v of lane (r, g) is

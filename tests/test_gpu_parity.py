@@ -619,6 +619,32 @@ def test_forward_config3_full_batch_every_frame(G, bnn, oracle):
     _hidden_bits_layer_by_layer(G, bnn, model, layers, X, keep)
 
 
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("M,K,N", [(4096, 2048, 2048), (300, 1024, 200), (777, 3072, 333), (130, 2048, 129), (1, 1024, 1),
+                                   (520, 4096, 2050)])
+def test_binx_sign_split_k(G, bnn, oracle, M, K, N, wb):
+    """Sign layers with K split between the two halves of an 8-wave workgroup (BNN_OPT_MFMA32_SPLITK, a comparison arm):
+    same bits, ragged shapes included."""
+    aw, bw = _bin_operands(oracle, 7 * M + K + N, M, K, N, wb)
+    _, _, scale, bias = _rand_layer(M + N + 3, 1, 1, N)
+    bnn.bnn_set_option(bnn.BNN_OPT_MFMA_SHAPE, 32)
+    bnn.bnn_set_option(bnn.BNN_OPT_MFMA32_WM, 4)
+    bnn.bnn_set_option(bnn.BNN_OPT_MFMA32_SPLITK, 1)
+    try:
+        Y = G.layer_binx(G.to_dev(aw), G.to_dev(bw), G.to_dev(scale), G.to_dev(bias), K, N, bnn.BNN_ACT_SIGN, wb)
+        torch.cuda.synchronize()
+        bnn.bnn_set_option(bnn.BNN_OPT_MFMA32_SPLITK, 0)
+        Y_off = G.layer_binx(G.to_dev(aw), G.to_dev(bw), G.to_dev(scale), G.to_dev(bias), K, N, bnn.BNN_ACT_SIGN, wb)
+        torch.cuda.synchronize()
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_MFMA_SHAPE, 0)
+        bnn.bnn_set_option(bnn.BNN_OPT_MFMA32_WM, 0)
+        bnn.bnn_set_option(bnn.BNN_OPT_MFMA32_SPLITK, 0)
+    want = oracle.layer_binw_binx(aw, bw, K, scale, bias, "sign", wb, form="xor")
+    assert np.array_equal(G.words_to_host(Y, wb), want)
+    assert np.array_equal(G.words_to_host(Y_off, wb), want)
+
+
 class _cooperative:
     """BNN_OPT_COOPERATIVE for the duration of a test (the test process runs one stream at a time, as the option asks)."""
 
