@@ -342,43 +342,6 @@ __global__ __launch_bounds__(kRealxThreads) void realx_sign_fused_kernel(const f
     // ---- resolve the listed outputs exactly: fp32 sum in ascending k, one lane per output; the frame comes from
     //      LDS, the packed weight row (all its words fetched first: one memory latency) from global memory
     const int count = (int)min(list_count, (unsigned int)kRealxListCap);
-    const int tstride = kpad + 4;                                   // floats per output in the term table
-    const int term_rows = min(kWave, (2 * stage_words) / tstride);  // outputs the table holds (the weight stages are free now)
-    if (count <= term_rows) {
-        // The usual case, a handful of outputs.  All threads first form the signed terms +-x[k] of every listed sum side
-        // by side and park them in LDS; then one lane per output runs down its terms in ascending k, 32 terms per batch
-        // of LDS reads.  acc + (+-x) rounds exactly as fma(+-1, x, acc) does.  (One lane per output doing everything,
-        // as below, spends three instructions and an LDS read per term: 3.5x the time, with the other waves idle.)
-        float* terms = reinterpret_cast<float*>(wst);
-        for (int i = 0; i < count; ++i) {
-            const unsigned int e = list[i];
-            const int ml = (int)(e >> 16), nl = (int)(e & 0xFFFFu);
-            const int k = (int)threadIdx.x;
-            if (k < K) {
-                const uint32_t flip = (~Wp[(size_t)(n_block + nl) * w32 + (k >> 5)] >> (k & 31)) << 31;   // weight bit 0: -x
-                terms[i * tstride + k] = __uint_as_float(__float_as_uint(xs[ml * xstride + k]) ^ flip);
-            }
-        }
-        __syncthreads();
-        if ((int)threadIdx.x < count) {
-            const unsigned int e = list[threadIdx.x];
-            const int ml = (int)(e >> 16), nl = (int)(e & 0xFFFFu);
-            const int n = n_block + nl;
-            const float* tr = terms + threadIdx.x * tstride;
-            float acc = 0.0f;
-            int k = 0;
-            for (; k + 32 <= K; k += 32) {
-                float4 t4[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) t4[j] = *reinterpret_cast<const float4*>(tr + k + 4 * j);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) { acc += t4[j].x; acc += t4[j].y; acc += t4[j].z; acc += t4[j].w; }
-            }
-            for (; k < K; ++k) acc += tr[k];
-            const float s1 = scale ? scale[n] : 1.0f, b1 = bias ? bias[n] : 0.0f;
-            if (sign_bit(affine(s1, acc, b1))) atomicOr(&tile[(size_t)ml * tw + (nl >> 5)], 1u << (nl & 31));
-        }
-    } else
     for (int i = threadIdx.x; i < count; i += kRealxThreads) {
         const unsigned int e = list[i];
         const int ml = (int)(e >> 16), nl = (int)(e & 0xFFFFu);
