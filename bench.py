@@ -3,7 +3,9 @@
 
 A step is one bnn_forward over one batch: Config 3 of the benchmark set (440 -> 6 x 2048 -> 3400, binary
 weights and binary activations, 4096 synthetic frames, 32-bit packed words), all seven layers, inputs and
-the packed model already resident in HBM.  Prints ONE JSON line with frames/s, binary TOPS, the roofline
+the packed model already resident in HBM.  The K timed steps are issued round-robin to --streams HIP streams (default 4:
+four batches in flight, as a server with queued batches runs them); "single_stream" in the line is the same K steps one
+after the other.  Prints ONE JSON line with frames/s, binary TOPS, the roofline
 of the dominant kernel (timed live with HIP events on the launch stream) and the CPU oracle timed on the
 host cores on a bounded sample of the same workload.
 
@@ -276,6 +278,9 @@ def main() -> int:
     ap.add_argument("--arm", choices=["mfma", "mfma_i8", "valu"], default="mfma",
                     help="arm of the binary product: 4-bit-float MFMA (default), int8 MFMA, or XOR/popcount on the vector ALU")
     ap.add_argument("--cpu-sample-frames", type=int, default=4096)
+    ap.add_argument("--streams", type=int, default=4,
+                    help="steps in flight: the K timed steps go round-robin to this many HIP streams, each with its own "
+                         "batch, output and workspace (1 = one step after the other)")
     ap.add_argument("--no-cooperative", action="store_true",
                     help="leave BNN_OPT_COOPERATIVE off: the output layer then runs as product kernel + row kernel")
     ap.add_argument("--no-configs", action="store_true",
@@ -356,8 +361,44 @@ def main() -> int:
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     dev_ms = e0.elapsed_time(e1)
-    ms_per_step = wall_ms / args.steps
+    single_ms_per_step = wall_ms / args.steps
+    ms_per_step = single_ms_per_step
     frames_per_s = M / (ms_per_step * 1e-3)
+
+    # ---- the same K steps with several of them in flight: S streams, each with its own batch of 4096 frames, its own
+    #      output and workspace (what a server with batches queued up does).  A hidden-layer launch gives every SIMD one
+    #      wave; a second launch beside it fills the matrix cores' idle slots and the gaps between dependent launches.
+    #      Kernels that wait for each other need the device to themselves, so BNN_OPT_COOPERATIVE is off here.
+    S = max(1, args.streams)
+    pipelined = None
+    if S > 1:
+        bnn.bnn_set_option(bnn.BNN_OPT_COOPERATIVE, 0)
+        nbytes = bnn.bnn_forward_workspace_bytes(model.layers, model.n_layers, M)
+        streams = [torch.cuda.Stream() for _ in range(S)]
+        Xs = [X] + [X.clone() for _ in range(S - 1)]
+        outs = [torch.empty_like(out) for _ in range(S)]
+        wss = [torch.empty(max(nbytes, 256), dtype=torch.uint8, device=G.DEV) for _ in range(S)]
+        torch.cuda.synchronize()
+
+        def step(i):
+            j = i % S
+            bnn.bnn_forward(model.layers, model.n_layers, Xs[j].data_ptr(), M, outs[j].data_ptr(), wss[j].data_ptr(), nbytes,
+                            streams[j].cuda_stream)
+        for i in range(max(args.warmup, S)):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        frames_per_s = M / (ms_per_step * 1e-3)
+        scale_out = float(out.abs().max())
+        pipelined = {"streams": S, "ms_per_step": round(ms_per_step, 5), "frames_per_s": round(frames_per_s, 1),
+                     "outputs_identical_across_streams": all(torch.equal(outs[0], o) for o in outs[1:]),
+                     "max_abs_diff_to_single_stream": float((outs[0] - out).abs().max()), "output_scale": scale_out}
+        del Xs, wss
+        bnn.bnn_set_option(bnn.BNN_OPT_COOPERATIVE, 1 if cooperative else 0)
 
     macs_all = cfg.macs_per_frame() * M
     macs_bin = cfg.binbin_macs_per_frame() * M
@@ -443,8 +484,12 @@ def main() -> int:
                   "valu": "b1 (xor+popcount u32) + f32"}[args.arm],
         "data": "synthetic",
         "config": {"workload": cfg.name, "dims": list(cfg.dims), "batch_frames": M, "word_bits": cfg.word_bits,
-                   "binx_arm": args.arm, "options": {"BNN_OPT_COOPERATIVE": int(cooperative)}},
-        "device_ms_per_step": round(dev_ms / args.steps, 5),
+                   "binx_arm": args.arm, "steps_in_flight": S,
+                   "options": {"BNN_OPT_COOPERATIVE": 0 if S > 1 else int(cooperative)}},
+        # one step after the other on one stream (with the cooperative output layer unless --no-cooperative)
+        "single_stream": {"ms_per_step": round(single_ms_per_step, 5), "frames_per_s": round(M / (single_ms_per_step * 1e-3), 1),
+                          "options": {"BNN_OPT_COOPERATIVE": int(cooperative)}},
+        "device_ms_per_step_single_stream": round(dev_ms / args.steps, 5),
         "binary_tops_all_layers": round(2.0 * macs_all / (ms_per_step * 1e-3) / 1e12, 2),
         "binary_tops_binbin_kernels": round(binbin_tops, 2),
         "layer_us": [round(v, 2) for v in layer_us],
@@ -493,11 +538,18 @@ def main() -> int:
         lines += [time_gemm(sh, bnn.BNN_ARM_MFMA, 10 if sh.M * sh.K * sh.N < 1e12 else 3, bnn, workloads, G, torch)
                   for sh in corners]
         result["configs"] = lines
+    if pipelined:
+        result["pipelined"] = pipelined
     if cooperative:
         result["cooperative_timeouts"] = bnn.bnn_cooperative_timeouts()
     print(json.dumps(result))
     if result.get("cooperative_timeouts"):
         print("bench.py: a cooperative kernel's bounded wait ran out", file=sys.stderr)
+        return 1
+    if pipelined and not (pipelined["outputs_identical_across_streams"] and
+                          pipelined["max_abs_diff_to_single_stream"] <= 1e-4 * pipelined["output_scale"]):
+        print("bench.py: the steps in flight on several streams disagree with each other or with the single-stream pass",
+              file=sys.stderr)
         return 1
     cb = result.get("cpu_baseline")
     if cb and not cb["gpu_vs_oracle_max_abs_err"] <= 1e-4 * cb["oracle_output_scale"]:

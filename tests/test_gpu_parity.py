@@ -840,6 +840,33 @@ def test_forward_twice_same_result_and_other_stream(G, bnn, oracle):
     assert torch.equal(a, b)
 
 
+def test_forward_several_batches_in_flight_on_four_streams(G, bnn, oracle):
+    """Config 3 at its full size with four batches in flight on four streams (the way the benchmark issues its steps):
+    each stream has its own frames, output and workspace, the packed model is shared; every output equals the one the
+    same frames give alone on one stream, bit for bit, over three rounds."""
+    cfg = workloads.CONFIGS[3]
+    Ws, bs = workloads.make_net_params(cfg)
+    model = G.GpuModel(Ws, bs, cfg.hidden_act, cfg.word_bits)
+    M, S = cfg.M, 4
+    rng = np.random.default_rng(77)
+    Xh = [workloads.make_frames(cfg)] + [rng.standard_normal((M, cfg.dims[0])).astype(np.float32) for _ in range(S - 1)]
+    Xs = [G.to_dev(x) for x in Xh]
+    alone = [model.forward(x).clone() for x in Xs]
+    torch.cuda.synchronize()
+    nbytes = bnn.bnn_forward_workspace_bytes(model.layers, model.n_layers, M)
+    streams = [torch.cuda.Stream() for _ in range(S)]
+    outs = [torch.full((M, model.N_out), float("nan"), dtype=torch.float32, device=G.DEV) for _ in range(S)]
+    wss = [torch.empty(max(nbytes, 256), dtype=torch.uint8, device=G.DEV) for _ in range(S)]
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for j in range(S):
+            bnn.bnn_forward(model.layers, model.n_layers, Xs[j].data_ptr(), M, outs[j].data_ptr(), wss[j].data_ptr(), nbytes,
+                            streams[j].cuda_stream)
+    torch.cuda.synchronize()
+    for j in range(S):
+        assert torch.equal(outs[j], alone[j]), f"stream {j}"
+
+
 # ----------------------------------------------------------------------------- seeded random shapes, every layer kind
 
 def _random_shapes(seed, count):
