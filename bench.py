@@ -374,16 +374,34 @@ def main() -> int:
     if S > 1:
         bnn.bnn_set_option(bnn.BNN_OPT_COOPERATIVE, 0)
         nbytes = bnn.bnn_forward_workspace_bytes(model.layers, model.n_layers, M)
-        streams = [torch.cuda.Stream() for _ in range(S)]
         Xs = [X] + [X.clone() for _ in range(S - 1)]
         outs = [torch.empty_like(out) for _ in range(S)]
         wss = [torch.empty(max(nbytes, 256), dtype=torch.uint8, device=G.DEV) for _ in range(S)]
         torch.cuda.synchronize()
+        streams = None
 
         def step(i):
             j = i % S
             bnn.bnn_forward(model.layers, model.n_layers, Xs[j].data_ptr(), M, outs[j].data_ptr(), wss[j].data_ptr(), nbytes,
                             streams[j].cuda_stream)
+        # Streams share the process's few hardware queues, and which streams end up on one queue (and then run one
+        # after the other) depends on the order the runtime created them in: as part of the warm-up, a few sets of S
+        # streams out of 2 S + 1 candidates run 40 untimed steps each, and the fastest set takes the timed steps.
+        pool = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(2 * S)]
+        best = None
+        for first in range(0, S + 2):
+            streams = pool[first:first + S]
+            for i in range(2 * S):
+                step(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(40):
+                step(i)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            if best is None or dt < best[0]:
+                best = (dt, first)
+        streams = pool[best[1]:best[1] + S]
         for i in range(max(args.warmup, S)):
             step(i)
         torch.cuda.synchronize()
@@ -394,7 +412,8 @@ def main() -> int:
         ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
         frames_per_s = M / (ms_per_step * 1e-3)
         scale_out = float(out.abs().max())
-        pipelined = {"streams": S, "ms_per_step": round(ms_per_step, 5), "frames_per_s": round(frames_per_s, 1),
+        pipelined = {"streams": S, "stream_set": f"candidates {best[1]}..{best[1] + S - 1} of {len(pool)} (fastest of {S + 2} sets in the warm-up)",
+                     "ms_per_step": round(ms_per_step, 5), "frames_per_s": round(frames_per_s, 1),
                      "outputs_identical_across_streams": all(torch.equal(outs[0], o) for o in outs[1:]),
                      "max_abs_diff_to_single_stream": float((outs[0] - out).abs().max()), "output_scale": scale_out}
         del Xs, wss
@@ -436,6 +455,31 @@ def main() -> int:
         torch.cuda.synchronize()
         layer_us.append(a.elapsed_time(b) * 1e3 / reps)
 
+    # ---- the hidden layers' kernel with four launches in flight (four streams, own output each, same operands): what the
+    #      kernel sustains when a second workgroup shares each CU, as in the pipelined steps above
+    in_flight = None
+    if S > 1 and model.n_layers > 2:
+        d = model.descs[1]
+        st4 = streams
+        dst4 = [torch.empty_like(ws_bits[1]) for _ in range(S)]
+        torch.cuda.synchronize()
+
+        def call4(i):
+            bnn.bnn_layer_binw_binx(ws_bits[0].data_ptr(), d["Wp"], d["scale"], d["bias"], M, d["K"], d["N"], d["act"],
+                                    d["word_bits"], dst4[i % S].data_ptr(), st4[i % S].cuda_stream)
+        for i in range(8 * S):
+            call4(i)
+        torch.cuda.synchronize()
+        n4 = 100 * S
+        t0 = time.perf_counter()
+        for i in range(n4):
+            call4(i)
+        torch.cuda.synchronize()
+        us4 = (time.perf_counter() - t0) * 1e6 / n4
+        tf4 = 2.0 * M * d["K"] * d["N"] / (us4 * 1e-6) / 1e12
+        in_flight = {"streams": S, "avg_launch_us": round(us4, 2), "achieved": round(tf4, 1),
+                     "identical_outputs": all(torch.equal(dst4[0], o) for o in dst4[1:]) and torch.equal(dst4[0], ws_bits[1])}
+
     # kernel groups: layer 1 (real input), hidden binary layers (one kernel, launched 5x per step), output layer
     hidden_us = layer_us[1:-1]
     groups = {
@@ -474,6 +518,10 @@ def main() -> int:
                 # every binary x binary layer of the step (5 hidden + the output layer with its log-softmax), products
                 # over the sum of their launch times, against the same matrix-core peak
                 "frac_all_binbin": round(binbin_tops / peak, 4) if bound == "mfma" and not dominant.startswith("realx") else None}
+    if in_flight and dominant.startswith("binx hidden") and bound == "mfma":
+        # the same kernel, same shape, with launches in flight on several streams (host clock over 100 launches per stream)
+        in_flight["frac"] = round(in_flight["achieved"] / peak, 4)
+        roofline["launches_in_flight"] = in_flight
 
     result = {
         "metric": "frames/sec, 6x2048 binarized DNN (binary weights and activations), batch 4096, 1xMI355X",
