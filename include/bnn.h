@@ -27,6 +27,12 @@
  *     packed row is byte-identical to the 32-bit packed row padded to a multiple of 8 bytes.
  *   - word_bits is 32 or 64.  Packed pointers must be aligned to word_bits/8 bytes, fp32 pointers to 4.
  *   - M and K are at most 2^30 (K < 2^24 for a binary input), N at most 2^22; beyond that: BNN_ESHAPE.
+ *   - Calls may be made from several host threads and on several streams at once, as long as their outputs and
+ *     workspaces are distinct (inputs and the packed model may be shared): the library keeps no per-call state on
+ *     the host or the device.  Two exceptions, each stated at its entry point or option: bnn_forward_static (one
+ *     scratch array per device) and BNN_OPT_COOPERATIVE (one such kernel on a device at a time).  Several batches
+ *     in flight on several streams is also how the device is used best: a layer launch of a few thousand frames
+ *     leaves half of every CU's wave slots free for the launch beside it.
  *   - Output buffers must not overlap input buffers.
  *   - Return value: BNN_OK (0) or a negative bnn_status.  On error nothing has been
  *     enqueued.  M == 0 is valid and does nothing.
