@@ -14,6 +14,7 @@
 #include "mfma_kernels.hpp"
 #include "pack_kernels.hpp"
 #include "realx_fused_kernel.hpp"
+#include "realx_slab_kernels.hpp"
 #include "softmax_kernels.hpp"
 #include "train_kernels.hpp"
 #include "valu_kernels.hpp"
@@ -614,6 +615,48 @@ int run_realx_sign_mfma(const float* X, const void* Wp, const float* scale, cons
     return launch_status();
 }
 
+// The same filter for any real-input Sign layer (any position in the network, K up to kSlabMaxK): the frames are
+// quantised into digit planes in the caller's workspace first, then K streams through LDS in slabs.
+bool realx_sign_slab_applies(const bnn_layer_desc& d) {
+    return !d.x_is_binary && !d.w_is_real && d.act == BNN_ACT_SIGN && d.K <= kSlabMaxK;
+}
+size_t realx_sign_slab_bytes(int64_t M, int64_t K) {
+    const size_t kpad = (size_t)(K + 63) / 64 * 64;
+    return (kDigits * (size_t)M * kpad + 255) / 256 * 256 + ((size_t)M * sizeof(RowMeta) + 255) / 256 * 256;
+}
+int run_realx_sign_slab(const float* X, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K,
+                        int64_t N, int wb, void* Y, void* scratch_mem, hipStream_t st) {
+    const int Mi = (int)M, Ki = (int)K, Ni = (int)N;
+    const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
+    const int kpad = (Ki + 63) / 64 * 64;
+    int8_t* planes = static_cast<int8_t*>(scratch_mem);
+    RowMeta* meta = reinterpret_cast<RowMeta*>(planes + (kDigits * (size_t)M * kpad + 255) / 256 * 256);
+    if (Ki % 4 == 0 && Ki <= 2048 && aligned(X, 16))
+        realx_quantize_kernel<true><<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, kpad, slab_quant_bits(Ki), planes, meta);
+    else
+        realx_quantize_kernel<false><<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, kpad, slab_quant_bits(Ki), planes, meta);
+    const size_t lds = slab_dynamic_lds();
+    const bool vec16 = aligned(Wp, 16) && (w32 % 4 == 0);
+    static std::atomic<int> granted[2] = {{0}, {0}};   // more than 64 KB of LDS per workgroup has to be requested explicitly
+    if (!granted[vec16].load()) {
+        const void* fn = vec16 ? reinterpret_cast<const void*>(realx_sign_slab_kernel<true>)
+                               : reinterpret_cast<const void*>(realx_sign_slab_kernel<false>);
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            return BNN_EDEVICE;
+        }
+        granted[vec16].store(1);
+    }
+    const dim3 grid((Mi + kRealxBM - 1) / kRealxBM, (Ni + kSlabNB - 1) / kSlabNB), block(kSlabThreads);
+    if (vec16)
+        realx_sign_slab_kernel<true><<<grid, block, lds, st>>>(X, planes, meta, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki,
+                                                              kpad, Ni, w32, static_cast<uint32_t*>(Y), yw32);
+    else
+        realx_sign_slab_kernel<false><<<grid, block, lds, st>>>(X, planes, meta, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki,
+                                                               kpad, Ni, w32, static_cast<uint32_t*>(Y), yw32);
+    return launch_status();
+}
+
 int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
     if (!L || n_layers <= 0) return BNN_EINVAL;
     if (M < 0 || M > kMaxDim) return BNN_ESHAPE;
@@ -940,7 +983,7 @@ BNN_EXPORT int bnn_semi_stochastic_binarize(float* w, const float* u, int64_t co
 }
 
 // Workspace layout of bnn_forward: two ping-pong buffers of `half` bytes, then `unpacked` bytes for the fp32 copy of
-// the bits that a real-weight layer reads.
+// the bits that a real-weight layer reads, or for the digit planes of a real-input Sign layer (whichever is larger).
 struct ForwardWorkspace {
     size_t half, unpacked;
 };
@@ -953,6 +996,11 @@ static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_la
         }
         if (layers[l].w_is_real && layers[l].x_is_binary) {
             const size_t b = (size_t)M * (size_t)layers[l].K * 4;
+            if (b > unpacked) unpacked = b;
+        }
+        // digit planes of a real-input Sign layer that the first-layer kernel does not take (same region: one layer at a time)
+        if (realx_sign_slab_applies(layers[l]) && !(l == 0 && realx_sign_mfma_applies(layers[l]))) {
+            const size_t b = realx_sign_slab_bytes(M, layers[l].K);
             if (b > unpacked) unpacked = b;
         }
     }
@@ -1048,6 +1096,9 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
             } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load() && M > g_stream_max_frames.load()) {
                 rc = run_realx_sign_mfma(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
                                          o, st);
+            } else if (realx_sign_slab_applies(d) && g_realx_sign_mfma.load() && M > g_stream_max_frames.load()) {
+                rc = run_realx_sign_slab(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits, o,
+                                         unpacked, st);
             } else {
                 rc = run_realx(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o,
                                st);

@@ -477,7 +477,10 @@ def _first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, use_mfma):
 
 @pytest.mark.parametrize("wb", [32, 64])
 @pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 31, 5), (70, 33, 65), (64, 440, 512), (300, 440, 2048), (130, 64, 200),
-                                   (37, 1023, 300), (50, 100, 3307), (257, 129, 129)])
+                                   (37, 1023, 300), (50, 100, 3307), (257, 129, 129),
+                                   # more than 512 inputs: the filter with K streamed in slabs
+                                   (130, 513, 65), (300, 2048, 700), (64, 4096, 200), (33, 8192, 40), (17, 600, 1025),
+                                   (1000, 2048, 2048)])
 def test_first_layer_mfma_filter_bit_exact(G, bnn, oracle, M, K, N, wb):
     X, W, scale, bias = _rand_layer(M * 7 + K + N, M, K, N)
     Wp = oracle.pack_sign(W, wb)
@@ -506,8 +509,31 @@ def test_first_layer_mfma_filter_all_outputs_near_tie(G, bnn, oracle):
     assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, True), want)
 
 
-def test_first_layer_mfma_filter_special_rows(G, bnn, oracle):
-    M, K, N, wb = 70, 440, 130, 32
+def test_slab_filter_sigmoid_inputs_and_near_ties(G, bnn, oracle):
+    """The layer the paper's (sigma, b, ...) topology puts behind its first Sigmoid layer: 2048 inputs in (0, 1), Sign
+    outputs.  Half of the biases are set so that the pre-activation of frame 0 is within rounding of 0: those outputs go
+    through the exact sums (list, several passes of the term table, overflow), the others through the filter."""
+    M, K, N, wb = 200, 2048, 1100, 32
+    rng = np.random.default_rng(11)
+    X = (1.0 / (1.0 + np.exp(-rng.standard_normal((M, K))))).astype(np.float32)
+    X[1::2] = X[0] * np.float32(1.0 + 2.0 ** -21)                 # many frames nearly equal to frame 0
+    W = rng.uniform(-1, 1, (N, K)).astype(np.float32)
+    Wp = oracle.pack_sign(W, wb)
+    scale = np.full(N, 0.25, np.float32)
+    scale[::5] = -0.25
+    acc32, _ = oracle.realx_acc(X[:1], oracle.unpack_pm1(Wp, K, wb))
+    bias = (rng.standard_normal(N) * 3).astype(np.float32)
+    bias[::2] = (-scale[::2] * acc32[0, ::2]).astype(np.float32)
+    bias[::6] = np.nextafter(bias[::6], np.float32(np.inf))
+    want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "sign", wb)
+    frac = np.unpackbits(want.view(np.uint8), bitorder="little").mean()
+    assert 0.05 < frac < 0.95
+    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, True), want)
+
+
+@pytest.mark.parametrize("K", [440, 1100])
+def test_first_layer_mfma_filter_special_rows(G, bnn, oracle, K):
+    M, N, wb = 70, 130, 32
     X, W, scale, bias = _rand_layer(123, M, K, N)
     X[0] = 0.0
     X[1] *= np.float32(1e-41)          # subnormal row
