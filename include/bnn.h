@@ -82,8 +82,11 @@ typedef enum bnn_option {
                                   that many frames per wavefront on the row-broadcast kernel.  Same results.        */
     BNN_OPT_BINX_VALU_TM = 3,  /* frames per wavefront of the XOR/popcount kernel: 1, 2, 4, 8, 16 (default) or 32  */
     BNN_OPT_MFMA_WM = 4,       /* 16-row accumulator fragments per wavefront of the matrix-core kernel: 2 or 4  */
-    BNN_OPT_REALX_SIGN_MFMA = 5, /* bnn_forward, first layer real input -> Sign: 1 = matrix-core filter with exact
-                                   resolution of uncertain outputs (default), 0 = vector-ALU kernel; same bits  */
+    BNN_OPT_REALX_SIGN_MFMA = 5, /* bnn_forward, binary-weight layers real input -> Sign (the first layer of a
+                                   binary-activation network; the layer behind a Sigmoid layer in the paper's Table 2
+                                   topology): 1 = matrix-core filter with exact sums for the outputs it cannot decide
+                                   (default; K <= 8192, scratch from the forward workspace for K > 512 or layers other
+                                   than the first), 0 = vector-ALU kernel; same bits                             */
     BNN_OPT_FUSED_LOGSOFTMAX = 6, /* binary-input LOGSOFTMAX layer on the matrix-core arm: 1 = product and
                                    log-Softmax in one kernel (needs K % 256 == 0 and N <= 4096),
                                    0 = product kernel followed by a row kernel (default: measured faster)        */
