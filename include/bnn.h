@@ -260,7 +260,8 @@ size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, i
  *   workspace DEVICE scratch of at least bnn_forward_workspace_bytes() bytes, 256-byte aligned
  *             (may be NULL for a one-layer network)
  * A layer with w_is_real = 1 runs as bnn_layer_realw (after bnn_unpack_activations if its input is binary).
- * Enqueues one kernel per layer (two for a LOGSOFTMAX layer) on `stream`, no host synchronisation.
+ * Enqueues one kernel per layer (two for a LOGSOFTMAX layer or a real-input Sign layer on the slab filter) on `stream`,
+ * no host synchronisation.
  */
 int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
                 void* workspace, size_t workspace_bytes, void* stream);
@@ -271,7 +272,9 @@ int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64
  * BNN_FORWARD_STATIC_MAX_BYTES array inside the library's device image.  Calls no hipMalloc / hipFree or any other
  * allocating routine.  Arguments, results and errors as bnn_forward, except:
  *   - BNN_EWORKSPACE if bnn_forward_workspace_bytes(layers, n_layers, M) exceeds BNN_FORWARD_STATIC_MAX_BYTES
- *     (16 MiB: Config-3-sized networks up to 32768 frames, 4096-unit ones up to 16384);
+ *     (16 MiB: Config-3-sized networks up to 32768 frames, 4096-unit ones up to 16384; a network with a real-input
+ *     Sign layer that is not its first layer, or has more than 512 inputs, also keeps 3 bytes per input and frame of
+ *     that layer there: 2048 inputs fit up to about 2600 frames);
  *   - BNN_EDEVICE if the array's address cannot be obtained on the current device.
  * Every call on a GPU shares that GPU's one array: calls that overlap in time on one GPU (different streams or threads)
  * race on it; calls on one stream are ordered and safe.  Nothing in the array has to be cleared between calls: every
