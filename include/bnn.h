@@ -115,6 +115,10 @@ typedef enum bnn_option {
                                        waves, the second four taking the second half of K and handing their sums over
                                        through LDS (two waves per SIMD from a grid of one workgroup per CU); 0 = no
                                        (default: measured 12.4 against 9.9 us at 4096 x 2048 x 2048).  Same bits.       */
+    BNN_OPT_COOPERATIVE_SPIN = 15,  /* polls of the other workgroups' flags before a workgroup of a cooperative kernel gives
+                                       up (>= 1; default 2^20, about a second).  A small value makes the bounded wait run
+                                       out on purpose: the kernel still ends, its rows are wrong and
+                                       bnn_cooperative_timeouts counts the workgroups that gave up (for tests of that path) */
     BNN_OPT_COOPERATIVE = 13        /* 1 = kernels whose workgroups wait for each other may be used: a binary-input
                                        LOGSOFTMAX layer on the matrix-core arm then finishes its rows inside the product
                                        kernel (the tiles of a row exchange their maxima and sums of exponentials through

@@ -49,6 +49,7 @@ std::atomic<int> g_realx_f32_mfma{0};
 std::atomic<int> g_mfma32_xcd_order{0};
 std::atomic<int> g_stream_max_frames{64};
 std::atomic<int> g_cooperative{0};
+std::atomic<int> g_coop_spin{1 << 20};
 std::atomic<int> g_mfma32_splitk{0};
 
 std::atomic<unsigned long long> g_coop_launches{0};
@@ -512,7 +513,7 @@ int run_binx(const void* Xp, const void* Wp, const float* scale, const float* bi
                 coop.partials = reinterpret_cast<float2*>(slot + kCoopFlagBytes);
                 coop.stamp = launch;
                 coop.timeouts = reinterpret_cast<unsigned int*>(base);
-                coop.spin_limit = 1 << 20;
+                coop.spin_limit = g_coop_spin.load();
                 act = ACT_LSM_COOP;
             }
         }
@@ -752,6 +753,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_COOPERATIVE:
             if (value != 0 && value != 1) return BNN_EINVAL;
             g_cooperative.store(value);
+            return BNN_OK;
+        case BNN_OPT_COOPERATIVE_SPIN:
+            if (value < 1) return BNN_EINVAL;
+            g_coop_spin.store(value);
             return BNN_OK;
         case BNN_OPT_MFMA32_SPLITK:
             if (value != 0 && value != 1) return BNN_EINVAL;

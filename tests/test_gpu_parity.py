@@ -714,6 +714,32 @@ def test_cooperative_logsoftmax_layer(G, bnn, oracle, M, K, N, x01):
     _close(got, plain, "cooperative against the two-kernel path")
 
 
+def test_cooperative_wait_runs_out_and_the_kernel_still_ends(G, bnn, oracle):
+    """The bounded wait, forced to run out from the host (one poll instead of a million): the kernel ends on its own,
+    the workgroups that gave up are counted, and the next call with the normal limit is right again."""
+    M, K, N = 4096, 2048, 3400
+    aw, bw = _bin_operands(oracle, 99, M, K, N, 32)
+    _, _, scale, bias = _rand_layer(98, 1, 1, N)
+    scale = scale / np.float32(np.sqrt(K))
+    dA, dB, dsc, dbi = (G.to_dev(a) for a in (aw, bw, scale, bias))
+    before = bnn.bnn_cooperative_timeouts()
+    bnn.bnn_set_option(bnn.BNN_OPT_COOPERATIVE, 1)
+    bnn.bnn_set_option(bnn.BNN_OPT_COOPERATIVE_SPIN, 1)
+    try:
+        G.layer_binx(dA, dB, dsc, dbi, K, N, bnn.BNN_ACT_LOGSOFTMAX, 32)
+        torch.cuda.synchronize()                               # returns: every workgroup left its wait
+        gave_up = bnn.bnn_cooperative_timeouts() - before
+        assert gave_up > 0
+        bnn.bnn_set_option(bnn.BNN_OPT_COOPERATIVE_SPIN, 1 << 20)
+        Y = G.layer_binx(dA, dB, dsc, dbi, K, N, bnn.BNN_ACT_LOGSOFTMAX, 32)
+        torch.cuda.synchronize()
+        assert bnn.bnn_cooperative_timeouts() - before == gave_up
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_COOPERATIVE_SPIN, 1 << 20)
+        bnn.bnn_set_option(bnn.BNN_OPT_COOPERATIVE, 0)
+    _close(Y.cpu().numpy(), oracle.layer_binw_binx(aw, bw, K, scale, bias, "logsoftmax", 32, form="xor"), "after a wait that ran out")
+
+
 def test_forward_config3_full_batch_cooperative(G, bnn, oracle):
     """Config 3 at its full size with the cooperative output layer, the configuration the benchmark times: every
     log-posterior of every frame against the oracle."""
