@@ -112,6 +112,11 @@ def test_real_weight_layers_in_a_chain(bnn):
     arr = bnn.make_layer_array(d)
     assert bnn.bnn_forward_workspace_bytes(arr, 3, 4096) == 2 * 4096 * 2048 * 4 + 4096 * 2048 * 4
     d[2]["w_is_real"] = 0
+    # layer 2 reads 2048 real inputs and has Sign units: the third region then holds the scratch of its matrix-core
+    # filter instead, three digit bytes per input and frame plus 16 bytes per frame
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + 3 * 4096 * 2048 + 4096 * 16
+    d[1]["act"] = G                # no Sign layer behind real inputs: two buffers only
+    d[2]["x_is_binary"] = 0
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4
     d[2]["w_is_real"] = 2
     assert _status(bnn.bnn_forward, bnn.make_layer_array(d), 3, P, 8, R, 0x4000000, 1 << 26, 0) == bnn.BNN_EINVAL
