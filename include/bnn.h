@@ -245,9 +245,11 @@ int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, 
 
 /*
  * Bytes of scratch bnn_forward needs for M frames: two ping-pong buffers, each large enough for the
- * largest inter-layer activation (packed bits or fp32), each 256-byte aligned, plus, if a real-weight layer reads
- * the bits of a binary layer, a third buffer for those bits as fp32.  0 for a one-layer network and on invalid
- * arguments.  HOST helper; layers is a HOST array.
+ * largest inter-layer activation (packed bits or fp32), each 256-byte aligned, plus a third region: for the bits of a
+ * binary layer as fp32 if a real-weight layer reads them, or for the matrix-core filter of a binary-weight layer with
+ * real inputs and Sign units (3 bytes per input and frame, 16 bytes per frame; not needed by a first layer of at most
+ * 512 inputs), whichever is larger.  0 on invalid arguments, and for a one-layer network without such a layer.
+ * HOST helper; layers is a HOST array.
  */
 size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M);
 
@@ -262,7 +264,7 @@ size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, i
  *   out       output of the last layer: fp32 [M][N_last] (log-posteriors when its act is LOGSOFTMAX),
  *             or packed bits when its act is SIGN
  *   workspace DEVICE scratch of at least bnn_forward_workspace_bytes() bytes, 256-byte aligned
- *             (may be NULL for a one-layer network)
+ *             (may be NULL when that is 0)
  * A layer with w_is_real = 1 runs as bnn_layer_realw (after bnn_unpack_activations if its input is binary).
  * Enqueues one kernel per layer (two for a LOGSOFTMAX layer or a real-input Sign layer on the slab filter) on `stream`,
  * no host synchronisation.
