@@ -427,7 +427,7 @@ def main() -> int:
     ws_bits = [torch.empty((M, bnn.bnn_packed_words(d["N"], cfg.word_bits)), dtype=torch.int32, device=G.DEV)
                for d in model.descs[:-1]]
     layer_us = []
-    reps = max(20, min(args.steps, 200))
+    reps = 200   # (its own loops of back-to-back launches, whatever --steps is: 20 launches after an idle device read 10 % long)
     # layer 1 exactly as bnn_forward runs it: a one-layer network (real input -> Sign bits)
     first = bnn.make_layer_array(model.descs[:1])
     first_ws_bytes = bnn.bnn_forward_workspace_bytes(first, 1, M)
