@@ -115,6 +115,12 @@ typedef enum bnn_option {
                                        waves, the second four taking the second half of K and handing their sums over
                                        through LDS (two waves per SIMD from a grid of one workgroup per CU); 0 = no
                                        (default: measured 12.4 against 9.9 us at 4096 x 2048 x 2048).  Same bits.       */
+    BNN_OPT_REALX_I8_LOGSOFTMAX = 16, /* bnn_forward, LOGSOFTMAX layer with binary weights and real inputs, 128 frames or more,
+                                       K <= 8192: 1 = the sum of +-x on the int8 matrix cores from four 7-bit digit planes of
+                                       the frames (|sum - exact| < K 2^-27 max|x| per frame: below what the order of an fp32
+                                       summation changes; about 3x faster than the fp32 matrix cores; default, unless
+                                       BNN_OPT_REALX_F32_MFMA = 2 asks for the ascending-k sum everywhere), 0 = as
+                                       BNN_OPT_REALX_F32_MFMA says                                                        */
     BNN_OPT_COOPERATIVE_SPIN = 15,  /* polls of the other workgroups' flags before a workgroup of a cooperative kernel gives
                                        up (>= 1; default 2^20, about a second).  A small value makes the bounded wait run
                                        out on purpose: the kernel still ends, its rows are wrong and

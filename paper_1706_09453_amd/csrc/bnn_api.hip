@@ -48,6 +48,7 @@ std::atomic<int> g_mfma32_pipeline{0};
 std::atomic<int> g_realx_f32_mfma{0};
 std::atomic<int> g_mfma32_xcd_order{0};
 std::atomic<int> g_stream_max_frames{64};
+std::atomic<int> g_realx_i8_lsm{1};
 std::atomic<int> g_cooperative{0};
 std::atomic<int> g_coop_spin{1 << 20};
 std::atomic<int> g_mfma32_splitk{0};
@@ -658,6 +659,46 @@ int run_realx_sign_slab(const float* X, const void* Wp, const float* scale, cons
     return launch_status();
 }
 
+// Output layer with real inputs and binary weights on the int8 matrix cores (four digit planes), inside bnn_forward
+// (the planes live in the workspace): product kernel, then the log-Softmax row kernel.
+bool realx_i8_lsm_applies(const bnn_layer_desc& d, int64_t M) {
+    return !d.x_is_binary && !d.w_is_real && d.act == BNN_ACT_LOGSOFTMAX && d.K <= kSlabMaxK && M >= 128;
+}
+size_t realx_i8_lsm_bytes(int64_t M, int64_t K) {
+    const size_t kpad = (size_t)(K + 63) / 64 * 64;
+    return (kDigits4 * (size_t)M * kpad + 255) / 256 * 256 + ((size_t)M * sizeof(RowMeta4) + 255) / 256 * 256;
+}
+int run_realx_i8_lsm(const float* X, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K, int64_t N,
+                     int wb, float* Y, void* scratch_mem, hipStream_t st) {
+    const int Mi = (int)M, Ki = (int)K, Ni = (int)N;
+    const int w32 = (int)row_w32(K, wb);
+    const int kpad = (Ki + 63) / 64 * 64;
+    int8_t* planes = static_cast<int8_t*>(scratch_mem);
+    RowMeta4* meta = reinterpret_cast<RowMeta4*>(planes + (kDigits4 * (size_t)M * kpad + 255) / 256 * 256);
+    realx_quantize4_kernel<<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, kpad, planes, meta);
+    const size_t lds = slab4_dynamic_lds();
+    const bool vec16 = aligned(Wp, 16) && (w32 % 4 == 0);
+    static std::atomic<int> granted[2] = {{0}, {0}};
+    if (!granted[vec16].load()) {
+        const void* fn = vec16 ? reinterpret_cast<const void*>(realx_i8_linear_kernel<true>)
+                               : reinterpret_cast<const void*>(realx_i8_linear_kernel<false>);
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            return BNN_EDEVICE;
+        }
+        granted[vec16].store(1);
+    }
+    const dim3 grid((Mi + kRealxBM - 1) / kRealxBM, (Ni + kSlabNB - 1) / kSlabNB), block(kSlabThreads);
+    if (vec16)
+        realx_i8_linear_kernel<true><<<grid, block, lds, st>>>(X, planes, meta, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki,
+                                                              kpad, Ni, w32, Y);
+    else
+        realx_i8_linear_kernel<false><<<grid, block, lds, st>>>(X, planes, meta, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki,
+                                                               kpad, Ni, w32, Y);
+    launch_log_softmax(Y, Mi, Ni, st);
+    return launch_status();
+}
+
 int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
     if (!L || n_layers <= 0) return BNN_EINVAL;
     if (M < 0 || M > kMaxDim) return BNN_ESHAPE;
@@ -753,6 +794,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_COOPERATIVE:
             if (value != 0 && value != 1) return BNN_EINVAL;
             g_cooperative.store(value);
+            return BNN_OK;
+        case BNN_OPT_REALX_I8_LOGSOFTMAX:
+            if (value != 0 && value != 1) return BNN_EINVAL;
+            g_realx_i8_lsm.store(value);
             return BNN_OK;
         case BNN_OPT_COOPERATIVE_SPIN:
             if (value < 1) return BNN_EINVAL;
@@ -1003,6 +1048,10 @@ static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_la
             const size_t b = (size_t)M * (size_t)layers[l].K * 4;
             if (b > unpacked) unpacked = b;
         }
+        if (realx_i8_lsm_applies(layers[l], M)) {
+            const size_t b = realx_i8_lsm_bytes(M, layers[l].K);
+            if (b > unpacked) unpacked = b;
+        }
         // digit planes of a real-input Sign layer that the first-layer kernel does not take (same region: one layer at a time)
         if (realx_sign_slab_applies(layers[l]) && !(l == 0 && realx_sign_mfma_applies(layers[l]))) {
             const size_t b = realx_sign_slab_bytes(M, layers[l].K);
@@ -1101,6 +1150,10 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
             } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load() && M > g_stream_max_frames.load()) {
                 rc = run_realx_sign_mfma(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
                                          o, st);
+            } else if (realx_i8_lsm_applies(d, M) && g_realx_i8_lsm.load() && g_realx_f32_mfma.load() != 2 &&
+                       M > g_stream_max_frames.load()) {
+                rc = run_realx_i8_lsm(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
+                                      static_cast<float*>(o), unpacked, st);
             } else if (realx_sign_slab_applies(d) && g_realx_sign_mfma.load() && M > g_stream_max_frames.load()) {
                 rc = run_realx_sign_slab(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits, o,
                                          unpacked, st);

@@ -432,4 +432,225 @@ __global__ __launch_bounds__(kSlabThreads) void realx_sign_slab_kernel(const flo
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Real input x binary weights with fp32 outputs that feed the log-Softmax (the output layer of a network with real
+// hidden activations), on the int8 matrix cores: the same digit-plane product with FOUR 7-bit digits, |xq| <= 2^27.
+// The integer sum a = sum +-xq is exact, and x differs from xq 2^-s by at most half a unit, so
+//     | sum +-x  -  a 2^-s |  <=  K / 2 * 2^-s  <  K 2^-27 max|x|
+// (4e-6 max|x| at K = 2048): below what the order of an fp32 summation changes (the sum in ascending k, the fp32
+// matrix-core kernel and this one agree within a few 1e-6 of the sum's scale), and only used where nothing but the
+// log-Softmax follows.  Frames with NaN, Inf or values too large to quantise take the fp32 sum in ascending k.
+//   realx_quantize4_kernel   one wave per frame -> planes [4][M][kpad] + RowMeta4
+//   realx_i8_linear_kernel   16 frames x 512 outputs per workgroup, K in slabs of 512 through LDS, z = fma(scale, sum, bias)
+constexpr int kDigits4 = 4;
+constexpr int kQuantBits4 = 27;
+struct RowMeta4 {
+    long long R;       // sum_k xq[k]
+    float inv_scale;   // 2^-s
+    int flags;         // 1: the row holds NaN/Inf or values too large to quantise
+};
+__host__ __device__ constexpr size_t slab4_planes_bytes() { return (size_t)2 * kDigits4 * kRealxBM * kSlabPlaneRow; }
+__host__ __device__ constexpr size_t slab4_dynamic_lds() { return slab4_planes_bytes() + slab_weights_bytes(); }
+
+// Grid: ceil(M / 4) workgroups of 256 threads.
+__global__ __launch_bounds__(256) void realx_quantize4_kernel(const float* __restrict__ X, int M, int K, int kpad,
+                                                              int8_t* __restrict__ planes, RowMeta4* __restrict__ meta) {
+    const int m = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+    if (m >= M) return;   // wave-uniform
+    const int lane = lane_id();
+    const float* x = X + (size_t)m * K;
+    unsigned int mx = 0;
+    for (int k0 = 0; k0 < K; k0 += 256) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int k = k0 + 64 * b + lane;
+            if (k < K) mx = max(mx, __float_as_uint(x[k]) & 0x7fffffffu);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = max(mx, (unsigned int)__shfl_xor((int)mx, off, kWave));
+    const int e = (int)(mx >> 23) - 127;
+    const int flags = (mx >= 0x7f800000u || e >= 90) ? 1 : 0;
+    int s = kQuantBits4 - 1 - e;                          // max|x| < 2^(e+1)  =>  |x| 2^s < 2^27
+    s = s > 100 ? 100 : s;
+    const float qs = __uint_as_float((unsigned int)(s + 127) << 23);
+    const size_t plane = (size_t)M * kpad;
+    int8_t* row = planes + (size_t)m * kpad;
+    __shared__ __attribute__((aligned(16))) int8_t qstage[4][kDigits4][256];
+    int8_t (*qs4)[256] = qstage[threadIdx.x >> 6];
+    const int pos = permuted_byte_of_k(lane);
+    long long R = 0;
+    for (int k0 = 0; k0 < kpad; k0 += 256) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int kb = k0 + 64 * b;
+            if (kb < kpad) {   // wave-uniform
+                const int k = kb + lane;
+                const float v = k < K ? x[k] : 0.0f;
+                const int xq = flags ? 0 : (int)__builtin_rintf(v * qs);
+                R += xq;
+                qs4[0][64 * b + pos] = (int8_t)(xq & 127);
+                qs4[1][64 * b + pos] = (int8_t)((xq >> kDigitBits) & 127);
+                qs4[2][64 * b + pos] = (int8_t)((xq >> (2 * kDigitBits)) & 127);
+                qs4[3][64 * b + pos] = (int8_t)(xq >> (3 * kDigitBits));
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        const int kd = k0 + 4 * lane;
+        if (kd < kpad) {
+#pragma unroll
+            for (int d = 0; d < kDigits4; ++d)
+                *reinterpret_cast<int*>(row + d * plane + kd) = *reinterpret_cast<const int*>(&qs4[d][4 * lane]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) R += __shfl_xor(R, off, kWave);
+    if (lane == 0) {
+        RowMeta4 rm;
+        rm.R = R;
+        rm.inv_scale = __uint_as_float((unsigned int)(127 - s) << 23);
+        rm.flags = flags;
+        meta[m] = rm;
+    }
+}
+
+// Grid: x = ceil(M / 16), y = ceil(N / 512); block = 512 threads; dynamic LDS = slab4_dynamic_lds().
+// Z: fp32 [M][N], z = fma(scale, sum, bias) (the log-Softmax row kernel follows).
+template <bool VEC16>
+__global__ __launch_bounds__(kSlabThreads) void realx_i8_linear_kernel(const float* __restrict__ X, const int8_t* __restrict__ planes,
+                                                                      const RowMeta4* __restrict__ meta, const uint32_t* __restrict__ Wp,
+                                                                      const float* __restrict__ scale, const float* __restrict__ bias,
+                                                                      int M, int K, int kpad, int N, int w32, float* __restrict__ Z) {
+    constexpr int WN = 4;
+    extern __shared__ __attribute__((aligned(16))) int8_t lds_raw[];
+    __shared__ RowMeta4 meta_s[kRealxBM];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = lane_id();
+    const int r = lane & 15, g = lane >> 4;
+    const int m_base = (int)blockIdx.x * kRealxBM;
+    const int n_block = (int)blockIdx.y * kSlabNB;
+    const int nb = min(kSlabNB, N - n_block);
+    int8_t* pl = lds_raw;                                                                 // [2][4][16][kSlabPlaneRow]
+    uint32_t* wst = reinterpret_cast<uint32_t*>(lds_raw + slab4_planes_bytes());           // [2][512][kSlabWRow]
+    constexpr int pl_buf = kDigits4 * kRealxBM * kSlabPlaneRow;
+    constexpr int w_buf = kSlabNB * kSlabWRow;
+    if (threadIdx.x < kRealxBM) {
+        const int m = m_base + (int)threadIdx.x;
+        meta_s[threadIdx.x] = meta[m < M ? m : M - 1];
+    }
+    const int nsl = (kpad + kSlabK - 1) / kSlabK;
+    const size_t plane = (size_t)M * kpad;
+
+    uint4 preg[4], wreg[4];
+    auto fetch_slab = [&](int sl) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int p = (int)threadIdx.x + i * kSlabThreads;        // 0 .. 2047
+            const int rowi = p >> 5, c16 = p & 31;                    // (digit, frame) row 0 .. 63, 16-byte column
+            const int d = rowi >> 4, f = rowi & 15;
+            const int m = m_base + f;
+            const int k = sl * kSlabK + c16 * 16;
+            preg[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (k < kpad) preg[i] = *reinterpret_cast<const uint4*>(planes + d * plane + (size_t)(m < M ? m : M - 1) * kpad + k);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int p = (int)threadIdx.x + i * kSlabThreads;
+            const int rowi = p >> 2, q = p & 3;
+            const int wi = sl * 16 + q * 4;
+            const uint32_t* src = Wp + (size_t)(n_block + (rowi < nb ? rowi : nb - 1)) * w32;
+            wreg[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (VEC16 && wi + 3 < w32) {
+                wreg[i] = *reinterpret_cast<const uint4*>(src + wi);
+            } else {
+                if (wi + 0 < w32) wreg[i].x = src[wi + 0];
+                if (wi + 1 < w32) wreg[i].y = src[wi + 1];
+                if (wi + 2 < w32) wreg[i].z = src[wi + 2];
+                if (wi + 3 < w32) wreg[i].w = src[wi + 3];
+            }
+        }
+    };
+    auto store_slab = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int p = (int)threadIdx.x + i * kSlabThreads;
+            const int rowi = p >> 5, c16 = p & 31;
+            *reinterpret_cast<uint4*>(pl + buf * pl_buf + rowi * kSlabPlaneRow + c16 * 16) = preg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int p = (int)threadIdx.x + i * kSlabThreads;
+            const int rowi = p >> 2, q = p & 3;
+            uint32_t* dst = wst + buf * w_buf + rowi * kSlabWRow + q * 4;
+            dst[0] = wreg[i].x; dst[1] = wreg[i].y; dst[2] = wreg[i].z; dst[3] = wreg[i].w;
+        }
+    };
+    fetch_slab(0);
+    store_slab(0);
+    __syncthreads();
+
+    const int nw = wave * (WN * 16);
+    const int sh = 4 * (g & 1);
+    v4i32 acc[kDigits4][WN];
+#pragma unroll
+    for (int d = 0; d < kDigits4; ++d)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) acc[d][j] = v4i32{0, 0, 0, 0};
+    for (int sl = 0; sl < nsl; ++sl) {
+        const int buf = sl & 1;
+        const bool more = sl + 1 < nsl;
+        if (more) fetch_slab(sl + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (nw < nb) {   // wave-uniform
+            const int8_t* al = pl + buf * pl_buf + r * kSlabPlaneRow + 16 * g;
+            const uint32_t* bl = wst + buf * w_buf + (nw + r) * kSlabWRow + (g >> 1);
+            const int steps = min(kSlabK, kpad - sl * kSlabK) >> 6;
+            for (int st = 0; st < steps; ++st) {
+                v4i32 bx[WN];
+#pragma unroll
+                for (int f = 0; f < WN; ++f) {
+                    const uint32_t ws = bl[f * 16 * kSlabWRow + 2 * st] >> sh;
+                    bx[f][0] = (int)(ws & 0x01010101u);
+                    bx[f][1] = (int)((ws >> 1) & 0x01010101u);
+                    bx[f][2] = (int)((ws >> 2) & 0x01010101u);
+                    bx[f][3] = (int)((ws >> 3) & 0x01010101u);
+                }
+#pragma unroll
+                for (int d = 0; d < kDigits4; ++d) {
+                    const v4i32 ax = *reinterpret_cast<const v4i32*>(al + d * kRealxBM * kSlabPlaneRow + st * 64);
+#pragma unroll
+                    for (int fn = 0; fn < WN; ++fn)
+                        acc[d][fn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ax, bx[fn], acc[d][fn], 0, 0, 0);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) store_slab(buf ^ 1);
+        __syncthreads();
+    }
+
+    // accumulator register q of lane (r, g), fragment fn: frame 4 g + q of the tile, output nw + 16 fn + r of the block
+    if (nw < nb) {   // wave-uniform
+#pragma unroll
+        for (int fn = 0; fn < WN; ++fn) {
+            const int nl = nw + fn * 16 + r;
+            const int n = n_block + nl;
+            const float sc1 = (nl < nb && scale) ? scale[n] : 1.0f, bi1 = (nl < nb && bias) ? bias[n] : 0.0f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ml = 4 * g + q, m = m_base + ml;
+                const RowMeta4 rm = meta_s[ml];
+                // P = sum_k b_k xq_k from its four digit sums (each below 2^18), a = 2 P - R: 64-bit integers, then one rounding
+                const long long P = ((((long long)acc[3][fn][q] * 128 + acc[2][fn][q]) * 128 + acc[1][fn][q]) * 128) + acc[0][fn][q];
+                float a = (float)(double)(2 * P - rm.R) * rm.inv_scale;
+                if (m < M && nl < nb) {
+                    if (rm.flags) a = canonical_acc_global(X + (size_t)m * K, Wp + (size_t)n * w32, K);   // rare: NaN, Inf, huge values
+                    Z[(size_t)m * N + n] = affine(sc1, a, bi1);
+                }
+            }
+        }
+    }
+}
+
 }  // namespace bnn

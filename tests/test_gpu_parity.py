@@ -554,6 +554,77 @@ def test_first_layer_mfma_filter_special_rows(G, bnn, oracle, K):
     assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, False), want)
 
 
+def _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, i8):
+    """Real input, binary weights, log-posteriors, through bnn_forward with a one-layer network."""
+    keep = [G.to_dev(Wp), G.to_dev(scale), G.to_dev(bias)]
+    d = [dict(K=K, N=N, act=bnn.BNN_ACT_LOGSOFTMAX, word_bits=wb, x_is_binary=False, Wp=G.ptr(keep[0]),
+              scale=G.ptr(keep[1]), bias=G.ptr(keep[2]))]
+    arr = bnn.make_layer_array(d)
+    M = X.shape[0]
+    nbytes = bnn.bnn_forward_workspace_bytes(arr, 1, M)
+    ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=G.DEV)
+    out = torch.full((M, N), float("nan"), dtype=torch.float32, device=G.DEV)
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_I8_LOGSOFTMAX, 1 if i8 else 0)
+    dX = G.to_dev(X)
+    try:
+        bnn.bnn_forward(arr, 1, G.ptr(dX), M, G.ptr(out), G.ptr(ws), nbytes, G.stream())
+        torch.cuda.synchronize()
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALX_I8_LOGSOFTMAX, 1)
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("kind", ["normal", "sigmoid", "wide"])
+@pytest.mark.parametrize("M,K,N", [(128, 1, 1), (130, 440, 200), (300, 2048, 3400), (257, 1023, 129), (128, 8192, 65),
+                                   (1000, 2048, 2048), (513, 600, 3307)])
+def test_output_layer_real_inputs_int8_digit_planes(G, bnn, oracle, M, K, N, kind, wb):
+    """The output layer of a network with real hidden activations (binary weights, real inputs, log-Softmax) on the
+    int8 matrix cores from four digit planes: log-posteriors against the oracle's, ten times closer than the tolerance
+    asks, and as close to the fp32 matrix-core kernel's."""
+    rng = np.random.default_rng(M * 13 + K * 5 + N + wb)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    if kind == "sigmoid":
+        X = (1.0 / (1.0 + np.exp(-X))).astype(np.float32)
+    if kind == "wide":                                      # 12 orders of magnitude inside a frame, and tiny frames
+        X *= np.exp(rng.uniform(-14, 14, (M, K))).astype(np.float32)
+        X[::7] *= np.float32(1e-30)
+    W = rng.uniform(-1, 1, (N, K)).astype(np.float32)
+    Wp = oracle.pack_sign(W, wb)
+    scale = np.full(N, 1.0 / np.sqrt(K), np.float32) * rng.uniform(0.5, 1.5, N).astype(np.float32)
+    scale[::11] *= -1
+    bias = (rng.standard_normal(N) * 0.5).astype(np.float32)
+    want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "logsoftmax", wb)
+    got = _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, True)
+    ref = _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, False)
+    s = float(np.max(np.abs(want)))
+    assert np.isfinite(got).all()
+    assert float(np.max(np.abs(got.astype(np.float64) - want))) <= 1e-5 * s
+    assert float(np.max(np.abs(got.astype(np.float64) - ref))) <= 1e-5 * s
+    assert np.allclose(np.exp(got.astype(np.float64)).sum(1), 1.0, atol=1e-4)
+
+
+def test_output_layer_int8_digit_planes_special_frames(G, bnn, oracle):
+    """Frames the quantisation cannot take (NaN, Inf, values beyond 2^90) go through the fp32 sum in ascending k: their
+    rows come out as the oracle's (NaN rows stay NaN), the other rows are untouched by them."""
+    M, K, N, wb = 140, 700, 300, 32
+    X, W, scale, bias = _rand_layer(321, M, K, N)
+    scale = scale / np.float32(np.sqrt(K))
+    X[3, 17] = np.inf
+    X[4, 100] = np.nan
+    X[5] *= np.float32(1e30)
+    X[6] = 0.0
+    X[7] *= np.float32(1e-41)
+    Wp = oracle.pack_sign(W, wb)
+    with np.errstate(all="ignore"):
+        want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "logsoftmax", wb)
+    got = _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, True)
+    fin = np.isfinite(want).all(axis=1)
+    assert not fin[3] and not fin[4]
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    _close(got[fin], want[fin], "finite rows")
+
+
 # ----------------------------------------------------------------------------- whole network
 
 def _net_parity(G, bnn, oracle, cfg, M, frames=None, form="xor", arm=None):
