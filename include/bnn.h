@@ -254,7 +254,8 @@ int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, 
  * largest inter-layer activation (packed bits or fp32), each 256-byte aligned, plus a third region: for the bits of a
  * binary layer as fp32 if a real-weight layer reads them, or for the matrix-core filter of a binary-weight layer with
  * real inputs and Sign units (3 bytes per input and frame, 16 bytes per frame; not needed by a first layer of at most
- * 512 inputs), whichever is larger.  0 on invalid arguments, and for a one-layer network without such a layer.
+ * 512 inputs), or for the digit planes of a binary-weight LOGSOFTMAX layer with real inputs (4 bytes per input and
+ * frame, 16 per frame, from 128 frames on), whichever is larger.  0 on invalid arguments, and for a one-layer network without such a layer.
  * HOST helper; layers is a HOST array.
  */
 size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M);

@@ -115,8 +115,10 @@ def test_real_weight_layers_in_a_chain(bnn):
     # layer 2 reads 2048 real inputs and has Sign units: the third region then holds the scratch of its matrix-core
     # filter instead, three digit bytes per input and frame plus 16 bytes per frame
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + 3 * 4096 * 2048 + 4096 * 16
-    d[1]["act"] = G                # no Sign layer behind real inputs: two buffers only
-    d[2]["x_is_binary"] = 0
+    d[1]["act"] = G                # no Sign layer behind real inputs, but a binary-weight output layer that reads real
+    d[2]["x_is_binary"] = 0        # inputs: four digit bytes per input and frame plus 16 bytes per frame
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + 4 * 4096 * 2048 + 4096 * 16
+    d[2]["w_is_real"] = 1          # real weights there: two buffers only
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4
     d[2]["w_is_real"] = 2
     assert _status(bnn.bnn_forward, bnn.make_layer_array(d), 3, P, 8, R, 0x4000000, 1 << 26, 0) == bnn.BNN_EINVAL
@@ -195,7 +197,9 @@ def test_forward_chain_validation_and_workspace(bnn):
     binfirst = _chain(bnn, (2048, 2048, 3400), (S, Z), first_binary=True)
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(binfirst), 2, 4096) == 2 * 4096 * 256
     d2 = _chain(bnn, (440, 2048, 2048, 3400), (H, H, Z))
-    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2), 3, 4096) == 2 * 4096 * 2048 * 4
+    # two buffers of 4096 x 2048 fp32, and the four digit planes (+ 16 bytes per frame) of the output layer's real inputs
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2), 3, 4096) == 2 * 4096 * 2048 * 4 + 4 * 4096 * 2048 + 4096 * 16
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2), 3, 100) == 2 * 100 * 2048 * 4   # fewer than 128 frames: no planes
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d[:1]), 1, 4096) == 0
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2[:1]), 1, 4096) == 0
     # workspace too small / missing
