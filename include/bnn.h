@@ -121,6 +121,15 @@ typedef enum bnn_option {
                                        summation changes; about 3x faster than the fp32 matrix cores; default, unless
                                        BNN_OPT_REALX_F32_MFMA = 2 asks for the ascending-k sum everywhere), 0 = as
                                        BNN_OPT_REALX_F32_MFMA says                                                        */
+    BNN_OPT_REALW_SPLIT_LOGSOFTMAX = 17, /* bnn_forward, LOGSOFTMAX layer with real-valued weights, 128 frames or more:
+                                       1 = the products run on the bf16 matrix cores with every fp32 operand split into
+                                       three bf16 pieces (v = p0 + p1 + p2 to 2^-24 |v|) and the six piece products of
+                                       weight 2^-16 or more added in fp32: |sum - exact| <= 2^-22 sum_k |x_k w_k| plus
+                                       ordinary fp32 rounding, no more than the fp32 matrix cores give, in half their time
+                                       (default, unless BNN_OPT_REALX_F32_MFMA = 2 asks for the ascending-k sum
+                                       everywhere); 2 = the same with workgroups of eight waves, two per SIMD (measured
+                                       2 % slower); 0 = as BNN_OPT_REALX_F32_MFMA says.  The planes of both operands
+                                       (six bytes per element, K padded to 32) are part of bnn_forward_workspace_bytes */
     BNN_OPT_COOPERATIVE_SPIN = 15,  /* polls of the other workgroups' flags before a workgroup of a cooperative kernel gives
                                        up (>= 1; default 2^20, about a second).  A small value makes the bounded wait run
                                        out on purpose: the kernel still ends, its rows are wrong and

@@ -11,6 +11,7 @@
 #include "mfma_i8_kernels.hpp"
 #include "realx_mfma_kernels.hpp"
 #include "realw_kernels.hpp"
+#include "realw_split_kernels.hpp"
 #include "mfma_kernels.hpp"
 #include "pack_kernels.hpp"
 #include "realx_fused_kernel.hpp"
@@ -49,6 +50,7 @@ std::atomic<int> g_realx_f32_mfma{0};
 std::atomic<int> g_mfma32_xcd_order{0};
 std::atomic<int> g_stream_max_frames{64};
 std::atomic<int> g_realx_i8_lsm{1};
+std::atomic<int> g_realw_split_lsm{1};
 std::atomic<int> g_cooperative{0};
 std::atomic<int> g_coop_spin{1 << 20};
 std::atomic<int> g_mfma32_splitk{0};
@@ -699,6 +701,51 @@ int run_realx_i8_lsm(const float* X, const void* Wp, const float* scale, const f
     return launch_status();
 }
 
+// Softmax layer with real weights on the bf16 matrix cores (three bf16 pieces per operand, six piece products), inside
+// bnn_forward (the planes of both operands live in the workspace): two split passes, the product kernel, then the
+// log-Softmax row kernel.  `scratch_mem` is 256-byte aligned.
+bool realw_split_lsm_applies(const bnn_layer_desc& d, int64_t M) {
+    return d.w_is_real && d.act == BNN_ACT_LOGSOFTMAX && M >= 128;
+}
+size_t realw_split_planes_bytes(int64_t rows, int64_t K) {
+    return (kSplitPieces * (size_t)rows * (size_t)split_kpad((int)K) * 2 + 255) / 256 * 256;
+}
+size_t realw_split_lsm_bytes(int64_t M, int64_t K, int64_t N) {
+    return realw_split_planes_bytes(M, K) + realw_split_planes_bytes(N, K);
+}
+void launch_split(const float* A, int64_t rows, int K, int kpad, uint16_t* planes, hipStream_t st) {
+    const int64_t blocks = (rows * (kpad / 8) + 255) / 256;
+    const unsigned grid = (unsigned)(blocks < 16384 ? blocks : 16384);
+    if ((K & 3) == 0 && aligned(A, 16)) split_bf16x3_kernel<true><<<grid, 256, 0, st>>>(A, rows, K, kpad, planes);
+    else split_bf16x3_kernel<false><<<grid, 256, 0, st>>>(A, rows, K, kpad, planes);
+}
+int run_realw_split_lsm(const float* X, const float* W, const float* bias, int64_t M, int64_t K, int64_t N, float* Y,
+                        void* scratch_mem, hipStream_t st) {
+    const int Mi = (int)M, Ki = (int)K, Ni = (int)N;
+    const int kpad = split_kpad(Ki);
+    uint16_t* xs = static_cast<uint16_t*>(scratch_mem);
+    uint16_t* ws = reinterpret_cast<uint16_t*>(static_cast<char*>(scratch_mem) + realw_split_planes_bytes(M, K));
+    launch_split(X, M, Ki, kpad, xs, st);
+    launch_split(W, N, Ki, kpad, ws, st);
+    const unsigned lds = split_dynamic_lds();
+    const int eight = g_realw_split_lsm.load() == 2;   // 4 x 2 waves of 64 x 64 (two per SIMD) instead of 2 x 2 waves of 128 x 64
+    static std::atomic<int> granted[2] = {{0}, {0}};   // more than 64 KB of LDS per workgroup has to be requested explicitly
+    if (!granted[eight].load()) {
+        const void* fn = eight ? reinterpret_cast<const void*>(realw_bf16x3_kernel<ACT_LINEAR, 8>)
+                               : reinterpret_cast<const void*>(realw_bf16x3_kernel<ACT_LINEAR, 4>);
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            return BNN_EDEVICE;
+        }
+        granted[eight].store(1);
+    }
+    const dim3 grid((unsigned)((Mi + kSplitTileM - 1) / kSplitTileM), (unsigned)((Ni + kSplitTileN - 1) / kSplitTileN));
+    if (eight) realw_bf16x3_kernel<ACT_LINEAR, 8><<<grid, 512, lds, st>>>(xs, ws, bias, Mi, kpad, Ni, Y);
+    else realw_bf16x3_kernel<ACT_LINEAR, 4><<<grid, 256, lds, st>>>(xs, ws, bias, Mi, kpad, Ni, Y);
+    launch_log_softmax(Y, Mi, Ni, st);
+    return launch_status();
+}
+
 int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
     if (!L || n_layers <= 0) return BNN_EINVAL;
     if (M < 0 || M > kMaxDim) return BNN_ESHAPE;
@@ -798,6 +845,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_REALX_I8_LOGSOFTMAX:
             if (value != 0 && value != 1) return BNN_EINVAL;
             g_realx_i8_lsm.store(value);
+            return BNN_OK;
+        case BNN_OPT_REALW_SPLIT_LOGSOFTMAX:
+            if (value < 0 || value > 2) return BNN_EINVAL;
+            g_realw_split_lsm.store(value);
             return BNN_OK;
         case BNN_OPT_COOPERATIVE_SPIN:
             if (value < 1) return BNN_EINVAL;
@@ -1037,15 +1088,18 @@ BNN_EXPORT int bnn_semi_stochastic_binarize(float* w, const float* u, int64_t co
 struct ForwardWorkspace {
     size_t half, unpacked;
 };
-static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_layers, int64_t M) {
+// `split`: room for the bf16 planes of a Softmax layer with real weights (without it that layer runs on the fp32 matrix cores)
+static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_layers, int64_t M, bool split = true) {
     size_t biggest = 0, unpacked = 0;
     for (int l = 0; l < n_layers; ++l) {
         if (l + 1 < n_layers) {
             const size_t b = out_bytes(M, layers[l].N, layers[l].act, layers[l].word_bits);
             if (b > biggest) biggest = b;
         }
-        if (layers[l].w_is_real && layers[l].x_is_binary) {
-            const size_t b = (size_t)M * (size_t)layers[l].K * 4;
+        if (layers[l].w_is_real) {
+            // unpacked binary input first, then the bf16 planes of both operands of a Softmax layer with real weights
+            size_t b = layers[l].x_is_binary ? round_up((size_t)M * (size_t)layers[l].K * 4, 256) : 0;
+            if (split && realw_split_lsm_applies(layers[l], M)) b += realw_split_lsm_bytes(M, layers[l].K, layers[l].N);
             if (b > unpacked) unpacked = b;
         }
         if (realx_i8_lsm_applies(layers[l], M)) {
@@ -1095,32 +1149,48 @@ void* static_scratch() {
 }
 }  // namespace
 
+static int forward_run(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out, void* workspace,
+                       size_t workspace_bytes, void* stream, bool split);
+
 BNN_EXPORT int bnn_forward_static(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
                                   void* stream) {
     const int rc = check_chain(layers, n_layers, M);
     if (rc != BNN_OK) return rc;
     if (M == 0) return BNN_OK;
-    const size_t need = bnn_forward_workspace_bytes(layers, n_layers, M);
-    if (need > kStaticScratchBytes) return BNN_EWORKSPACE;
-    void* ws = nullptr;
-    if (need) {
-        ws = static_scratch();
-        if (!ws) return BNN_EDEVICE;
+    // The bf16 planes of a Softmax layer with real weights (six bytes per weight) are left out when they do not fit the
+    // array: that layer then runs on the fp32 matrix cores, as it does in bnn_forward with the option off.
+    bool split = true;
+    ForwardWorkspace ws = forward_workspace(layers, n_layers, M, true);
+    if (2 * ws.half + ws.unpacked > kStaticScratchBytes) {
+        split = false;
+        ws = forward_workspace(layers, n_layers, M, false);
     }
-    return bnn_forward(layers, n_layers, X, M, out, ws, need, stream);
+    const size_t need = 2 * ws.half + ws.unpacked;
+    if (need > kStaticScratchBytes) return BNN_EWORKSPACE;
+    void* mem = nullptr;
+    if (need) {
+        mem = static_scratch();
+        if (!mem) return BNN_EDEVICE;
+    }
+    return forward_run(layers, n_layers, X, M, out, mem, need, stream, split);
 }
 
 BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
                            void* workspace, size_t workspace_bytes, void* stream) {
+    return forward_run(layers, n_layers, X, M, out, workspace, workspace_bytes, stream, true);
+}
+
+static int forward_run(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out, void* workspace,
+                       size_t workspace_bytes, void* stream, bool split) {
     int rc = check_chain(layers, n_layers, M);
     if (rc != BNN_OK) return rc;
     if (M == 0) return BNN_OK;
     if (!X || !out) return BNN_EINVAL;
-    const size_t need = bnn_forward_workspace_bytes(layers, n_layers, M);
+    const ForwardWorkspace ws = forward_workspace(layers, n_layers, M, split);
+    const size_t need = 2 * ws.half + ws.unpacked;
     if (need && (!workspace || workspace_bytes < need)) return BNN_EWORKSPACE;
     if (need && !aligned(workspace, 256)) return BNN_EALIGN;
     // Check every layer's arguments before anything is enqueued.
-    const ForwardWorkspace ws = forward_workspace(layers, n_layers, M);
     char* buf[2] = {static_cast<char*>(workspace), static_cast<char*>(workspace) + ws.half};
     float* unpacked = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * ws.half);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -1138,12 +1208,19 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
                 }
             } else if (d.w_is_real) {
                 const float* xin = static_cast<const float*>(in);
+                char* planes = reinterpret_cast<char*>(unpacked);
                 if (d.x_is_binary) {
                     rc = run_unpack(in, M, d.K, d.word_bits, d.x_is_binary == 2, unpacked, st);
                     if (rc != BNN_OK) return rc;
                     xin = unpacked;
+                    planes += round_up((size_t)M * (size_t)d.K * 4, 256);
                 }
-                rc = run_realw(xin, static_cast<const float*>(d.Wp), d.bias, M, d.K, d.N, d.act, d.word_bits, o, st);
+                if (split && realw_split_lsm_applies(d, M) && g_realw_split_lsm.load() && g_realx_f32_mfma.load() != 2 &&
+                    M > g_stream_max_frames.load())
+                    rc = run_realw_split_lsm(xin, static_cast<const float*>(d.Wp), d.bias, M, d.K, d.N,
+                                             static_cast<float*>(o), planes, st);
+                else
+                    rc = run_realw(xin, static_cast<const float*>(d.Wp), d.bias, M, d.K, d.N, d.act, d.word_bits, o, st);
             } else if (d.x_is_binary) {
                 rc = run_binx(in, d.Wp, d.scale, d.bias, M, d.K, d.N, d.act, d.word_bits, o, BNN_ARM_AUTO, st,
                               d.x_is_binary == 2);

@@ -108,9 +108,12 @@ def test_real_weight_layers_in_a_chain(bnn):
     S, G, Z = bnn.BNN_ACT_SIGN, bnn.BNN_ACT_SIGMOID, bnn.BNN_ACT_LOGSOFTMAX
     d = _chain(bnn, (440, 2048, 2048, 3400), (G, S, Z))
     d[0]["w_is_real"] = 1
-    d[2]["w_is_real"] = 1          # reads the bits of layer 2: needs the third buffer, 4096 x 2048 fp32
-    arr = bnn.make_layer_array(d)
-    assert bnn.bnn_forward_workspace_bytes(arr, 3, 4096) == 2 * 4096 * 2048 * 4 + 4096 * 2048 * 4
+    d[2]["w_is_real"] = 1          # reads the bits of layer 2: the third region holds them as 4096 x 2048 fp32, and
+    arr = bnn.make_layer_array(d)  # behind them three bf16 planes of the frames and of the 3400 weight rows
+    planes = 3 * 2 * 2048 * (4096 + 3400)
+    assert bnn.bnn_forward_workspace_bytes(arr, 3, 4096) == 2 * 4096 * 2048 * 4 + 4096 * 2048 * 4 + planes
+    # fewer than 128 frames: no matrix-core Softmax layer, no planes (the first two regions: 64 x 2048 fp32 each)
+    assert bnn.bnn_forward_workspace_bytes(arr, 3, 64) == 2 * 64 * 2048 * 4 + 64 * 2048 * 4
     d[2]["w_is_real"] = 0
     # layer 2 reads 2048 real inputs and has Sign units: the third region then holds the scratch of its matrix-core
     # filter instead, three digit bytes per input and frame plus 16 bytes per frame
@@ -118,8 +121,11 @@ def test_real_weight_layers_in_a_chain(bnn):
     d[1]["act"] = G                # no Sign layer behind real inputs, but a binary-weight output layer that reads real
     d[2]["x_is_binary"] = 0        # inputs: four digit bytes per input and frame plus 16 bytes per frame
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + 4 * 4096 * 2048 + 4096 * 16
-    d[2]["w_is_real"] = 1          # real weights there: two buffers only
-    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4
+    d[2]["w_is_real"] = 1          # real weights there: the planes of both operands only
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + planes
+    d[2]["K"], d[1]["N"] = 2041, 2041   # K is padded to a multiple of 32 in the planes (2041 -> 2048), rows to 256 bytes
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + planes
+    d[2]["K"], d[1]["N"] = 2048, 2048
     d[2]["w_is_real"] = 2
     assert _status(bnn.bnn_forward, bnn.make_layer_array(d), 3, P, 8, R, 0x4000000, 1 << 26, 0) == bnn.BNN_EINVAL
     d[2]["w_is_real"] = 1

@@ -625,6 +625,100 @@ def test_output_layer_int8_digit_planes_special_frames(G, bnn, oracle):
     _close(got[fin], want[fin], "finite rows")
 
 
+def _one_layer_realw_logsoftmax(G, bnn, X, W, bias, K, N, split, x_bits=None, wb=32):
+    """Real weights, log-posteriors, through bnn_forward with a one-layer network; `x_bits` = packed input instead of X."""
+    keep = [G.to_dev(W), G.to_dev(bias)]
+    d = [dict(K=K, N=N, act=bnn.BNN_ACT_LOGSOFTMAX, word_bits=wb, x_is_binary=x_bits is not None, w_is_real=True,
+              Wp=G.ptr(keep[0]), scale=0, bias=G.ptr(keep[1]))]
+    arr = bnn.make_layer_array(d)
+    dX = G.to_dev(X if x_bits is None else x_bits)
+    M = dX.shape[0]
+    nbytes = bnn.bnn_forward_workspace_bytes(arr, 1, M)
+    ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=G.DEV)
+    out = torch.full((M, N), float("nan"), dtype=torch.float32, device=G.DEV)
+    bnn.bnn_set_option(bnn.BNN_OPT_REALW_SPLIT_LOGSOFTMAX, int(split))
+    try:
+        bnn.bnn_forward(arr, 1, G.ptr(dX), M, G.ptr(out), G.ptr(ws), nbytes, G.stream())
+        torch.cuda.synchronize()
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALW_SPLIT_LOGSOFTMAX, 1)
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("kind", ["normal", "sigmoid", "wide"])
+@pytest.mark.parametrize("M,K,N", [(128, 1, 1), (130, 440, 200), (300, 2048, 3400), (257, 1023, 129), (128, 8191, 65),
+                                   (1000, 2048, 2048), (513, 600, 3307), (256, 32, 128), (640, 96, 384)])
+def test_softmax_layer_real_weights_bf16_pieces(G, bnn, oracle, M, K, N, kind):
+    """The Softmax layer with real weights and real inputs (paper Sec. 3.1, 4.3) on the bf16 matrix cores from three
+    pieces per operand: log-posteriors against the oracle's, ten times closer than the tolerance asks, and as close to
+    the fp32 matrix-core kernel's."""
+    rng = np.random.default_rng(M * 17 + K * 3 + N)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    if kind == "sigmoid":
+        X = (1.0 / (1.0 + np.exp(-X))).astype(np.float32)
+    W = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    if kind == "wide":                                      # 12 orders of magnitude inside a row, on both sides
+        X *= np.exp(rng.uniform(-14, 14, (M, K))).astype(np.float32)
+        W *= np.exp(rng.uniform(-14, 14, (N, K))).astype(np.float32)
+        X[::7] *= np.float32(1e-30)
+    bias = (rng.standard_normal(N) * 0.5).astype(np.float32)
+    want = oracle.layer_realw(X, W, bias, "logsoftmax", 32)
+    ref = _one_layer_realw_logsoftmax(G, bnn, X, W, bias, K, N, 0)
+    s = float(np.max(np.abs(want)))
+    for waves in (1, 2):                                    # workgroups of four waves (default) and of eight
+        got = _one_layer_realw_logsoftmax(G, bnn, X, W, bias, K, N, waves)
+        assert np.isfinite(got).all()
+        assert float(np.max(np.abs(got.astype(np.float64) - want))) <= 1e-5 * s
+        assert float(np.max(np.abs(got.astype(np.float64) - ref))) <= 1e-5 * s
+        assert np.allclose(np.exp(got.astype(np.float64)).sum(1), 1.0, atol=1e-4)
+
+
+def test_softmax_layer_bf16_pieces_sum_within_its_bound(G, bnn, oracle):
+    """The bound the kernel states for its sums, seen through the log-posteriors: out[m][a] - out[m][0] = z_a - z_0, and
+    each z is within 2^-22 sum_k |x_k w_k| (the piece products left out) plus the rounding of about 800 fp32 additions
+    (allowed here: 2^-18 of the row's largest |z|, twice what a random walk of that length gives) of the exact sum."""
+    M, K, N = 256, 2048, 256
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    W = rng.standard_normal((N, K)).astype(np.float32)
+    bias = np.zeros(N, np.float32)
+    got = _one_layer_realw_logsoftmax(G, bnn, X, W, bias, K, N, True).astype(np.float64)
+    _, z = oracle.realw_acc(X, W)
+    mass = np.abs(X.astype(np.float64)) @ np.abs(W.astype(np.float64)).T
+    bound = 2.0 ** -22 * mass + 2.0 ** -18 * np.abs(z).max(1, keepdims=True)
+    assert np.all(np.abs((got - got[:, :1]) - (z - z[:, :1])) <= bound + bound[:, :1])
+
+
+def test_softmax_layer_bf16_pieces_binary_inputs_and_special_values(G, bnn, oracle):
+    """Packed binary inputs are unpacked in front of the split (their pieces are +-1, 0, 0: the products are exact);
+    rows holding NaN or Inf come out NaN like the oracle's, values next to the largest finite float stay finite in the
+    split, tiny rows keep their relative accuracy, and no row disturbs another."""
+    M, K, N = 200, 777, 150
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    W = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    bias = (rng.standard_normal(N) * 0.5).astype(np.float32)
+    xb = oracle.pack_sign(X, 32)
+    want = oracle.layer_realw(oracle.unpack_pm1(xb, K, 32).astype(np.float32), W, bias, "logsoftmax", 32)
+    got = _one_layer_realw_logsoftmax(G, bnn, None, W, bias, K, N, True, x_bits=xb)
+    _close(got, want, "binary inputs")
+    X[3, 17] = np.inf
+    X[4, 100] = np.nan
+    X[5] = 0.0
+    X[6] *= np.float32(1e-41)
+    X[7] *= np.float32(1e-30)
+    X[8, :] = 0.0
+    X[8, 5] = np.float32(3.4028234e38)       # rounds up to infinity as a bf16: must be cut instead
+    W[9, 5] = np.float32(1e-38)
+    with np.errstate(all="ignore"):
+        want = oracle.layer_realw(X, W, bias, "logsoftmax", 32)
+    got = _one_layer_realw_logsoftmax(G, bnn, X, W, bias, K, N, True)
+    fin = np.isfinite(want).all(axis=1)
+    assert not fin[3] and not fin[4]
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    _close(got[fin], want[fin], "finite rows")
+
+
 # ----------------------------------------------------------------------------- whole network
 
 def _net_parity(G, bnn, oracle, cfg, M, frames=None, form="xor", arm=None):
