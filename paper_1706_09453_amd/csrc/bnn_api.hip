@@ -16,6 +16,7 @@
 #include "pack_kernels.hpp"
 #include "realx_fused_kernel.hpp"
 #include "realx_slab_kernels.hpp"
+#include "realx_i8_gemm_kernels.hpp"
 #include "softmax_kernels.hpp"
 #include "train_kernels.hpp"
 #include "valu_kernels.hpp"
@@ -746,6 +747,97 @@ int run_realw_split_lsm(const float* X, const float* W, const float* bias, int64
     return launch_status();
 }
 
+// Real-input layers with binary weights on the int8 matrix cores as a tiled product (128 frames x 256 outputs per
+// workgroup), inside bnn_forward for batches of 128 frames or more: Sign layers (three digit planes, exact bits: the
+// outputs the filter cannot decide are listed and resolved by a second kernel) and the layer in front of the
+// log-Softmax (four digit planes).  Scratch, all 256-byte aligned: digit planes, weight bytes, one record per frame,
+// the list's counter, the list.
+bool realx_i8_gemm_applies(const bnn_layer_desc& d, int64_t M) {
+    return !d.x_is_binary && !d.w_is_real && d.K <= kSlabMaxK && M >= 128 &&
+           (d.act == BNN_ACT_SIGN || d.act == BNN_ACT_LOGSOFTMAX);
+}
+struct I8GemmScratch {
+    size_t planes, bytes, meta, counter, list, total;
+    unsigned int cap;
+};
+I8GemmScratch i8_gemm_scratch(int64_t M, int64_t K, int64_t N, int act) {
+    const size_t kpad = (size_t)i8_kpad((int)K);
+    const int digits = act == BNN_ACT_SIGN ? 3 : 4;
+    I8GemmScratch s{};
+    s.planes = 0;
+    s.bytes = round_up((size_t)digits * (size_t)M * kpad, 256);
+    s.meta = s.bytes + round_up((size_t)N * kpad, 256);
+    s.counter = s.meta + round_up((size_t)M * 16, 256);
+    s.list = s.counter + 256;
+    // room for one output in 64 (the filter leaves about one in 250 undecided at K = 2048); what does not fit is summed
+    // by the lane that finds it
+    size_t cap = act == BNN_ACT_SIGN ? (size_t)M * (size_t)N / 64 : 0;
+    if (act == BNN_ACT_SIGN && cap < 4096) cap = 4096;
+    if (cap > (1u << 24)) cap = 1u << 24;
+    s.cap = (unsigned int)cap;
+    s.total = s.list + round_up(cap * sizeof(ListedOutput), 256);
+    return s;
+}
+template <int D>
+int launch_realx_i8_gemm(const float* X, const void* Wp, const float* scale, const float* bias, int Mi, int Ki, int Ni, int w32,
+                         void* Y, int yw32, char* mem, const I8GemmScratch& sc, hipStream_t st) {
+    const int kpad = i8_kpad(Ki);
+    int8_t* planes = reinterpret_cast<int8_t*>(mem + sc.planes);
+    int8_t* bytes = reinterpret_cast<int8_t*>(mem + sc.bytes);
+    void* meta = mem + sc.meta;
+    unsigned int* counter = reinterpret_cast<unsigned int*>(mem + sc.counter);
+    ListedOutput* list = reinterpret_cast<ListedOutput*>(mem + sc.list);
+    const int qbits = D == 3 ? slab_quant_bits(Ki) : kQuantBits4;
+    if ((Ki & 3) == 0 && aligned(X, 16))
+        realx_quantize_nat_kernel<D, true><<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, kpad, qbits, planes, meta,
+                                                                                     D == 3 ? counter : nullptr);
+    else
+        realx_quantize_nat_kernel<D, false><<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, kpad, qbits, planes, meta,
+                                                                                      D == 3 ? counter : nullptr);
+    const int64_t eb = ((int64_t)Ni * (kpad / 16) + 255) / 256;
+    bits_to_bytes_kernel<<<(unsigned)(eb < 16384 ? eb : 16384), 256, 0, st>>>(static_cast<const uint32_t*>(Wp), Ni, Ki, w32, kpad, bytes);
+    static std::atomic<int> granted{0};   // more than 64 KB of LDS per workgroup has to be requested explicitly
+    if (!granted.load()) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(realx_i8_gemm_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)i8_gemm_lds(D)) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(realx_resolve_list_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)resolve_lds()) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(realx_resolve_list_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)resolve_lds()) != hipSuccess) {
+            (void)hipGetLastError();
+            return BNN_EDEVICE;
+        }
+        granted.store(1);
+    }
+    const dim3 grid((unsigned)((Mi + kI8TileM - 1) / kI8TileM), (unsigned)((Ni + kI8TileN - 1) / kI8TileN));
+    realx_i8_gemm_kernel<D><<<grid, kI8Threads, i8_gemm_lds(D), st>>>(planes, bytes, meta, X, static_cast<const uint32_t*>(Wp), scale, bias,
+                                                                      Mi, Ki, kpad, Ni, w32, Y, yw32, list, sc.cap, counter);
+    if (D == 3) {
+        const unsigned int chunks = (sc.cap + kResolveRows - 1) / kResolveRows;
+        const unsigned int rg = chunks < 2048u ? chunks : 2048u;
+        if ((Ki & 3) == 0 && aligned(X, 16))
+            realx_resolve_list_kernel<true><<<rg, kSlabThreads, resolve_lds(), st>>>(
+                X, static_cast<const uint32_t*>(Wp), scale, bias, Ki, w32, list, counter, sc.cap, static_cast<uint32_t*>(Y), yw32);
+        else
+            realx_resolve_list_kernel<false><<<rg, kSlabThreads, resolve_lds(), st>>>(
+                X, static_cast<const uint32_t*>(Wp), scale, bias, Ki, w32, list, counter, sc.cap, static_cast<uint32_t*>(Y), yw32);
+    }
+    return BNN_OK;
+}
+int run_realx_i8_gemm(const float* X, const void* Wp, const float* scale, const float* bias, int64_t M, int64_t K, int64_t N, int wb,
+                      int act, void* Y, void* scratch_mem, hipStream_t st) {
+    const I8GemmScratch sc = i8_gemm_scratch(M, K, N, act);
+    const int w32 = (int)row_w32(K, wb), yw32 = (int)row_w32(N, wb);
+    int rc;
+    if (act == BNN_ACT_SIGN) {
+        rc = launch_realx_i8_gemm<3>(X, Wp, scale, bias, (int)M, (int)K, (int)N, w32, Y, yw32, static_cast<char*>(scratch_mem), sc, st);
+    } else {
+        rc = launch_realx_i8_gemm<4>(X, Wp, scale, bias, (int)M, (int)K, (int)N, w32, Y, 0, static_cast<char*>(scratch_mem), sc, st);
+        if (rc == BNN_OK) launch_log_softmax(static_cast<float*>(Y), (int)M, (int)N, st);
+    }
+    return rc != BNN_OK ? rc : launch_status();
+}
+
 int check_chain(const bnn_layer_desc* L, int n_layers, int64_t M) {
     if (!L || n_layers <= 0) return BNN_EINVAL;
     if (M < 0 || M > kMaxDim) return BNN_ESHAPE;
@@ -835,7 +927,7 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
             g_fused_softmax.store(value);
             return BNN_OK;
         case BNN_OPT_REALX_SIGN_MFMA:
-            if (value != 0 && value != 1) return BNN_EINVAL;
+            if (value < 0 || value > 2) return BNN_EINVAL;
             g_realx_sign_mfma.store(value);
             return BNN_OK;
         case BNN_OPT_COOPERATIVE:
@@ -843,7 +935,7 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
             g_cooperative.store(value);
             return BNN_OK;
         case BNN_OPT_REALX_I8_LOGSOFTMAX:
-            if (value != 0 && value != 1) return BNN_EINVAL;
+            if (value < 0 || value > 2) return BNN_EINVAL;
             g_realx_i8_lsm.store(value);
             return BNN_OK;
         case BNN_OPT_REALW_SPLIT_LOGSOFTMAX:
@@ -1106,6 +1198,10 @@ static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_la
             const size_t b = realx_i8_lsm_bytes(M, layers[l].K);
             if (b > unpacked) unpacked = b;
         }
+        if (realx_i8_gemm_applies(layers[l], M) && !(l == 0 && realx_sign_mfma_applies(layers[l]))) {
+            const size_t b = i8_gemm_scratch(M, layers[l].K, layers[l].N, layers[l].act).total;
+            if (b > unpacked) unpacked = b;
+        }
         // digit planes of a real-input Sign layer that the first-layer kernel does not take (same region: one layer at a time)
         if (realx_sign_slab_applies(layers[l]) && !(l == 0 && realx_sign_mfma_applies(layers[l]))) {
             const size_t b = realx_sign_slab_bytes(M, layers[l].K);
@@ -1227,6 +1323,11 @@ static int forward_run(const bnn_layer_desc* layers, int n_layers, const void* X
             } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load() && M > g_stream_max_frames.load()) {
                 rc = run_realx_sign_mfma(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
                                          o, st);
+            } else if (realx_i8_gemm_applies(d, M) && M > g_stream_max_frames.load() &&
+                       (d.act == BNN_ACT_SIGN ? g_realx_sign_mfma.load() == 1
+                                              : (g_realx_i8_lsm.load() == 1 && g_realx_f32_mfma.load() != 2))) {
+                rc = run_realx_i8_gemm(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits, d.act, o,
+                                       unpacked, st);
             } else if (realx_i8_lsm_applies(d, M) && g_realx_i8_lsm.load() && g_realx_f32_mfma.load() != 2 &&
                        M > g_stream_max_frames.load()) {
                 rc = run_realx_i8_lsm(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,

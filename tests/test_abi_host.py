@@ -116,11 +116,16 @@ def test_real_weight_layers_in_a_chain(bnn):
     assert bnn.bnn_forward_workspace_bytes(arr, 3, 64) == 2 * 64 * 2048 * 4 + 64 * 2048 * 4
     d[2]["w_is_real"] = 0
     # layer 2 reads 2048 real inputs and has Sign units: the third region then holds the scratch of its matrix-core
-    # filter instead, three digit bytes per input and frame plus 16 bytes per frame
-    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + 3 * 4096 * 2048 + 4096 * 16
+    # filter instead.  128 frames or more (the tiled product): three digit bytes per input and frame, one byte per
+    # weight, 16 bytes per frame, the list's counter (256 bytes) and a list of 8-byte entries for one output in 64
+    pingpong = 2 * 4096 * 2048 * 4
+    sign_scratch = 3 * 4096 * 2048 + 2048 * 2048 + 4096 * 16 + 256 + 8 * (4096 * 2048 // 64)
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == pingpong + sign_scratch
+    # fewer than 128 frames (workgroups of 16 frames): three digit bytes per input and frame plus 16 bytes per frame
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 64) == 2 * 64 * 2048 * 4 + 3 * 64 * 2048 + 64 * 16
     d[1]["act"] = G                # no Sign layer behind real inputs, but a binary-weight output layer that reads real
-    d[2]["x_is_binary"] = 0        # inputs: four digit bytes per input and frame plus 16 bytes per frame
-    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + 4 * 4096 * 2048 + 4096 * 16
+    d[2]["x_is_binary"] = 0        # inputs: four digit bytes per input and frame, one byte per weight, 16 bytes per frame
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == pingpong + 4 * 4096 * 2048 + 3400 * 2048 + 4096 * 16 + 256
     d[2]["w_is_real"] = 1          # real weights there: the planes of both operands only
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + planes
     d[2]["K"], d[1]["N"] = 2041, 2041   # K is padded to a multiple of 32 in the planes (2041 -> 2048), rows to 256 bytes
@@ -203,8 +208,10 @@ def test_forward_chain_validation_and_workspace(bnn):
     binfirst = _chain(bnn, (2048, 2048, 3400), (S, Z), first_binary=True)
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(binfirst), 2, 4096) == 2 * 4096 * 256
     d2 = _chain(bnn, (440, 2048, 2048, 3400), (H, H, Z))
-    # two buffers of 4096 x 2048 fp32, and the four digit planes (+ 16 bytes per frame) of the output layer's real inputs
-    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2), 3, 4096) == 2 * 4096 * 2048 * 4 + 4 * 4096 * 2048 + 4096 * 16
+    # two buffers of 4096 x 2048 fp32, and for the output layer's real inputs four digit planes, one byte per weight,
+    # 16 bytes per frame and 256 bytes for a counter
+    assert (bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2), 3, 4096) ==
+            2 * 4096 * 2048 * 4 + 4 * 4096 * 2048 + 3400 * 2048 + 4096 * 16 + 256)
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2), 3, 100) == 2 * 100 * 2048 * 4   # fewer than 128 frames: no planes
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d[:1]), 1, 4096) == 0
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2[:1]), 1, 4096) == 0

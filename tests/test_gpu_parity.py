@@ -465,7 +465,7 @@ def _first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, use_mfma):
     nbytes = bnn.bnn_forward_workspace_bytes(arr, 1, M)
     ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=G.DEV)
     out = G.word_tensor(M, N, wb)
-    bnn.bnn_set_option(bnn.BNN_OPT_REALX_SIGN_MFMA, 1 if use_mfma else 0)
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_SIGN_MFMA, int(use_mfma))   # 1: tiled product for 128 frames or more, 2: 16-frame workgroups
     dX = G.to_dev(X)
     try:
         bnn.bnn_forward(arr, 1, G.ptr(dX), M, G.ptr(out), G.ptr(ws), nbytes, G.stream())
@@ -480,13 +480,15 @@ def _first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, use_mfma):
                                    (37, 1023, 300), (50, 100, 3307), (257, 129, 129),
                                    # more than 512 inputs: the filter with K streamed in slabs
                                    (130, 513, 65), (300, 2048, 700), (64, 4096, 200), (33, 8192, 40), (17, 600, 1025),
-                                   (1000, 2048, 2048)])
+                                   (1000, 2048, 2048),
+                                   # 128 frames or more: the tiled product (128 x 256 tiles, ragged on both sides)
+                                   (128, 8192, 300), (257, 1000, 513), (129, 577, 31), (640, 2048, 257), (1100, 3000, 96)])
 def test_first_layer_mfma_filter_bit_exact(G, bnn, oracle, M, K, N, wb):
     X, W, scale, bias = _rand_layer(M * 7 + K + N, M, K, N)
     Wp = oracle.pack_sign(W, wb)
     want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "sign", wb)
-    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, True), want)
-    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, False), want)
+    for arm in (1, 2, 0):
+        assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, arm), want), arm
 
 
 def test_first_layer_mfma_filter_all_outputs_near_tie(G, bnn, oracle):
@@ -528,12 +530,16 @@ def test_slab_filter_sigmoid_inputs_and_near_ties(G, bnn, oracle):
     want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "sign", wb)
     frac = np.unpackbits(want.view(np.uint8), bitorder="little").mean()
     assert 0.05 < frac < 0.95
-    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, True), want)
+    # the tiled product lists what it cannot decide in global memory (here far more than the list holds: the rest is
+    # summed by the lane that finds it); the 16-frame kernel keeps its list in LDS
+    for arm in (1, 2):
+        assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, arm), want), arm
 
 
+@pytest.mark.parametrize("M", [70, 200])
 @pytest.mark.parametrize("K", [440, 1100])
-def test_first_layer_mfma_filter_special_rows(G, bnn, oracle, K):
-    M, N, wb = 70, 130, 32
+def test_first_layer_mfma_filter_special_rows(G, bnn, oracle, K, M):
+    N, wb = 130, 32
     X, W, scale, bias = _rand_layer(123, M, K, N)
     X[0] = 0.0
     X[1] *= np.float32(1e-41)          # subnormal row
@@ -550,8 +556,8 @@ def test_first_layer_mfma_filter_special_rows(G, bnn, oracle, K):
     Wp = oracle.pack_sign(W, wb)
     with np.errstate(all="ignore"):
         want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "sign", wb)
-    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, True), want)
-    assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, False), want)
+    for arm in (1, 2, 0):
+        assert np.array_equal(_first_layer_bits(G, bnn, X, Wp, scale, bias, K, N, wb, arm), want), arm
 
 
 def _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, i8):
@@ -564,7 +570,7 @@ def _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, i8):
     nbytes = bnn.bnn_forward_workspace_bytes(arr, 1, M)
     ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=G.DEV)
     out = torch.full((M, N), float("nan"), dtype=torch.float32, device=G.DEV)
-    bnn.bnn_set_option(bnn.BNN_OPT_REALX_I8_LOGSOFTMAX, 1 if i8 else 0)
+    bnn.bnn_set_option(bnn.BNN_OPT_REALX_I8_LOGSOFTMAX, int(i8))   # 1: tiled product, 2: 16-frame workgroups
     dX = G.to_dev(X)
     try:
         bnn.bnn_forward(arr, 1, G.ptr(dX), M, G.ptr(out), G.ptr(ws), nbytes, G.stream())
@@ -595,13 +601,17 @@ def test_output_layer_real_inputs_int8_digit_planes(G, bnn, oracle, M, K, N, kin
     scale[::11] *= -1
     bias = (rng.standard_normal(N) * 0.5).astype(np.float32)
     want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "logsoftmax", wb)
-    got = _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, True)
-    ref = _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, False)
+    ref = _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, 0)
     s = float(np.max(np.abs(want)))
-    assert np.isfinite(got).all()
-    assert float(np.max(np.abs(got.astype(np.float64) - want))) <= 1e-5 * s
-    assert float(np.max(np.abs(got.astype(np.float64) - ref))) <= 1e-5 * s
-    assert np.allclose(np.exp(got.astype(np.float64)).sum(1), 1.0, atol=1e-4)
+    both = []
+    for arm in (1, 2):
+        got = _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, arm)
+        assert np.isfinite(got).all()
+        assert float(np.max(np.abs(got.astype(np.float64) - want))) <= 1e-5 * s
+        assert float(np.max(np.abs(got.astype(np.float64) - ref))) <= 1e-5 * s
+        assert np.allclose(np.exp(got.astype(np.float64)).sum(1), 1.0, atol=1e-4)
+        both.append(got)
+    assert np.array_equal(both[0], both[1])                 # the same exact integer sums, the same roundings after them
 
 
 def test_output_layer_int8_digit_planes_special_frames(G, bnn, oracle):
@@ -618,11 +628,12 @@ def test_output_layer_int8_digit_planes_special_frames(G, bnn, oracle):
     Wp = oracle.pack_sign(W, wb)
     with np.errstate(all="ignore"):
         want = oracle.layer_binw_realx(X, Wp, K, scale, bias, "logsoftmax", wb)
-    got = _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, True)
-    fin = np.isfinite(want).all(axis=1)
-    assert not fin[3] and not fin[4]
-    assert np.array_equal(np.isnan(got), np.isnan(want))
-    _close(got[fin], want[fin], "finite rows")
+    for arm in (1, 2):
+        got = _one_layer_logsoftmax(G, bnn, X, Wp, scale, bias, K, N, wb, arm)
+        fin = np.isfinite(want).all(axis=1)
+        assert not fin[3] and not fin[4]
+        assert np.array_equal(np.isnan(got), np.isnan(want))
+        _close(got[fin], want[fin], "finite rows")
 
 
 def _one_layer_realw_logsoftmax(G, bnn, X, W, bias, K, N, split, x_bits=None, wb=32):
