@@ -86,7 +86,10 @@ typedef enum bnn_option {
                                    binary-activation network; the layer behind a Sigmoid layer in the paper's Table 2
                                    topology): 1 = matrix-core filter with exact sums for the outputs it cannot decide
                                    (default; K <= 8192, scratch from the forward workspace for K > 512 or layers other
-                                   than the first), 0 = vector-ALU kernel; same bits                             */
+                                   than the first: for 128 frames or more a tiled product, 128 frames x 256 outputs per
+                                   workgroup, followed by a kernel that sums the undecided outputs; workgroups of 16
+                                   frames otherwise), 2 = the same with workgroups of 16 frames for every batch size,
+                                   0 = vector-ALU kernel; same bits in all three                                  */
     BNN_OPT_FUSED_LOGSOFTMAX = 6, /* binary-input LOGSOFTMAX layer on the matrix-core arm: 1 = product and
                                    log-Softmax in one kernel (needs K % 256 == 0 and N <= 4096),
                                    0 = product kernel followed by a row kernel (default: measured faster)        */
@@ -119,8 +122,9 @@ typedef enum bnn_option {
                                        K <= 8192: 1 = the sum of +-x on the int8 matrix cores from four 7-bit digit planes of
                                        the frames (|sum - exact| < K 2^-27 max|x| per frame: below what the order of an fp32
                                        summation changes; about 3x faster than the fp32 matrix cores; default, unless
-                                       BNN_OPT_REALX_F32_MFMA = 2 asks for the ascending-k sum everywhere), 0 = as
-                                       BNN_OPT_REALX_F32_MFMA says                                                        */
+                                       BNN_OPT_REALX_F32_MFMA = 2 asks for the ascending-k sum everywhere; a tiled product,
+                                       128 frames x 256 outputs per workgroup), 2 = the same sums with workgroups of 16
+                                       frames x 512 outputs (identical results), 0 = as BNN_OPT_REALX_F32_MFMA says       */
     BNN_OPT_REALW_SPLIT_LOGSOFTMAX = 17, /* bnn_forward, LOGSOFTMAX layer with real-valued weights, 128 frames or more:
                                        1 = the products run on the bf16 matrix cores with every fp32 operand split into
                                        three bf16 pieces (v = p0 + p1 + p2 to 2^-24 |v|) and the six piece products of
