@@ -220,6 +220,25 @@ def train_step(args, bnn, workloads, G, torch) -> int:
                 if l < L - 1:
                     bnn.bnn_pack_activations(P(hhat[l]), M, N, wb, P(bits[l]), st)
 
+        # the two backward products with binary operands, in the oracle's order (fp32, ascending index) or on the int8
+        # matrix cores (bnn_layer_binw_realx_i8: closer to the exact sum, not the same bits)
+        i8_bytes = max(max(bnn.bnn_layer_binw_realx_i8_workspace_bytes(w.shape[0], M, w.shape[1]),
+                           bnn.bnn_layer_binw_realx_i8_workspace_bytes(M, w.shape[0], w.shape[1])) for w in Ws)
+        i8_ws = torch.empty(i8_bytes, dtype=torch.uint8, device=dev)
+        fast = [False]
+
+        def weight_grad_binh(l, N, K):
+            if fast[0]:
+                bnn.bnn_layer_binw_realx_i8(P(gt[l]), P(hbT[l]), 0, 0, N, M, K, wb, P(gw[l]), P(i8_ws), i8_bytes, st)
+            else:
+                bnn.bnn_backward_weight_binh(P(gt[l]), P(hbT[l]), N, K, M, wb, P(gw[l]), st)
+
+        def input_grad_binw(l, N, K):
+            if fast[0]:
+                bnn.bnn_layer_binw_realx_i8(P(gbuf[l]), P(WpT[l]), 0, 0, M, N, K, wb, P(gbuf[l - 1]), P(i8_ws), i8_bytes, st)
+            else:
+                bnn.bnn_backward_input_binw(P(gbuf[l]), P(WpT[l]), M, N, K, wb, P(gbuf[l - 1]), st)
+
         def backward():
             bnn.bnn_softmax_xent_grad(P(hhat[-1]), P(labels), M, cfg.dims[-1], P(gbuf[-1]), st)
             for l in range(L - 1, -1, -1):
@@ -233,10 +252,10 @@ def train_step(args, bnn, workloads, G, torch) -> int:
                     bnn.bnn_backward_weight(P(gt[l]), P(ht[l]), N, K, M, P(gw[l]), st)
                 else:               # the input is Sign(hhat of the layer below): its transposed bits, add/subtract
                     bnn.bnn_pack_weights_transposed(P(hhat[l - 1]), M, K, wb, P(hbT[l]), st)
-                    bnn.bnn_backward_weight_binh(P(gt[l]), P(hbT[l]), N, K, M, wb, P(gw[l]), st)
+                    weight_grad_binh(l, N, K)
                 bnn.bnn_bias_grad(P(g), M, N, P(gr[l]), st)
                 if l > 0:
-                    bnn.bnn_backward_input_binw(P(g), P(WpT[l]), M, N, K, wb, P(gbuf[l - 1]), st)
+                    input_grad_binw(l, N, K)
 
         def update():
             for l in range(L):
@@ -258,13 +277,18 @@ def train_step(args, bnn, workloads, G, torch) -> int:
         reps = 20 if M <= 256 else 5
         ms = {"binarise": timed(binarise, reps), "forward": timed(forward, reps), "backward": timed(backward, reps),
               "update": timed(update, reps)}
+        fast[0] = True
+        backward_i8 = timed(backward, reps)
+        fast[0] = False
         total = sum(ms.values())
         flops = 3 * 2.0 * cfg.macs_per_frame() * M - 2.0 * cfg.dims[0] * cfg.dims[1] * M   # forward + two backward products
         print(json.dumps({"workload": f"training step, {cfg.name.split(' M=')[0]}, minibatch {M}", "batch_frames": M,
                           "ms_per_step": round(total, 3), "frames_per_s": round(M / (total * 1e-3), 1),
                           "phase_ms": {k: round(v, 3) for k, v in ms.items()},
-                          "tflops_products": round(flops / (total * 1e-3) / 1e12, 1)}), flush=True)
-        del X, labels, W, r, Wp, WpT, hhat, bits, hbT, gbuf, gin, gt, ht, gw, gr
+                          "tflops_products": round(flops / (total * 1e-3) / 1e12, 1),
+                          "backward_ms_int8_products": round(backward_i8, 3),
+                          "ms_per_step_int8_products": round(total - ms["backward"] + backward_i8, 3)}), flush=True)
+        del X, labels, W, r, Wp, WpT, hhat, bits, hbT, gbuf, gin, gt, ht, gw, gr, i8_ws
         torch.cuda.empty_cache()
     return 0
 

@@ -72,6 +72,9 @@ _SIGNATURES = {
     "bnn_backward_input_realw": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p]),
     "bnn_backward_weight": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p]),
     "bnn_backward_weight_binh": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_void_p, c_void_p]),
+    "bnn_layer_binw_realx_i8_workspace_bytes": (c_size_t, [c_int64, c_int64, c_int64]),
+    "bnn_layer_binw_realx_i8": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int, c_void_p,
+                                c_void_p, c_size_t, c_void_p]),
     "bnn_bias_grad": (c_int, [c_void_p, c_int64, c_int64, c_void_p, c_void_p]),
     "bnn_update_clip": (c_int, [c_void_p, c_void_p, c_int64, c_float, c_int, c_void_p]),
     "bnn_grad_norm_clip": (c_int, [c_void_p, c_int64, c_float, c_void_p, c_void_p, c_void_p]),
@@ -195,6 +198,16 @@ def bnn_backward_weight(g_hhat_t: int, h_t: int, N: int, K: int, M: int, g_w: in
 
 def bnn_backward_weight_binh(g_hhat_t: int, HpT: int, N: int, K: int, M: int, word_bits: int, g_w: int, stream: int = 0) -> int:
     return _check(_lib.bnn_backward_weight_binh(g_hhat_t, HpT, N, K, M, word_bits, g_w, stream or None))
+
+
+def bnn_layer_binw_realx_i8_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(_lib.bnn_layer_binw_realx_i8_workspace_bytes(M, K, N))
+
+
+def bnn_layer_binw_realx_i8(X: int, Wp: int, scale: int, bias: int, M: int, K: int, N: int, word_bits: int, Y: int,
+                            workspace: int, workspace_bytes: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_layer_binw_realx_i8(X, Wp, scale or None, bias or None, M, K, N, word_bits, Y, workspace or None,
+                                               workspace_bytes, stream or None))
 
 
 def bnn_bias_grad(g_hhat: int, M: int, N: int, g_r: int, stream: int = 0) -> int:

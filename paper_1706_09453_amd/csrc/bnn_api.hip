@@ -1100,6 +1100,30 @@ BNN_EXPORT int bnn_sigmoid_grad(const float* g_h, const float* h, int64_t count,
     return launch_status();
 }
 
+BNN_EXPORT size_t bnn_layer_binw_realx_i8_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    if (M <= 0 || K <= 0 || N <= 0 || M > kMaxDim || K > kSlabMaxK || N > kMaxN) return 0;
+    return i8_gemm_scratch(M, K, N, BNN_ACT_LINEAR).total;
+}
+
+BNN_EXPORT int bnn_layer_binw_realx_i8(const float* X, const void* Wp, const float* scale, const float* bias, int64_t M,
+                                       int64_t K, int64_t N, int word_bits, float* Y, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
+    const int rc = check_layer_args(X, Wp, M, K, N, BNN_ACT_LINEAR, word_bits, Y, false);
+    if (rc != BNN_OK) return rc;
+    if (K > kSlabMaxK) return BNN_ESHAPE;
+    if (M == 0) return BNN_OK;
+    const I8GemmScratch sc = i8_gemm_scratch(M, K, N, BNN_ACT_LINEAR);
+    if (!workspace || workspace_bytes < sc.total) return BNN_EWORKSPACE;
+    if (!aligned(workspace, 256)) return BNN_EALIGN;
+    const size_t yb = (size_t)M * N * 4;
+    if (overlap(workspace, sc.total, Y, yb) || overlap(workspace, sc.total, X, (size_t)M * K * 4) ||
+        overlap(workspace, sc.total, Wp, (size_t)N * row_w32(K, word_bits) * 4))
+        return BNN_EINVAL;
+    const int lrc = launch_realx_i8_gemm<4>(X, Wp, scale, bias, (int)M, (int)K, (int)N, (int)row_w32(K, word_bits), Y, 0,
+                                            static_cast<char*>(workspace), sc, static_cast<hipStream_t>(stream));
+    return lrc != BNN_OK ? lrc : launch_status();
+}
+
 BNN_EXPORT int bnn_backward_input_binw(const float* g_hhat, const void* WpT, int64_t M, int64_t N, int64_t K, int word_bits,
                                        float* g_h, void* stream) {
     // the forward layer with the roles exchanged: "inputs" are the N gradients of a frame, "outputs" the K inputs

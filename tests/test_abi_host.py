@@ -139,6 +139,27 @@ def test_real_weight_layers_in_a_chain(bnn):
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 0
 
 
+def test_int8_layer_argument_validation(bnn):
+    fn, size = bnn.bnn_layer_binw_realx_i8, bnn.bnn_layer_binw_realx_i8_workspace_bytes
+    # four digit bytes per input and frame, one byte per weight (K padded to 64), 16 bytes per frame, 256 for a counter
+    assert size(4096, 2048, 3400) == 4 * 4096 * 2048 + 3400 * 2048 + 4096 * 16 + 256
+    assert size(3, 5, 7) == 4 * 3 * 64 + (7 * 64 + 255) // 256 * 256 + 256 + 256
+    assert size(4, 8193, 7) == 0 and size(0, 8, 8) == 0 and size(4, 0, 8) == 0
+    W = 0x40000000
+    need = size(4, 64, 64)
+    assert _status(fn, 0, Q, 0, 0, 4, 64, 64, 32, R, W, need, 0) == bnn.BNN_EINVAL        # null X
+    assert _status(fn, P, Q, 0, 0, 4, 64, 64, 32, 0, W, need, 0) == bnn.BNN_EINVAL        # null Y
+    assert _status(fn, P, Q, 0, 0, 4, 8193, 64, 32, R, W, 1 << 30, 0) == bnn.BNN_ESHAPE   # K beyond 8192
+    assert _status(fn, P, Q, 0, 0, 4, 64, 64, 48, R, W, need, 0) == bnn.BNN_ESHAPE        # word_bits
+    assert _status(fn, P, Q, 0, 0, 4, 64, 64, 32, R, 0, need, 0) == bnn.BNN_EWORKSPACE    # no workspace
+    assert _status(fn, P, Q, 0, 0, 4, 64, 64, 32, R, W, need - 1, 0) == bnn.BNN_EWORKSPACE
+    assert _status(fn, P, Q, 0, 0, 4, 64, 64, 32, R, W + 128, need, 0) == bnn.BNN_EALIGN  # workspace at 128 mod 256
+    assert _status(fn, P, Q, 0, 0, 4, 64, 64, 32, R + 2, W, need, 0) == bnn.BNN_EALIGN    # fp32 out at 2 mod 4
+    assert _status(fn, P, Q, 0, 0, 4, 64, 64, 32, W + 256, W, need, 0) == bnn.BNN_EINVAL  # Y inside the workspace
+    assert _status(fn, W, Q, 0, 0, 4, 64, 64, 32, R, W, need, 0) == bnn.BNN_EINVAL        # X inside the workspace
+    assert fn(0, 0, 0, 0, 0, 64, 64, 32, 0, 0, 0, 0) == 0                                  # M = 0: nothing to do
+
+
 def test_training_argument_validation(bnn):
     E, S, A = bnn.BNN_EINVAL, bnn.BNN_ESHAPE, bnn.BNN_EALIGN
     assert _status(bnn.bnn_pack_weights_transposed, 0, 4, 64, 32, Q, 0) == E

@@ -162,6 +162,98 @@ def test_weight_gradient_of_sign_units_by_add_and_subtract(G, bnn, oracle, T, M,
     assert np.array_equal(gw.cpu().numpy(), want)
 
 
+def _realx_i8(G, bnn, dX, dWp, M, K, N, wb, scale=None, bias=None):
+    """bnn_layer_binw_realx_i8 with a fresh workspace; returns the fp32 outputs."""
+    nbytes = bnn.bnn_layer_binw_realx_i8_workspace_bytes(M, K, N)
+    assert nbytes > 0
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    out = _f32(M, N)
+    bnn.bnn_layer_binw_realx_i8(G.ptr(dX), G.ptr(dWp), 0 if scale is None else G.ptr(scale), 0 if bias is None else G.ptr(bias),
+                                M, K, N, wb, G.ptr(out), G.ptr(ws), nbytes, G.stream())
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("wb", [32, 64])
+@pytest.mark.parametrize("M,K,N", [(1, 1, 1), (3, 5, 7), (130, 440, 200), (128, 64, 256), (300, 2048, 700), (257, 1023, 129),
+                                   (129, 8192, 65), (1000, 4096, 300), (2048, 256, 2048)])
+def test_layer_binw_realx_on_the_int8_matrix_cores(G, bnn, oracle, M, K, N, wb):
+    """The sign-selected sum from four digit planes: within K 2^-27 max|x| (or K 2^-101 for tiny frames) of the exact sum
+    for every frame (the bound the header states; the fp64 sum of the oracle stands for the exact one), scale and bias
+    applied by one fma."""
+    rng = np.random.default_rng(M * 3 + K + N + wb)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    X[::5] *= np.exp(rng.uniform(-12, 12, (len(X[::5]), K))).astype(np.float32)      # wide range inside some frames
+    X[1::7] *= np.float32(1e-30)
+    W = rng.uniform(-1, 1, (N, K)).astype(np.float32)
+    Wp = oracle.pack_sign(W, wb)
+    scale = (rng.uniform(0.5, 1.5, N) * np.where(rng.random(N) < 0.2, -1, 1)).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    _, acc64 = oracle.realx_acc(X, oracle.unpack_pm1(Wp, K, wb))
+    got = _realx_i8(G, bnn, G.to_dev(X), G.to_dev(Wp), M, K, N, wb)
+    # (frames whose largest element is below 2^-74 are rounded to multiples of 2^-100)
+    bound = K * np.maximum(2.0 ** -27 * np.abs(X).max(1, keepdims=True).astype(np.float64), 2.0 ** -101)
+    assert np.all(np.abs(got.astype(np.float64) - acc64) <= bound + 2.0 ** -23 * np.abs(acc64))   # + the final rounding to fp32
+    got = _realx_i8(G, bnn, G.to_dev(X), G.to_dev(Wp), M, K, N, wb, G.to_dev(scale), G.to_dev(bias))
+    want = oracle.affine_f64(acc64, scale, bias)
+    tol = np.abs(scale.astype(np.float64)) * bound + 2.0 ** -22 * (np.abs(want) + np.abs(bias))
+    assert np.all(np.abs(got.astype(np.float64) - want) <= tol)
+
+
+def test_layer_binw_realx_int8_rows_that_cannot_be_quantised(G, bnn, oracle):
+    """Frames with NaN, Inf or values beyond 2^90 take the fp32 sum in ascending k: the bits of bnn_layer_binw_realx."""
+    M, K, N, wb = 140, 700, 300, 32
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    X[3, 17] = np.inf
+    X[4, 100] = np.nan
+    X[5] *= np.float32(1e30)
+    X[6] = 0.0
+    W = rng.uniform(-1, 1, (N, K)).astype(np.float32)
+    Wp = oracle.pack_sign(W, wb)
+    dX, dWp = G.to_dev(X), G.to_dev(Wp)
+    got = _realx_i8(G, bnn, dX, dWp, M, K, N, wb)
+    with np.errstate(all="ignore"):
+        acc32, acc64 = oracle.realx_acc(X, oracle.unpack_pm1(Wp, K, wb))
+    for m in (3, 4, 5):
+        assert np.array_equal(got[m].view(np.uint32), acc32[m].view(np.uint32)), m
+    assert np.all(got[6] == 0.0)
+    rest = np.ones(M, bool); rest[[3, 4, 5]] = False
+    bound = K * 2.0 ** -27 * np.abs(X[rest]).max(1, keepdims=True).astype(np.float64)
+    assert np.all(np.abs(got[rest].astype(np.float64) - acc64[rest]) <= bound + 2.0 ** -23 * np.abs(acc64[rest]))
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 300, 200), (1024, 512, 2048), (4096, 130, 257)])
+def test_backward_products_on_the_int8_matrix_cores(G, bnn, oracle, T, M, N, K):
+    """Both backward products of Alg. 1 through bnn_layer_binw_realx_i8 (g_h = g_hhat w^b with the transposed signs,
+    g_w = g_hhat^T h with the bits of h^T): within M or N times 2^-27 of the largest gradient of the row of the oracle's
+    product (whose own fp32 chain is further from the exact sum than that)."""
+    rng = np.random.default_rng(M + N + K)
+    g = (rng.standard_normal((M, N)) * np.exp(rng.uniform(-6, 0, (M, 1)))).astype(np.float32)   # frames of very different weight
+    W = rng.uniform(-1, 1, (N, K)).astype(np.float32)
+    hhat_prev = rng.standard_normal((M, K)).astype(np.float32)
+    dg, dW, dhh = G.to_dev(g), G.to_dev(W), G.to_dev(hhat_prev)
+    WpT, HpT, gt = G.word_tensor(K, N, 32), G.word_tensor(K, M, 32), _f32(N, M)
+    bnn.bnn_pack_weights_transposed(G.ptr(dW), N, K, 32, G.ptr(WpT), G.stream())
+    bnn.bnn_pack_weights_transposed(G.ptr(dhh), M, K, 32, G.ptr(HpT), G.stream())
+    bnn.bnn_transpose_f32(G.ptr(dg), M, N, G.ptr(gt), G.stream())
+    gh = _realx_i8(G, bnn, dg, WpT, M, N, K, 32)              # rows: frames, summed over the N outputs
+    gw = _realx_i8(G, bnn, gt, HpT, N, M, K, 32)              # rows: outputs, summed over the M frames
+    want_h = T.backward_input_binw(g, np.where(W > 0, 1, -1).astype(np.int8)).astype(np.float64)
+    want_w = T.backward_weight(g, np.where(hhat_prev > 0, 1.0, -1.0).astype(np.float32)).astype(np.float64)
+    u = 2.0 ** -24
+    tol_h = (N * 2.0 ** -27 + N * u) * np.abs(g).max(1, keepdims=True) * 1.0 + N * u * np.abs(g).sum(1, keepdims=True)
+    tol_w = (M * 2.0 ** -27) * np.abs(g).max(0)[:, None] + M * u * np.abs(g).sum(0)[:, None]
+    assert np.all(np.abs(gh - want_h) <= tol_h)
+    assert np.all(np.abs(gw - want_w) <= tol_w)
+    # against the exact products (fp64; the oracle's fp32 chains are further from them than the matrix-core sums): the
+    # bound the header states plus the one rounding to fp32
+    g64, s_w, s_h = g.astype(np.float64), np.where(W > 0, 1.0, -1.0), np.where(hhat_prev > 0, 1.0, -1.0)
+    exact_h, exact_w = g64 @ s_w, g64.T @ s_h
+    assert np.all(np.abs(gh - exact_h) <= N * 2.0 ** -27 * np.abs(g64).max(1, keepdims=True) + 2.0 ** -23 * np.abs(exact_h))
+    assert np.all(np.abs(gw - exact_w) <= M * 2.0 ** -27 * np.abs(g64).max(0)[:, None] + 2.0 ** -23 * np.abs(exact_w))
+
+
 @pytest.mark.parametrize("clip", [0, 1])
 def test_update_clip(G, bnn, T, clip):
     rng = np.random.default_rng(5)
