@@ -300,7 +300,10 @@ int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64
  *   - BNN_EWORKSPACE if bnn_forward_workspace_bytes(layers, n_layers, M) exceeds BNN_FORWARD_STATIC_MAX_BYTES
  *     (16 MiB: Config-3-sized networks up to 32768 frames, 4096-unit ones up to 16384; a network with a real-input
  *     Sign layer that is not its first layer, or has more than 512 inputs, also keeps 3 bytes per input and frame of
- *     that layer there: 2048 inputs fit up to about 2600 frames);
+ *     that layer there: 2048 inputs fit up to about 2600 frames).  The extra scratch of the tiled matrix-core products
+ *     (a byte per weight of a real-input layer with binary weights, six bytes per weight of a Softmax layer with real
+ *     weights) is left out when it does not fit: those layers then run on the kernels with 16-frame workgroups and on
+ *     the fp32 matrix cores, with the results those give in bnn_forward (same bits for Sign layers);
  *   - BNN_EDEVICE if the array's address cannot be obtained on the current device.
  * Every call on a GPU shares that GPU's one array: calls that overlap in time on one GPU (different streams or threads)
  * race on it; calls on one stream are ordered and safe.  Nothing in the array has to be cleared between calls: every

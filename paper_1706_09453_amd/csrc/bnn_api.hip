@@ -1204,8 +1204,9 @@ BNN_EXPORT int bnn_semi_stochastic_binarize(float* w, const float* u, int64_t co
 struct ForwardWorkspace {
     size_t half, unpacked;
 };
-// `split`: room for the bf16 planes of a Softmax layer with real weights (without it that layer runs on the fp32 matrix cores)
-static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_layers, int64_t M, bool split = true) {
+// `roomy`: with the scratch of the tiled matrix-core products (the weight bytes and the list of realx_i8_gemm, the bf16
+// planes of a Softmax layer with real weights); without it those layers run on the kernels that need less or none
+static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_layers, int64_t M, bool roomy = true) {
     size_t biggest = 0, unpacked = 0;
     for (int l = 0; l < n_layers; ++l) {
         if (l + 1 < n_layers) {
@@ -1215,14 +1216,14 @@ static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_la
         if (layers[l].w_is_real) {
             // unpacked binary input first, then the bf16 planes of both operands of a Softmax layer with real weights
             size_t b = layers[l].x_is_binary ? round_up((size_t)M * (size_t)layers[l].K * 4, 256) : 0;
-            if (split && realw_split_lsm_applies(layers[l], M)) b += realw_split_lsm_bytes(M, layers[l].K, layers[l].N);
+            if (roomy && realw_split_lsm_applies(layers[l], M)) b += realw_split_lsm_bytes(M, layers[l].K, layers[l].N);
             if (b > unpacked) unpacked = b;
         }
         if (realx_i8_lsm_applies(layers[l], M)) {
             const size_t b = realx_i8_lsm_bytes(M, layers[l].K);
             if (b > unpacked) unpacked = b;
         }
-        if (realx_i8_gemm_applies(layers[l], M) && !(l == 0 && realx_sign_mfma_applies(layers[l]))) {
+        if (roomy && realx_i8_gemm_applies(layers[l], M) && !(l == 0 && realx_sign_mfma_applies(layers[l]))) {
             const size_t b = i8_gemm_scratch(M, layers[l].K, layers[l].N, layers[l].act).total;
             if (b > unpacked) unpacked = b;
         }
@@ -1270,19 +1271,20 @@ void* static_scratch() {
 }  // namespace
 
 static int forward_run(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out, void* workspace,
-                       size_t workspace_bytes, void* stream, bool split);
+                       size_t workspace_bytes, void* stream, bool roomy);
 
 BNN_EXPORT int bnn_forward_static(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
                                   void* stream) {
     const int rc = check_chain(layers, n_layers, M);
     if (rc != BNN_OK) return rc;
     if (M == 0) return BNN_OK;
-    // The bf16 planes of a Softmax layer with real weights (six bytes per weight) are left out when they do not fit the
-    // array: that layer then runs on the fp32 matrix cores, as it does in bnn_forward with the option off.
-    bool split = true;
+    // The scratch of the tiled matrix-core products (a byte per weight of a real-input layer, six bytes per weight of a
+    // Softmax layer with real weights) is left out when it does not fit the array: those layers then run on the kernels
+    // bnn_forward uses with these products switched off.
+    bool roomy = true;
     ForwardWorkspace ws = forward_workspace(layers, n_layers, M, true);
     if (2 * ws.half + ws.unpacked > kStaticScratchBytes) {
-        split = false;
+        roomy = false;
         ws = forward_workspace(layers, n_layers, M, false);
     }
     const size_t need = 2 * ws.half + ws.unpacked;
@@ -1292,7 +1294,7 @@ BNN_EXPORT int bnn_forward_static(const bnn_layer_desc* layers, int n_layers, co
         mem = static_scratch();
         if (!mem) return BNN_EDEVICE;
     }
-    return forward_run(layers, n_layers, X, M, out, mem, need, stream, split);
+    return forward_run(layers, n_layers, X, M, out, mem, need, stream, roomy);
 }
 
 BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out,
@@ -1301,12 +1303,12 @@ BNN_EXPORT int bnn_forward(const bnn_layer_desc* layers, int n_layers, const voi
 }
 
 static int forward_run(const bnn_layer_desc* layers, int n_layers, const void* X, int64_t M, void* out, void* workspace,
-                       size_t workspace_bytes, void* stream, bool split) {
+                       size_t workspace_bytes, void* stream, bool roomy) {
     int rc = check_chain(layers, n_layers, M);
     if (rc != BNN_OK) return rc;
     if (M == 0) return BNN_OK;
     if (!X || !out) return BNN_EINVAL;
-    const ForwardWorkspace ws = forward_workspace(layers, n_layers, M, split);
+    const ForwardWorkspace ws = forward_workspace(layers, n_layers, M, roomy);
     const size_t need = 2 * ws.half + ws.unpacked;
     if (need && (!workspace || workspace_bytes < need)) return BNN_EWORKSPACE;
     if (need && !aligned(workspace, 256)) return BNN_EALIGN;
@@ -1335,7 +1337,7 @@ static int forward_run(const bnn_layer_desc* layers, int n_layers, const void* X
                     xin = unpacked;
                     planes += round_up((size_t)M * (size_t)d.K * 4, 256);
                 }
-                if (split && realw_split_lsm_applies(d, M) && g_realw_split_lsm.load() && g_realx_f32_mfma.load() != 2 &&
+                if (roomy && realw_split_lsm_applies(d, M) && g_realw_split_lsm.load() && g_realx_f32_mfma.load() != 2 &&
                     M > g_stream_max_frames.load())
                     rc = run_realw_split_lsm(xin, static_cast<const float*>(d.Wp), d.bias, M, d.K, d.N,
                                              static_cast<float*>(o), planes, st);
@@ -1347,7 +1349,7 @@ static int forward_run(const bnn_layer_desc* layers, int n_layers, const void* X
             } else if (l == 0 && realx_sign_mfma_applies(d) && g_realx_sign_mfma.load() && M > g_stream_max_frames.load()) {
                 rc = run_realx_sign_mfma(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits,
                                          o, st);
-            } else if (realx_i8_gemm_applies(d, M) && M > g_stream_max_frames.load() &&
+            } else if (roomy && realx_i8_gemm_applies(d, M) && M > g_stream_max_frames.load() &&
                        (d.act == BNN_ACT_SIGN ? g_realx_sign_mfma.load() == 1
                                               : (g_realx_i8_lsm.load() == 1 && g_realx_f32_mfma.load() != 2))) {
                 rc = run_realx_i8_gemm(static_cast<const float*>(in), d.Wp, d.scale, d.bias, M, d.K, d.N, d.word_bits, d.act, o,
