@@ -634,6 +634,36 @@ __global__ __launch_bounds__(SPLITK ? 512 : 256, SPLITK ? 1 : 2) void binx_mfma3
                     st[(8 * (v >> 2) + 4 * g + (v & 3)) * LDW + fn * 32 + r] = bits;
                 }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // this wave's LDS writes are done before it reads them back
+            if constexpr (ACT == ACT_DOT_I16) {
+                // int16 outputs: 8 lanes write the 128 bytes a row has in this wave tile (eight int16 = 16 bytes per lane),
+                // so a store instruction covers 8 rows and the tile takes half as many of them as with 8 bytes per lane
+                // (the stores, not their bytes, are what this epilogue costs).  The caller guarantees N % 4 == 0 and a
+                // 16-byte aligned Y.
+                const int c8 = (lane & 7) * 8;
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int row = it * 8 + (lane >> 3);
+                    const int m = m_base + fm * 32 + row;
+                    const int n = n_base + c8;
+                    const uint4 q0 = *reinterpret_cast<const uint4*>(st + row * LDW + c8);
+                    const uint4 q1 = *reinterpret_cast<const uint4*>(st + row * LDW + c8 + 4);
+                    uint4 h;
+                    h.x = (q0.x & 0xFFFFu) | (q0.y << 16);
+                    h.y = (q0.z & 0xFFFFu) | (q0.w << 16);
+                    h.z = (q1.x & 0xFFFFu) | (q1.y << 16);
+                    h.w = (q1.z & 0xFFFFu) | (q1.w << 16);
+                    if (m < M) {
+                        uint16_t* y = reinterpret_cast<uint16_t*>(Y) + (size_t)m * 2 * N + n;
+                        if (n + 7 < N) {
+                            *reinterpret_cast<uint4*>(y) = h;
+                        } else if (n < N) {   // N % 8 == 4: the last four outputs of the row
+                            *reinterpret_cast<uint2*>(y) = make_uint2(h.x, h.y);
+                        }
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // reads done before the next fragment row overwrites the slice
+                continue;
+            }
 #pragma unroll
             for (int it = 0; it < 8; ++it) {
                 const int row = it * 4 + (lane >> 4);
@@ -641,24 +671,14 @@ __global__ __launch_bounds__(SPLITK ? 512 : 256, SPLITK ? 1 : 2) void binx_mfma3
                 const int n = n_base + c4;
                 const uint4 q = *reinterpret_cast<const uint4*>(st + row * LDW + c4);
                 if (m < M) {
-                    if constexpr (ACT == ACT_DOT_I16) {
-                        // caller guarantees N % 4 == 0 and a 16-byte aligned Y: four int16 = one 8-byte store
-                        if (n < N) {
-                            uint2 h;
-                            h.x = (q.x & 0xFFFFu) | (q.y << 16);
-                            h.y = (q.z & 0xFFFFu) | (q.w << 16);
-                            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(Y) + (size_t)m * 2 * N + n) = h;
-                        }
+                    uint32_t* y = (uint32_t*)Y + (size_t)m * N + n;
+                    if (rows_vec && n + 3 < N) {
+                        *reinterpret_cast<uint4*>(y) = q;
                     } else {
-                        uint32_t* y = (uint32_t*)Y + (size_t)m * N + n;
-                        if (rows_vec && n + 3 < N) {
-                            *reinterpret_cast<uint4*>(y) = q;
-                        } else {
-                            if (n + 0 < N) y[0] = q.x;
-                            if (n + 1 < N) y[1] = q.y;
-                            if (n + 2 < N) y[2] = q.z;
-                            if (n + 3 < N) y[3] = q.w;
-                        }
+                        if (n + 0 < N) y[0] = q.x;
+                        if (n + 1 < N) y[1] = q.y;
+                        if (n + 2 < N) y[2] = q.z;
+                        if (n + 3 < N) y[3] = q.w;
                     }
                 }
             }
