@@ -757,8 +757,7 @@ bool realx_i8_gemm_applies(const bnn_layer_desc& d, int64_t M) {
            (d.act == BNN_ACT_SIGN || d.act == BNN_ACT_LOGSOFTMAX);
 }
 struct I8GemmScratch {
-    size_t planes, bytes, meta, counter, list, total;
-    unsigned int cap;
+    size_t planes, bytes, meta, undecided, total;
 };
 I8GemmScratch i8_gemm_scratch(int64_t M, int64_t K, int64_t N, int act) {
     const size_t kpad = (size_t)i8_kpad((int)K);
@@ -767,15 +766,11 @@ I8GemmScratch i8_gemm_scratch(int64_t M, int64_t K, int64_t N, int act) {
     s.planes = 0;
     s.bytes = round_up((size_t)digits * (size_t)M * kpad, 256);
     s.meta = s.bytes + round_up((size_t)N * kpad, 256);
-    s.counter = s.meta + round_up((size_t)M * 16, 256);
-    s.list = s.counter + 256;
-    // room for one output in 64 (the filter leaves about one in 250 undecided at K = 2048); what does not fit is summed
-    // by the lane that finds it
-    size_t cap = act == BNN_ACT_SIGN ? (size_t)M * (size_t)N / 64 : 0;
-    if (act == BNN_ACT_SIGN && cap < 4096) cap = 4096;
-    if (cap > (1u << 24)) cap = 1u << 24;
-    s.cap = (unsigned int)cap;
-    s.total = s.list + round_up(cap * sizeof(ListedOutput), 256);
+    s.undecided = s.meta + round_up((size_t)M * 16, 256);
+    // Sign layers: a record per frame and tile of 256 outputs, room for 31 of them (the filter leaves about one output
+    // in 250 undecided at K = 2048); what does not fit is summed by the lane that finds it
+    const size_t tiles = (size_t)((N + kI8TileN - 1) / kI8TileN);
+    s.total = s.undecided + (act == BNN_ACT_SIGN ? round_up((size_t)M * tiles * kUndecidedRecord, 256) : 0);
     return s;
 }
 template <int D>
@@ -785,25 +780,18 @@ int launch_realx_i8_gemm(const float* X, const void* Wp, const float* scale, con
     int8_t* planes = reinterpret_cast<int8_t*>(mem + sc.planes);
     int8_t* bytes = reinterpret_cast<int8_t*>(mem + sc.bytes);
     void* meta = mem + sc.meta;
-    unsigned int* counter = reinterpret_cast<unsigned int*>(mem + sc.counter);
-    ListedOutput* list = reinterpret_cast<ListedOutput*>(mem + sc.list);
+    unsigned char* undecided = reinterpret_cast<unsigned char*>(mem + sc.undecided);
     const int qbits = D == 3 ? slab_quant_bits(Ki) : kQuantBits4;
     if ((Ki & 3) == 0 && aligned(X, 16))
-        realx_quantize_nat_kernel<D, true><<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, kpad, qbits, planes, meta,
-                                                                                     D == 3 ? counter : nullptr);
+        realx_quantize_nat_kernel<D, true><<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, kpad, qbits, planes, meta);
     else
-        realx_quantize_nat_kernel<D, false><<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, kpad, qbits, planes, meta,
-                                                                                      D == 3 ? counter : nullptr);
+        realx_quantize_nat_kernel<D, false><<<dim3((Mi + 3) / 4), dim3(256), 0, st>>>(X, Mi, Ki, kpad, qbits, planes, meta);
     const int64_t eb = ((int64_t)Ni * (kpad / 16) + 255) / 256;
     bits_to_bytes_kernel<<<(unsigned)(eb < 16384 ? eb : 16384), 256, 0, st>>>(static_cast<const uint32_t*>(Wp), Ni, Ki, w32, kpad, bytes);
     static std::atomic<int> granted{0};   // more than 64 KB of LDS per workgroup has to be requested explicitly
     if (!granted.load()) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(realx_i8_gemm_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)i8_gemm_lds(D)) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(realx_resolve_list_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)resolve_lds()) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(realx_resolve_list_kernel<false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)resolve_lds()) != hipSuccess) {
+                                (int)i8_gemm_lds(D)) != hipSuccess) {
             (void)hipGetLastError();
             return BNN_EDEVICE;
         }
@@ -811,16 +799,15 @@ int launch_realx_i8_gemm(const float* X, const void* Wp, const float* scale, con
     }
     const dim3 grid((unsigned)((Mi + kI8TileM - 1) / kI8TileM), (unsigned)((Ni + kI8TileN - 1) / kI8TileN));
     realx_i8_gemm_kernel<D><<<grid, kI8Threads, i8_gemm_lds(D), st>>>(planes, bytes, meta, X, static_cast<const uint32_t*>(Wp), scale, bias,
-                                                                      Mi, Ki, kpad, Ni, w32, Y, yw32, list, sc.cap, counter);
+                                                                      Mi, Ki, kpad, Ni, w32, Y, yw32, D == 3 ? undecided : nullptr);
     if (D == 3) {
-        const unsigned int chunks = (sc.cap + kResolveRows - 1) / kResolveRows;
-        const unsigned int rg = chunks < 2048u ? chunks : 2048u;
+        const unsigned int rg = (unsigned int)((Mi + kResolveFrames - 1) / kResolveFrames);
         if ((Ki & 3) == 0 && aligned(X, 16))
-            realx_resolve_list_kernel<true><<<rg, kSlabThreads, resolve_lds(), st>>>(
-                X, static_cast<const uint32_t*>(Wp), scale, bias, Ki, w32, list, counter, sc.cap, static_cast<uint32_t*>(Y), yw32);
+            realx_resolve_rows_kernel<true><<<rg, kResolveThreads, 0, st>>>(X, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki, w32,
+                                                                          undecided, (int)grid.y, static_cast<uint32_t*>(Y), yw32);
         else
-            realx_resolve_list_kernel<false><<<rg, kSlabThreads, resolve_lds(), st>>>(
-                X, static_cast<const uint32_t*>(Wp), scale, bias, Ki, w32, list, counter, sc.cap, static_cast<uint32_t*>(Y), yw32);
+            realx_resolve_rows_kernel<false><<<rg, kResolveThreads, 0, st>>>(X, static_cast<const uint32_t*>(Wp), scale, bias, Mi, Ki, w32,
+                                                                           undecided, (int)grid.y, static_cast<uint32_t*>(Y), yw32);
     }
     return BNN_OK;
 }

@@ -6,8 +6,8 @@
 // What is computed is the filter described in realx_fused_kernel.hpp and realx_slab_kernels.hpp: every frame is scaled by
 // a power of two and rounded to integers xq, P = sum_k b_k xq_k is exact (b = the weight bit), a = 2 P - sum_k xq_k.
 //   Sign layers (three 7-bit digits, |xq| <= 2^qb, qb = 29 - ceil(log2 K) at most 20): an output whose interval
-//     [a - E, a + E] lies on one side of the threshold is decided; the others are listed in global memory and
-//     resolved by the fp32 sum in ascending k (realx_resolve_list_kernel), so every bit is the bit of that sum.
+//     [a - E, a + E] lies on one side of the threshold is decided; the others are listed in global memory, frame by
+//     frame, and resolved by the fp32 sum in ascending k (realx_resolve_rows_kernel), so every bit is the bit of that sum.
 //   Log-Softmax layers (four digits, |xq| <= 2^27): z = fma(scale, a 2^-s, bias), |a 2^-s - sum +-x| < K 2^-27 max|x|.
 //
 // Digits.  xq = d0 + 128 d1 + 16384 d2 (+ 2097152 d3) with d0, d1 (, d2) in 0..127 and the top digit signed.  Two
@@ -21,6 +21,8 @@
 // MFMAs): 2 x 2 waves of 64 frames x 128 outputs each, 2 x 4 accumulator fragments of 32 x 32, twice.
 #pragma once
 
+#include <utility>
+
 #include "realx_slab_kernels.hpp"
 
 namespace bnn {
@@ -28,6 +30,7 @@ namespace bnn {
 typedef int v16i32g __attribute__((ext_vector_type(16)));
 typedef int v4i32g __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4g __attribute__((ext_vector_type(4)));
 
 constexpr int kI8KStep = 64;                       // k per pipeline step
 constexpr int kI8TileM = 128, kI8TileN = 256;      // workgroup tile
@@ -39,8 +42,11 @@ __host__ __device__ constexpr int i8_stage(int digits) { return i8_stage_a(digit
 __host__ __device__ constexpr unsigned i8_gemm_lds(int digits) { return 2u * (unsigned)i8_stage(digits); }    // 81920 / 98304
 __host__ __device__ inline int i8_kpad(int K) { return (K + kI8KStep - 1) / kI8KStep * kI8KStep; }
 
-// An entry of the list of outputs the filter could not decide.
-struct ListedOutput { int m, n; };
+// The outputs the filter could not decide, per frame and tile of 256 outputs: a record of 32 bytes, byte 0 = how many
+// (at most 31), then the outputs' positions in the tile.  Records: [frame][tile], written whole by the one workgroup
+// that owns frame and tile (no atomics in global memory, nothing to clear beforehand).
+constexpr int kUndecidedRecord = 32;
+constexpr int kUndecidedMax = kUndecidedRecord - 1;
 
 // B[n][k] = bit k of weight row n as a byte (0 past K).  One thread per 16 k.  Grid: any number of blocks of 256.
 __global__ __launch_bounds__(256) void bits_to_bytes_kernel(const uint32_t* __restrict__ Wp, int64_t N, int K, int w32, int kpad,
@@ -65,14 +71,11 @@ __global__ __launch_bounds__(256) void bits_to_bytes_kernel(const uint32_t* __re
 
 // One wave per frame: scale, digits (odd digits negated), RowMeta (D = 3) or RowMeta4 (D = 4).  planes: [D][M][kpad].
 // The frame is read twice (largest element, then digits), four consecutive elements per lane.  VEC: K % 4 == 0 and X
-// 16-byte aligned.  `counter` (nullable) is set to 0 by the first thread of the grid: the list of the product kernel
-// that follows in the stream starts empty.  Grid: ceil(M / 4) workgroups of 256 threads.
+// 16-byte aligned.  Grid: ceil(M / 4) workgroups of 256 threads.
 template <int D, bool VEC>
 __global__ __launch_bounds__(256) void realx_quantize_nat_kernel(const float* __restrict__ X, int M, int K, int kpad, int qbits,
-                                                                 int8_t* __restrict__ planes, void* __restrict__ meta_out,
-                                                                 unsigned int* __restrict__ counter) {
+                                                                 int8_t* __restrict__ planes, void* __restrict__ meta_out) {
     static_assert(D == 3 || D == 4, "three digits for Sign layers, four in front of the log-Softmax");
-    if (counter && blockIdx.x == 0 && threadIdx.x == 0) *counter = 0u;
     const int m = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
     if (m >= M) return;   // wave-uniform
     const int lane = lane_id();
@@ -156,17 +159,17 @@ __global__ __launch_bounds__(256) void realx_quantize_nat_kernel(const float* __
 }
 
 // The product kernel.  D = 3: Sign bits into Yv (uint32 words [M][yw32]; bits of listed outputs are left 0) and the
-// list; D = 4: z = fma(scale, a 2^-s, bias) into Yv (fp32 [M][N]).
+// records of undecided outputs into `undecided` ([M][gridDim.y] records); D = 4: z = fma(scale, a 2^-s, bias) into Yv
+// (fp32 [M][N]), `undecided` unused.
 // planes [D][M][kpad], Bb [N][kpad], both 16-byte aligned, kpad % 64 == 0; meta: RowMeta (D = 3) or RowMeta4 (D = 4) [M].
-// X, Wp: the layer's own operands, for the fp32 sum in ascending k of outputs that do not fit the list (D = 3) or of
+// X, Wp: the layer's own operands, for the fp32 sum in ascending k of outputs that do not fit a record (D = 3) or of
 // frames that could not be quantised (D = 4).  Grid: x = ceil(M / 128), y = ceil(N / 256); block = 256 threads;
 // dynamic LDS i8_gemm_lds(D).
 template <int D>
 __global__ __launch_bounds__(kI8Threads) __attribute__((amdgpu_waves_per_eu(1, 1))) void realx_i8_gemm_kernel(
     const int8_t* __restrict__ planes, const int8_t* __restrict__ Bb, const void* __restrict__ meta_in, const float* __restrict__ X,
     const uint32_t* __restrict__ Wp, const float* __restrict__ scale, const float* __restrict__ bias, int M, int K, int kpad, int N,
-    int w32, void* __restrict__ Yv, int yw32, ListedOutput* __restrict__ list, unsigned int list_cap,
-    unsigned int* __restrict__ counter) {
+    int w32, void* __restrict__ Yv, int yw32, unsigned char* __restrict__ undecided) {
     static_assert(D == 3 || D == 4, "three digits for Sign layers, four in front of the log-Softmax");
     extern __shared__ __attribute__((aligned(16))) unsigned char i8_lds[];
     constexpr int WM = 2, WN = 4;
@@ -324,20 +327,21 @@ __global__ __launch_bounds__(kI8Threads) __attribute__((amdgpu_waves_per_eu(1, 1
         // A lane decides its 16 frames of a fragment on its own and keeps the answers as bit masks (bit v: frame v of
         // the fragment): no ballots, no scalar logic, no branch per sum.  The masks of all lanes go to LDS,
         // colmask[frame block of 32][g][output of the tile], and are turned into output words afterwards.
-        // LDS: column masks 4 x 2 x 256 x 2 bytes | the frames' records | the workgroup's own list.
-        constexpr int tw = kI8TileN / 32;
-        constexpr unsigned int kOwnCap = 4096;   // (frame in tile) << 16 | (output in tile); about 130 are expected
+        // LDS: column masks 4 x 2 x 256 x 2 bytes | the frames' quantisation records | per frame: how many undecided
+        // outputs | per frame: their records (about one output per frame is expected at K = 2048).
         uint16_t* colmask = reinterpret_cast<uint16_t*>(i8_lds);
         constexpr int kMaskBytes = 4 * 2 * kI8TileN * 2;
         RowMeta* meta_s = reinterpret_cast<RowMeta*>(i8_lds + kMaskBytes);
-        unsigned int* own = reinterpret_cast<unsigned int*>(i8_lds + kMaskBytes + kI8TileM * sizeof(RowMeta));
-        unsigned int* own_count = own + kOwnCap;   // [0]: entries, [1]: where they start in the global list
-        static_assert(kMaskBytes + kI8TileM * sizeof(RowMeta) + (kOwnCap + 2) * 4 <= i8_gemm_lds(3), "epilogue LDS");
+        unsigned int* und_count = reinterpret_cast<unsigned int*>(i8_lds + kMaskBytes + kI8TileM * sizeof(RowMeta));
+        unsigned char* und = reinterpret_cast<unsigned char*>(und_count + kI8TileM);   // [frame][kUndecidedRecord]
+        static_assert((kMaskBytes + kI8TileM * sizeof(RowMeta)) % 16 == 0 &&
+                          kMaskBytes + kI8TileM * (sizeof(RowMeta) + 4 + kUndecidedRecord) <= i8_gemm_lds(3),
+                      "epilogue LDS");
         if (tid < kI8TileM) {
             const int m = m_tile + tid;
             meta_s[tid] = meta[m < M ? m : M - 1];
+            und_count[tid] = 0u;
         }
-        if (tid == 0) own_count[0] = 0u;
         __syncthreads();
         float sc[WN], bi[WN], asc[WN];
         bool nvalid[WN];
@@ -384,10 +388,10 @@ __global__ __launch_bounds__(kI8Threads) __attribute__((amdgpu_waves_per_eu(1, 1
                     const int v = __builtin_ctz(ub);
                     ub &= ub - 1u;
                     const int ml = fb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-                    const unsigned int slot = atomicAdd(&own_count[0], 1u);
-                    if (slot < kOwnCap) {
-                        own[slot] = ((unsigned int)ml << 16) | (unsigned int)nl;
-                    } else {   // more than the workgroup's list holds: summed here
+                    const unsigned int slot = atomicAdd(&und_count[ml], 1u);
+                    if (slot < (unsigned int)kUndecidedMax) {
+                        und[ml * kUndecidedRecord + 1 + (int)slot] = (unsigned char)nl;
+                    } else {   // more than the frame's record holds: summed here
                         const int m = m_tile + ml, n = n_tile + nl;
                         if (sign_bit(affine(sc[fn], canonical_acc_global(X + (size_t)m * K, Wp + (size_t)n * w32, K), bi[fn]))) bt |= 1u << v;
                     }
@@ -423,25 +427,15 @@ __global__ __launch_bounds__(kI8Threads) __attribute__((amdgpu_waves_per_eu(1, 1
                     if (w_first + c < yw32) y[c] = words[c];
             }
         }
-        // the workgroup's entries go to the global list in one piece (one atomic per workgroup); what the global list
-        // cannot hold is summed here, after the words above have reached memory
-        const unsigned int mine = own_count[0] < kOwnCap ? own_count[0] : kOwnCap;
-        if (tid == 0 && mine) own_count[1] = atomicAdd(counter, mine);
-        __syncthreads();
-        if (mine) {   // workgroup-uniform
-            const unsigned int gbase = own_count[1];
-            for (unsigned int i = (unsigned int)tid; i < mine; i += kI8Threads) {
-                const unsigned int e = own[i];
-                const int ml = (int)(e >> 16), nl = (int)(e & 0xFFFFu);
-                const int m = m_tile + ml, n = n_tile + nl;
-                if (gbase + i < list_cap) {
-                    list[gbase + i] = ListedOutput{m, n};   // resolved by the kernel that follows
-                } else {
-                    const float s1 = scale ? scale[n] : 1.0f, b1 = bias ? bias[n] : 0.0f;
-                    if (sign_bit(affine(s1, canonical_acc_global(X + (size_t)m * K, Wp + (size_t)n * w32, K), b1)))
-                        atomicOr(&Y[(size_t)m * yw32 + (n >> 5)], 1u << (n & 31));
-                }
-            }
+        // the frames' records, 16 bytes per thread (the barrier above also ordered the entries written to them)
+        {
+            const int f = tid >> 1, h = tid & 1;
+            const int m = m_tile + f;
+            u32x4 rec = *reinterpret_cast<const u32x4*>(und + f * kUndecidedRecord + 16 * h);
+            const unsigned int cnt = und_count[f] < (unsigned int)kUndecidedMax ? und_count[f] : (unsigned int)kUndecidedMax;
+            if (h == 0) rec.x = (rec.x & ~0xFFu) | cnt;
+            if (m < M)
+                *reinterpret_cast<u32x4*>(undecided + ((size_t)m * gridDim.y + blockIdx.y) * kUndecidedRecord + 16 * h) = rec;
         }
     } else {
         const RowMeta4* meta = static_cast<const RowMeta4*>(meta_in);
@@ -507,100 +501,187 @@ __global__ __launch_bounds__(kI8Threads) __attribute__((amdgpu_waves_per_eu(1, 1
     }
 }
 
-// The listed outputs, exactly: the fp32 sum in ascending k, acc + (+-x) at every step (it rounds as fma(+-1, x, acc)
-// does), then bit = Sign(fma(scale, sum, bias)) ORed into Y (the product kernel left these bits 0).  A workgroup of
-// 512 threads takes 28 entries at a time: waves 1..7 form the signed terms of 4 outputs each for one slab of 512 k in
-// LDS (four consecutive k per lane; the frame's values and the weight words of the next slab are requested before
-// this slab's terms are added), then lanes 0..27 of wave 0 add their rows.  VEC: K % 4 == 0 and X 16-byte aligned.
-// Grid: any; workgroups stride over the list.  Dynamic LDS resolve_lds() (57 KiB: two workgroups per CU).
-constexpr int kResolveRows = 28;
-__host__ __device__ constexpr unsigned resolve_lds() { return (unsigned)(kResolveRows * kSlabTermRow * 4); }
+// The undecided outputs, exactly: the fp32 sum in ascending k, acc + (+-x) at every step, written as fma(+-1, x, acc)
+// (the product with +-1 is exact, so it rounds as the addition does), then bit = Sign(fma(scale, sum, bias)) ORed into Y
+// (the product kernel left these bits 0).
+// A sum is a chain of K dependent operations, and an output's terms are its frame's values with the signs of its weight
+// row, so the frames are what is worth sharing: a workgroup of 256 threads takes 16 frames, collects their undecided
+// outputs from the records (about 130 at K = 2048, N = 2048) and gives each to a lane.  The frames go through LDS in
+// slabs of 256 k, twice buffered (the next slab is on its way from memory while this one is added up, one barrier per
+// slab); a lane reads its frame's values from there (lanes of one frame read the same address, the 16 frames lie in
+// different banks), forms the signs from its own weight words (eight per slab, read one slab ahead) and adds.
+// More than 256 outputs: further passes over the frames; more than kResolveCap: the lane that finds them sums them
+// from global memory.  The last slab of a frame is padded with +0 and added up to the end of the block of 32 in which the
+// frame ends.
+// VEC: K % 4 == 0 and X 16-byte aligned.  Grid: ceil(M / 16) workgroups of 256 threads.
+constexpr int kResolveFrames = 16;
+constexpr int kResolveSlab = 256;
+constexpr int kResolveLd = kResolveSlab + 4;   // floats per frame in a buffer: frame r starts at bank 4 r
+constexpr int kResolveThreads = 256;
+constexpr int kResolveCap = 1024;
+
+// Term T of a slab and what stands around it (see the kernel); T = -16 .. -1 only start the stream.
+// The factor +-1 of a term is a half-precision number: bits j and j + 16 of a weight word, moved to the sign bits of
+// the two halves of a register over the bit pattern of (1.0, 1.0), serve terms j and j + 16 of the word's 32, and the
+// mixed-precision fused multiply-add takes either half as its first factor (widened exactly; the operation itself is
+// the fp32 one).  Two instructions per pair and one per term instead of three per term.
+// Rings: a shifted word lives for four terms, a pair for twenty, an LDS read for twenty.
+typedef _Float16 f16x2g __attribute__((ext_vector_type(2)));
+// Returns false behind the last term of a block of 32 when the frame ends there or before (kn: terms of this slab).
+template <int T>
+__device__ __forceinline__ bool resolve_term(int kn, const float* xr, const uint32_t (&wc)[kResolveSlab / 32], uint32_t (&sh)[8], uint32_t (&pr)[16],
+                                             f32x4g (&xv)[8], float& acc, uint32_t ones) {
+    if constexpr (T + 16 < kResolveSlab && ((T + 16) & 3) == 0) xv[((T + 16) >> 2) & 7] = *reinterpret_cast<const f32x4g*>(xr + T + 16);
+    if constexpr (T >= 0) {
+        const f16x2g pm = __builtin_bit_cast(f16x2g, pr[T & 15]);
+        acc = __builtin_fmaf((float)pm[(T >> 4) & 1], xv[(T >> 2) & 7][T & 3], acc);
+    }
+    if constexpr (T + 4 >= 0 && T + 4 < kResolveSlab && ((T + 4) & 31) < 16)   // one bit-field insert
+        pr[(T + 4) & 15] = (sh[(T + 4) & 7] & 0x80008000u) | (ones & ~0x80008000u);
+    if constexpr (T + 8 >= 0 && T + 8 < kResolveSlab && ((T + 8) & 31) < 16)
+        sh[(T + 8) & 7] = ~wc[(T + 8) >> 5] << (15 - ((T + 8) & 31));   // weight bit 0: -x
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (T >= 0 && (T & 31) == 31 && T + 1 < kResolveSlab) return T + 1 < kn;   // wave-uniform
+    return true;
+}
+template <int... I>
+__device__ __forceinline__ void resolve_slab(int kn, const float* xr, const uint32_t (&wc)[kResolveSlab / 32], float& acc,
+                                             std::integer_sequence<int, I...>) {
+    uint32_t sh[8];
+    uint32_t pr[16];
+    f32x4g xv[8];
+    uint32_t ones = 0x3C003C00u;   // (1.0, 1.0) in half precision, kept in a register as the insert's third operand
+    asm volatile("" : "+v"(ones));
+    (void)(resolve_term<I - 16>(kn, xr, wc, sh, pr, xv, acc, ones) && ...);
+}
 
 template <bool VEC>
-__global__ __launch_bounds__(kSlabThreads) void realx_resolve_list_kernel(const float* __restrict__ X, const uint32_t* __restrict__ Wp,
-                                                                         const float* __restrict__ scale, const float* __restrict__ bias,
-                                                                         int K, int w32, const ListedOutput* __restrict__ list,
-                                                                         const unsigned int* __restrict__ counter, unsigned int list_cap,
-                                                                         uint32_t* __restrict__ Y, int yw32) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char resolve_raw[];
-    float* terms = reinterpret_cast<float*>(resolve_raw);
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int lane = lane_id();
-    const unsigned int listed = *counter;
-    const int count = (int)(listed < list_cap ? listed : list_cap);
-    const int nsl = (K + kSlabK - 1) / kSlabK;
-    constexpr int kWaves = kSlabThreads / kWave - 1;                  // waves 1 .. 7 prepare terms, wave 0 adds them up
-    constexpr int kPerWave = (kResolveRows + kWaves - 1) / kWaves;   // 4
-    const int pw = wave - 1;
-    for (int base = (int)blockIdx.x * kResolveRows; base < count; base += (int)gridDim.x * kResolveRows) {   // workgroup-uniform
-        const int ne = min(kResolveRows, count - base);
-        float4 xv[kPerWave][2];
-        uint32_t wv[kPerWave][2];
-        auto request = [&](int sl) {
-            if (pw < 0) return;   // wave-uniform
+__global__ __launch_bounds__(kResolveThreads) void realx_resolve_rows_kernel(const float* __restrict__ X, const uint32_t* __restrict__ Wp,
+                                                                           const float* __restrict__ scale, const float* __restrict__ bias,
+                                                                           int M, int K, int w32, const unsigned char* __restrict__ undecided,
+                                                                           int tiles, uint32_t* __restrict__ Y, int yw32) {
+    __shared__ __attribute__((aligned(16))) float xs[2][kResolveFrames][kResolveLd];
+    __shared__ u32x4 ws[2][kResolveThreads][2];   // a lane's eight weight words of a slab
+    __shared__ unsigned int ent[kResolveCap];   // (frame of the workgroup) << 28 | output
+    __shared__ unsigned int total_s;
+    const int tid = (int)threadIdx.x;
+    const int m0 = (int)blockIdx.x * kResolveFrames;
+    const int nsl = (K + kResolveSlab - 1) / kResolveSlab;
+    // a slab is 16 frames x 64 pieces of four k: four pieces per thread
+    constexpr int kPPR = kResolveSlab / 4, kPer = kResolveFrames * kPPR / kResolveThreads;
+    struct Pieces { f32x4g x[kPer]; };   // native vectors: an array of them stays in registers
+    auto request = [&](Pieces& P, int sl) {
 #pragma unroll
-            for (int q = 0; q < kPerWave; ++q) {
-                const int i = min(pw + kWaves * q, ne - 1);   // past the last entry: the last one again (unused)
-                const ListedOutput e = list[base + i];
-                const float* xr = X + (size_t)e.m * K;
-                const uint32_t* wr = Wp + (size_t)e.n * w32;
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int k = sl * kSlabK + 256 * j + 4 * lane;
-                    if (VEC) {   // past K: the row's last four values (in bounds, unused)
-                        xv[q][j] = *reinterpret_cast<const float4*>(xr + min(k, K - 4));
-                    } else {
-                        xv[q][j] = make_float4(xr[min(k, K - 1)], xr[min(k + 1, K - 1)], xr[min(k + 2, K - 1)], xr[min(k + 3, K - 1)]);
-                    }
-                    wv[q][j] = wr[min(k, K - 1) >> 5];
-                }
+        for (int i = 0; i < kPer; ++i) {
+            const int p = tid + kResolveThreads * i;
+            const int m = min(m0 + p / kPPR, M - 1);   // past the last frame: the last one again (unused)
+            const int k = sl * kResolveSlab + 4 * (p % kPPR);
+            const float* xr = X + (size_t)m * K;
+            if (VEC) {   // past K: values of the frame's end (in bounds), replaced by deposit()
+                P.x[i] = *reinterpret_cast<const f32x4g*>(xr + min(k, K - 4));
+            } else {
+                P.x[i] = f32x4g{xr[min(k, K - 1)], xr[min(k + 1, K - 1)], xr[min(k + 2, K - 1)], xr[min(k + 3, K - 1)]};
             }
-        };
-        request(0);
+        }
+    };
+    // past K: +0, which leaves a sum as it is with either sign in front (a sum that starts at +0 never becomes -0).
+    // The first use of what was requested is here, after the slab in between has been added up.
+    auto deposit = [&](const Pieces& P, int sl) {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int p = tid + kResolveThreads * i;
+            const int k = sl * kResolveSlab + 4 * (p % kPPR);
+            f32x4g v = P.x[i];
+            v.x = k < K ? v.x : 0.0f;
+            v.y = k + 1 < K ? v.y : 0.0f;
+            v.z = k + 2 < K ? v.z : 0.0f;
+            v.w = k + 3 < K ? v.w : 0.0f;
+            *reinterpret_cast<f32x4g*>(&xs[sl & 1][p / kPPR][4 * (p % kPPR)]) = v;
+        }
+    };
+    Pieces P;
+    request(P, 0);   // the frames' first slab is on its way while the records are read
+    if (tid == 0) total_s = 0u;
+    __syncthreads();
+    for (int t = tid; t < kResolveFrames * tiles; t += kResolveThreads) {
+        const int r = t / tiles, tile = t - r * tiles;
+        const int m = m0 + r;
+        if (m >= M) continue;
+        const u32x4* rec = reinterpret_cast<const u32x4*>(undecided + ((size_t)m * tiles + tile) * kUndecidedRecord);
+        const u32x4 lo = rec[0];
+        const int cnt = min((int)(lo.x & 0xFFu), kUndecidedMax);
+        if (cnt == 0) continue;
+        const u32x4 hi = rec[1];
+        const unsigned int base = atomicAdd(&total_s, (unsigned int)cnt);
+        for (int i = 0; i < cnt; ++i) {
+            const int b = i + 1;   // byte of the record
+            const unsigned int word = b < 16 ? (b < 8 ? (b < 4 ? lo.x : lo.y) : (b < 12 ? lo.z : lo.w))
+                                             : (b < 24 ? (b < 20 ? hi.x : hi.y) : (b < 28 ? hi.z : hi.w));
+            const int n = tile * kI8TileN + (int)((word >> (8 * (b & 3))) & 0xFFu);
+            if (base + i < (unsigned int)kResolveCap) {
+                ent[base + i] = ((unsigned int)r << 28) | (unsigned int)n;
+            } else {
+                const float s1 = scale ? scale[n] : 1.0f, b1 = bias ? bias[n] : 0.0f;
+                if (sign_bit(affine(s1, canonical_acc_global(X + (size_t)m * K, Wp + (size_t)n * w32, K), b1)))
+                    atomicOr(&Y[(size_t)m * yw32 + (n >> 5)], 1u << (n & 31));
+            }
+        }
+    }
+    __syncthreads();
+    const int total = (int)min(total_s, (unsigned int)kResolveCap);   // workgroup-uniform
+    if (total == 0) return;
+    for (int first = 0; first < total; first += kResolveThreads) {   // workgroup-uniform
+        const bool active = first + tid < total;
+        const unsigned int e = ent[active ? first + tid : 0];
+        const int r = (int)(e >> 28), n = (int)(e & 0x0FFFFFFFu);
+        const uint32_t* wrow = Wp + (size_t)n * w32;
+        const int wlast = (K - 1) >> 5;
+        constexpr int kWords = kResolveSlab / 32;
+        static_assert(kWords == 8, "eight weight words per slab and lane");
         float acc32 = 0.0f;
+        struct Words { u32x4 lo, hi; };
+        auto words = [&](Words& w, int sl) {
+            uint32_t v[kWords];
+#pragma unroll
+            for (int b = 0; b < kWords; ++b) v[b] = wrow[min(sl * kWords + b, wlast)];
+            w.lo = u32x4{v[0], v[1], v[2], v[3]};
+            w.hi = u32x4{v[4], v[5], v[6], v[7]};
+        };
+        // What comes from global memory (the frames' next slab, the lane's next eight weight words) is requested before
+        // the slab is added up and goes to LDS after it: nothing in between waits for memory.
+        Words W;
+        __syncthreads();   // the previous pass no longer reads the buffers
+        if (first > 0) request(P, 0);
+        words(W, 0);
+        deposit(P, 0);
+        ws[0][tid][0] = W.lo;
+        ws[0][tid][1] = W.hi;
+        __syncthreads();
         for (int sl = 0; sl < nsl; ++sl) {
-#pragma unroll
-            for (int q = 0; q < kPerWave; ++q) {
-                const int i = pw + kWaves * q;
-                if (pw >= 0 && i < ne) {   // wave-uniform
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const uint32_t inv = ~wv[q][j] >> ((4 * lane) & 31);                // weight bit 0: -x
-                        float4 t;
-                        t.x = __uint_as_float(__float_as_uint(xv[q][j].x) ^ (inv << 31));
-                        t.y = __uint_as_float(__float_as_uint(xv[q][j].y) ^ ((inv >> 1) << 31));
-                        t.z = __uint_as_float(__float_as_uint(xv[q][j].z) ^ ((inv >> 2) << 31));
-                        t.w = __uint_as_float(__float_as_uint(xv[q][j].w) ^ ((inv >> 3) << 31));
-                        *reinterpret_cast<float4*>(terms + i * kSlabTermRow + 256 * j + 4 * lane) = t;
-                    }
-                }
+            if (sl + 1 < nsl) {   // workgroup-uniform
+                request(P, sl + 1);
+                words(W, sl + 1);
             }
-            __syncthreads();
-            if (sl + 1 < nsl) request(sl + 1);
-            if ((int)threadIdx.x < ne) {
-                const float* tr = terms + threadIdx.x * kSlabTermRow;
-                const int kn = min(kSlabK, K - sl * kSlabK);
-                float4 t4[8], n4[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) t4[j] = *reinterpret_cast<const float4*>(tr + 4 * j);
-                int k = 0;
-                for (; k + 32 <= kn; k += 32) {
-                    const int kn4 = k + 32 < kSlabK ? k + 32 : k;   // past the row's end: re-read (inside the table, unused)
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) n4[j] = *reinterpret_cast<const float4*>(tr + kn4 + 4 * j);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) { acc32 += t4[j].x; acc32 += t4[j].y; acc32 += t4[j].z; acc32 += t4[j].w; }
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) t4[j] = n4[j];
-                }
-                for (; k < kn; ++k) acc32 += tr[k];
+            if (active) {
+                // The slab's 256 terms as one stream (the last slab of a frame is padded with +0).  A result is ready some
+                // clocks after its instruction, and a wave has nothing else to issue meanwhile, so no instruction reads
+                // what one of the two before it wrote: around the addition of term t stand the mask of term t + 4, the
+                // shift of term t + 8 and, every fourth term, the LDS read of terms t + 16 .. t + 19.
+                const u32x4 lo = ws[sl & 1][tid][0], hi = ws[sl & 1][tid][1];
+                const uint32_t wc[kWords] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                resolve_slab(K - sl * kResolveSlab, &xs[sl & 1][r][0], wc, acc32, std::make_integer_sequence<int, kResolveSlab + 16>{});
+            }
+            if (sl + 1 < nsl) {
+                deposit(P, sl + 1);
+                ws[(sl + 1) & 1][tid][0] = W.lo;
+                ws[(sl + 1) & 1][tid][1] = W.hi;
             }
             __syncthreads();
         }
-        if ((int)threadIdx.x < ne) {
-            const ListedOutput e = list[base + threadIdx.x];
-            const float s1 = scale ? scale[e.n] : 1.0f, b1 = bias ? bias[e.n] : 0.0f;
-            if (sign_bit(affine(s1, acc32, b1))) atomicOr(&Y[(size_t)e.m * yw32 + (e.n >> 5)], 1u << (e.n & 31));
+        if (active) {
+            const int m = m0 + r;
+            const float s1 = scale ? scale[n] : 1.0f, b1 = bias ? bias[n] : 0.0f;
+            if (sign_bit(affine(s1, acc32, b1))) atomicOr(&Y[(size_t)m * yw32 + (n >> 5)], 1u << (n & 31));
         }
     }
 }

@@ -117,15 +117,15 @@ def test_real_weight_layers_in_a_chain(bnn):
     d[2]["w_is_real"] = 0
     # layer 2 reads 2048 real inputs and has Sign units: the third region then holds the scratch of its matrix-core
     # filter instead.  128 frames or more (the tiled product): three digit bytes per input and frame, one byte per
-    # weight, 16 bytes per frame, the list's counter (256 bytes) and a list of 8-byte entries for one output in 64
+    # weight, 16 bytes per frame, and a record of 32 bytes per frame and tile of 256 outputs for the undecided ones
     pingpong = 2 * 4096 * 2048 * 4
-    sign_scratch = 3 * 4096 * 2048 + 2048 * 2048 + 4096 * 16 + 256 + 8 * (4096 * 2048 // 64)
+    sign_scratch = 3 * 4096 * 2048 + 2048 * 2048 + 4096 * 16 + 32 * 4096 * (2048 // 256)
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == pingpong + sign_scratch
     # fewer than 128 frames (workgroups of 16 frames): three digit bytes per input and frame plus 16 bytes per frame
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 64) == 2 * 64 * 2048 * 4 + 3 * 64 * 2048 + 64 * 16
     d[1]["act"] = G                # no Sign layer behind real inputs, but a binary-weight output layer that reads real
     d[2]["x_is_binary"] = 0        # inputs: four digit bytes per input and frame, one byte per weight, 16 bytes per frame
-    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == pingpong + 4 * 4096 * 2048 + 3400 * 2048 + 4096 * 16 + 256
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == pingpong + 4 * 4096 * 2048 + 3400 * 2048 + 4096 * 16
     d[2]["w_is_real"] = 1          # real weights there: the planes of both operands only
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d), 3, 4096) == 2 * 4096 * 2048 * 4 + planes
     d[2]["K"], d[1]["N"] = 2041, 2041   # K is padded to a multiple of 32 in the planes (2041 -> 2048), rows to 256 bytes
@@ -141,9 +141,9 @@ def test_real_weight_layers_in_a_chain(bnn):
 
 def test_int8_layer_argument_validation(bnn):
     fn, size = bnn.bnn_layer_binw_realx_i8, bnn.bnn_layer_binw_realx_i8_workspace_bytes
-    # four digit bytes per input and frame, one byte per weight (K padded to 64), 16 bytes per frame, 256 for a counter
-    assert size(4096, 2048, 3400) == 4 * 4096 * 2048 + 3400 * 2048 + 4096 * 16 + 256
-    assert size(3, 5, 7) == 4 * 3 * 64 + (7 * 64 + 255) // 256 * 256 + 256 + 256
+    # four digit bytes per input and frame, one byte per weight (K padded to 64), 16 bytes per frame
+    assert size(4096, 2048, 3400) == 4 * 4096 * 2048 + 3400 * 2048 + 4096 * 16
+    assert size(3, 5, 7) == 4 * 3 * 64 + (7 * 64 + 255) // 256 * 256 + 256
     assert size(4, 8193, 7) == 0 and size(0, 8, 8) == 0 and size(4, 0, 8) == 0
     W = 0x40000000
     need = size(4, 64, 64)
@@ -230,9 +230,9 @@ def test_forward_chain_validation_and_workspace(bnn):
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(binfirst), 2, 4096) == 2 * 4096 * 256
     d2 = _chain(bnn, (440, 2048, 2048, 3400), (H, H, Z))
     # two buffers of 4096 x 2048 fp32, and for the output layer's real inputs four digit planes, one byte per weight,
-    # 16 bytes per frame and 256 bytes for a counter
+    # and 16 bytes per frame
     assert (bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2), 3, 4096) ==
-            2 * 4096 * 2048 * 4 + 4 * 4096 * 2048 + 3400 * 2048 + 4096 * 16 + 256)
+            2 * 4096 * 2048 * 4 + 4 * 4096 * 2048 + 3400 * 2048 + 4096 * 16)
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2), 3, 100) == 2 * 100 * 2048 * 4   # fewer than 128 frames: no planes
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d[:1]), 1, 4096) == 0
     assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d2[:1]), 1, 4096) == 0
