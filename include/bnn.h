@@ -134,6 +134,12 @@ typedef enum bnn_option {
                                        everywhere); 2 = the same with workgroups of eight waves, two per SIMD (measured
                                        2 % slower); 0 = as BNN_OPT_REALX_F32_MFMA says.  The planes of both operands
                                        (six bytes per element, K padded to 32) are part of bnn_forward_workspace_bytes */
+    BNN_OPT_REALW_VALU_LDS = 18,    /* bnn_forward, layer with real-valued weights whose outputs do not go into the
+                                       log-Softmax, 512 frames or more, K a multiple of 4, X 16-byte aligned: 1 = the
+                                       ascending-k sums on fused multiply-adds with three register operands (frames through
+                                       LDS, weights from a transposed copy made once per call: K padded to 64, times N, fp32,
+                                       part of bnn_forward_workspace_bytes); 0 = the kernel of bnn_layer_realw.  Same bits
+                                       (default 1: 130 against 192 us at 4096 x 440 x 2048)                              */
     BNN_OPT_COOPERATIVE_SPIN = 15,  /* polls of the other workgroups' flags before a workgroup of a cooperative kernel gives
                                        up (>= 1; default 2^20, about a second).  A small value makes the bounded wait run
                                        out on purpose: the kernel still ends, its rows are wrong and

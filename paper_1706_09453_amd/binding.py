@@ -29,6 +29,7 @@ BNN_OPT_MFMA32_SPLITK = 14
 BNN_OPT_COOPERATIVE_SPIN = 15
 BNN_OPT_REALX_I8_LOGSOFTMAX = 16
 BNN_OPT_REALW_SPLIT_LOGSOFTMAX = 17
+BNN_OPT_REALW_VALU_LDS = 18
 
 ACT_BY_NAME = {"raw": BNN_ACT_RAW_I32, "linear": BNN_ACT_LINEAR, "hardtanh": BNN_ACT_HARDTANH,
                "sign": BNN_ACT_SIGN, "step01": BNN_ACT_SIGN, "logsoftmax": BNN_ACT_LOGSOFTMAX,

@@ -52,6 +52,7 @@ std::atomic<int> g_mfma32_xcd_order{0};
 std::atomic<int> g_stream_max_frames{64};
 std::atomic<int> g_realx_i8_lsm{1};
 std::atomic<int> g_realw_split_lsm{1};
+std::atomic<int> g_realw_valu_lds{1};
 std::atomic<int> g_cooperative{0};
 std::atomic<int> g_coop_spin{1 << 20};
 std::atomic<int> g_mfma32_splitk{0};
@@ -254,6 +255,7 @@ void launch_realw_valu(const float* X, const float* W, const float* bias, int M,
                        hipStream_t st) {
     if (M <= g_stream_max_frames.load() && M <= 16) launch_realw_valu_tm<2, ACT, 64>(X, W, bias, M, K, N, Y, yw32, st);
     else if (M <= g_stream_max_frames.load()) launch_realw_valu_tm<2, ACT, 16>(X, W, bias, M, K, N, Y, yw32, st);
+    else if (M >= 2048 && getenv("BNN_REALW_TM32")) launch_realw_valu_tm<32, ACT, 16>(X, W, bias, M, K, N, Y, yw32, st);
     else launch_realw_valu_tm<16, ACT, 16>(X, W, bias, M, K, N, Y, yw32, st);
 }
 
@@ -747,6 +749,36 @@ int run_realw_split_lsm(const float* X, const float* W, const float* bias, int64
     return launch_status();
 }
 
+// Layers with real weights whose outputs are not log-Softmax inputs, 512 frames or more, inside bnn_forward: the
+// ascending-k chains of realw_valu_kernel on fmas with three register operands (realw_valu_lds_kernel), from a
+// transposed copy of the weights in the workspace (kpad x N fp32, 256-byte aligned; K padded to 64).
+bool realw_valu_lds_applies(const bnn_layer_desc& d, int64_t M) {
+    return d.w_is_real && d.act != BNN_ACT_LOGSOFTMAX && M >= 512 && (d.K & 3) == 0;
+}
+size_t realw_valu_lds_bytes(int64_t K, int64_t N) {
+    return round_up((size_t)realw_lds_kpad((int)K) * (size_t)N * 4, 256);
+}
+template <int ACT>
+void launch_realw_valu_lds(const float* X, const float* Wt, const float* bias, int M, int K, int kpad, int N, void* Y, int yw32,
+                           hipStream_t st) {
+    const dim3 grid((unsigned)((M + kRealwLdsFrames - 1) / kRealwLdsFrames), (unsigned)((N + 255) / 256));
+    realw_valu_lds_kernel<ACT><<<grid, 256, 0, st>>>(X, Wt, bias, M, K, kpad, N, Y, yw32);
+}
+int run_realw_valu_lds(const float* X, const float* W, const float* bias, int64_t M, int64_t K, int64_t N, int act, int wb, void* Y,
+                       void* scratch_mem, hipStream_t st) {
+    const int Mi = (int)M, Ki = (int)K, Ni = (int)N, kpad = realw_lds_kpad(Ki);
+    const int yw32 = (int)row_w32(N, wb);
+    float* Wt = static_cast<float*>(scratch_mem);
+    weights_transposed_kernel<<<dim3((unsigned)((Ni + 31) / 32), (unsigned)(kpad / 32)), 256, 0, st>>>(W, Ni, Ki, kpad, Wt);
+    switch (act) {
+        case BNN_ACT_SIGN: launch_realw_valu_lds<ACT_SIGN>(X, Wt, bias, Mi, Ki, kpad, Ni, Y, yw32, st); break;
+        case BNN_ACT_HARDTANH: launch_realw_valu_lds<ACT_HARDTANH>(X, Wt, bias, Mi, Ki, kpad, Ni, Y, yw32, st); break;
+        case BNN_ACT_SIGMOID: launch_realw_valu_lds<ACT_SIGMOID>(X, Wt, bias, Mi, Ki, kpad, Ni, Y, yw32, st); break;
+        default: launch_realw_valu_lds<ACT_LINEAR>(X, Wt, bias, Mi, Ki, kpad, Ni, Y, yw32, st); break;
+    }
+    return launch_status();
+}
+
 // Real-input layers with binary weights on the int8 matrix cores as a tiled product (128 frames x 256 outputs per
 // workgroup), inside bnn_forward for batches of 128 frames or more: Sign layers (three digit planes, exact bits: the
 // outputs the filter cannot decide are listed and resolved by a second kernel) and the layer in front of the
@@ -928,6 +960,10 @@ BNN_EXPORT int bnn_set_option(int option, int value) {
         case BNN_OPT_REALW_SPLIT_LOGSOFTMAX:
             if (value < 0 || value > 2) return BNN_EINVAL;
             g_realw_split_lsm.store(value);
+            return BNN_OK;
+        case BNN_OPT_REALW_VALU_LDS:
+            if (value != 0 && value != 1) return BNN_EINVAL;
+            g_realw_valu_lds.store(value);
             return BNN_OK;
         case BNN_OPT_COOPERATIVE_SPIN:
             if (value < 1) return BNN_EINVAL;
@@ -1201,9 +1237,11 @@ static ForwardWorkspace forward_workspace(const bnn_layer_desc* layers, int n_la
             if (b > biggest) biggest = b;
         }
         if (layers[l].w_is_real) {
-            // unpacked binary input first, then the bf16 planes of both operands of a Softmax layer with real weights
+            // unpacked binary input first, then the bf16 planes of both operands of a Softmax layer with real weights, or
+            // the transposed weights of another layer with real weights
             size_t b = layers[l].x_is_binary ? round_up((size_t)M * (size_t)layers[l].K * 4, 256) : 0;
             if (roomy && realw_split_lsm_applies(layers[l], M)) b += realw_split_lsm_bytes(M, layers[l].K, layers[l].N);
+            if (roomy && realw_valu_lds_applies(layers[l], M)) b += realw_valu_lds_bytes(layers[l].K, layers[l].N);
             if (b > unpacked) unpacked = b;
         }
         if (realx_i8_lsm_applies(layers[l], M)) {
@@ -1328,6 +1366,10 @@ static int forward_run(const bnn_layer_desc* layers, int n_layers, const void* X
                     M > g_stream_max_frames.load())
                     rc = run_realw_split_lsm(xin, static_cast<const float*>(d.Wp), d.bias, M, d.K, d.N,
                                              static_cast<float*>(o), planes, st);
+                else if (roomy && realw_valu_lds_applies(d, M) && g_realw_valu_lds.load() && M > g_stream_max_frames.load() &&
+                         !(d.act != BNN_ACT_SIGN && g_realx_f32_mfma.load() == 1) && aligned(xin, 16))
+                    rc = run_realw_valu_lds(xin, static_cast<const float*>(d.Wp), d.bias, M, d.K, d.N, d.act, d.word_bits, o,
+                                            planes, st);
                 else
                     rc = run_realw(xin, static_cast<const float*>(d.Wp), d.bias, M, d.K, d.N, d.act, d.word_bits, o, st);
             } else if (d.x_is_binary) {

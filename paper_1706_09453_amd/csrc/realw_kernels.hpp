@@ -253,4 +253,157 @@ __global__ __launch_bounds__(256) void bits_to_real_kernel(const uint32_t* __res
     }
 }
 
+// ---- real weights, large batches: every fma with three VGPR operands ----
+// The product of realw_valu_kernel (same chains, same bits) at the issue rate of realx_valu_lds_kernel: an fp32 fma with
+// three VGPR operands issues about every 2.7 clocks when two waves share a SIMD, the DPP form of realw_valu_kernel every
+// 4 or more.  A workgroup owns 64 frames x 256 outputs: wave w takes frames 16 w .. 16 w + 15, lane l the outputs
+// n0 + l + 64 j (j < 4): 64 accumulators per lane.  The frames go through LDS in chunks of 64 k (two stages, one barrier
+// per chunk; x[m][k .. k+3] is one broadcast ds_read_b128: one LDS read per 16 fmas).  The weights come from a
+// transposed copy Wt[k][n] (weights_transposed_kernel, once per call): the 64 lanes of a wave read 64 consecutive
+// numbers per k and j, the four waves of a workgroup read the same ones (one fetch from L2 for four), and the numbers
+// of the next four k are requested while these four are used.
+// Rows K .. kpad - 1 of Wt hold 0 and the frames are staged as 0 there: fma(0, 0, acc) returns acc.
+// K a multiple of 4, X 16-byte aligned, kpad = K rounded up to 64.  Grid: x = ceil(M / 64), y = ceil(N / 256).
+constexpr int kRealwLdsKC = 64, kRealwLdsFrames = 64;
+__host__ __device__ inline int realw_lds_kpad(int K) { return (K + kRealwLdsKC - 1) / kRealwLdsKC * kRealwLdsKC; }
+
+// Wt[k][n] = W[n][k] for k < K, 0 for K <= k < kpad.  Tiles of 32 x 32 through LDS.  Grid: x = ceil(N / 32),
+// y = kpad / 32; block = 256 threads (32 x 8).
+__global__ __launch_bounds__(256) void weights_transposed_kernel(const float* __restrict__ W, int N, int K, int kpad,
+                                                                 float* __restrict__ Wt) {
+    __shared__ float tile[32][33];
+    const int tx = (int)threadIdx.x & 31, ty = (int)threadIdx.x >> 5;
+    const int nb = (int)blockIdx.x * 32, kb = (int)blockIdx.y * 32;
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int n = nb + r, k = kb + tx;
+        tile[r][tx] = (n < N && k < K) ? W[(size_t)n * K + k] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = ty; r < 32; r += 8) {
+        const int k = kb + r, n = nb + tx;
+        if (n < N && k < kpad) Wt[(size_t)k * N + n] = tile[tx][r];
+    }
+}
+
+template <int ACT>
+__global__ __launch_bounds__(256, 2) void realw_valu_lds_kernel(const float* __restrict__ X, const float* __restrict__ Wt,
+                                                                const float* __restrict__ bias, int M, int K, int kpad, int N,
+                                                                void* __restrict__ Y, int yw32) {
+    constexpr int KC = kRealwLdsKC, FR = kRealwLdsFrames, TM = 16, TNN = 4, NP = FR * (KC / 4) / 256;
+    __shared__ __attribute__((aligned(16))) float xs[2][FR][KC];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = lane_id();
+    const int n0 = (int)blockIdx.y * (kWave * TNN);
+    const int m0 = (int)blockIdx.x * FR;
+    const int mw = m0 + TM * wave;
+    const bool active = mw < M;   // wave-uniform; an inactive wave still stages its share of x and meets the barriers
+    uint32_t wofs[TNN];   // byte offset of the lane's outputs in a row of Wt (past the last output: its values again, not stored)
+#pragma unroll
+    for (int j = 0; j < TNN; ++j) wofs[j] = 4u * (uint32_t)min(n0 + 64 * j + lane, N - 1);
+    // this thread's NP pieces of the x tile: piece p is row t / 16 + 16 p, floats 4 (t % 16) .. + 3
+    const int prow = (int)threadIdx.x >> 4, pcol = ((int)threadIdx.x & 15) * 4;
+    const float* xsrc[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) xsrc[p] = X + (size_t)min(m0 + prow + 16 * p, M - 1) * K + pcol;
+
+    float acc[TNN][TM];
+#pragma unroll
+    for (int j = 0; j < TNN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) acc[j][i] = 0.0f;
+
+    const int nchunks = kpad / KC;
+    float pre[NP][4];
+    auto fetch_x = [&](int c) {
+        const bool in = c * KC + pcol < K;   // K % 4 == 0: all four values or none; past K re-read the row's first four, unused
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const float4 t = *reinterpret_cast<const float4*>(in ? xsrc[p] + c * KC : xsrc[p] - pcol);
+            pre[p][0] = in ? t.x : 0.0f, pre[p][1] = in ? t.y : 0.0f, pre[p][2] = in ? t.z : 0.0f, pre[p][3] = in ? t.w : 0.0f;
+        }
+    };
+    auto stash = [&](int stage) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+            *reinterpret_cast<float4*>(&xs[stage][prow + 16 * p][pcol]) = make_float4(pre[p][0], pre[p][1], pre[p][2], pre[p][3]);
+    };
+    // the weights of k0 .. k0 + 3 (k0 + 3 < kpad): a row's address is wave-uniform, the lane adds its 32-bit offset.
+    // Requested last to first and used first to last, like the LDS reads of a step: the first use waits for all of them
+    // (one wait instead of sixteen; the other wave of the SIMD has work meanwhile).
+    auto fetch_w = [&](float (&w)[4][TNN], int k0) {
+#pragma unroll
+        for (int kk = 3; kk >= 0; --kk) {
+            const char* row = reinterpret_cast<const char*>(Wt + (size_t)(k0 + kk) * N);
+#pragma unroll
+            for (int j = TNN - 1; j >= 0; --j) {
+                // keeps the 32-bit offset next to its load (scalar base + 32-bit lane offset: no address arithmetic per load)
+                asm volatile("" : "+v"(wofs[j]));
+                w[kk][j] = *reinterpret_cast<const float*>(row + wofs[j]);
+            }
+        }
+    };
+    // A step of 4 k in two halves of 8 frames: the LDS reads of a half are requested before the half in front of it is
+    // multiplied, so only the first half of a chunk waits for LDS.
+    constexpr int HF = TM / 2;
+    auto read_x = [&](float (&xv)[HF][4], int stage, int q, int h) {
+#pragma unroll
+        for (int i = 0; i < HF; ++i) {
+            const float4 t = *reinterpret_cast<const float4*>(&xs[stage][TM * wave + HF * h + i][4 * q]);
+            xv[i][0] = t.x, xv[i][1] = t.y, xv[i][2] = t.z, xv[i][3] = t.w;
+        }
+    };
+    auto multiply = [&](const float (&w)[4][TNN], const float (&xv)[HF][4], int h) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int i = 0; i < HF; ++i)
+#pragma unroll
+                for (int j = 0; j < TNN; ++j) acc[j][HF * h + i] = __builtin_fmaf(w[kk][j], xv[i][kk], acc[j][HF * h + i]);
+    };
+
+    // two sets of weights in turn: the numbers of step q + 1 are requested before step q is multiplied
+    float wa[4][TNN], wb[4][TNN];
+    float xa[HF][4], xb[HF][4];
+    const int klast = kpad - 4;
+    fetch_x(0);
+    fetch_w(wa, 0);
+    stash(0);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        const int stage = c & 1;
+        if (c + 1 < nchunks) fetch_x(c + 1);   // workgroup-uniform
+        const int kc = c * KC;
+        if (active) {   // wave-uniform
+            read_x(xa, stage, 0, 0);
+#pragma unroll 1
+            for (int q = 0; q < KC / 4; q += 2) {   // the request past the last step reads the last four rows again, unused
+                // (nothing moves across the scheduling barriers: reads and requests stay one half-step ahead, no further)
+                fetch_w(wb, min(kc + 4 * q + 4, klast));
+                read_x(xb, stage, q, 1);
+                multiply(wa, xa, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                read_x(xa, stage, q + 1, 0);
+                multiply(wa, xb, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch_w(wa, min(kc + 4 * q + 8, klast));
+                read_x(xb, stage, q + 1, 1);
+                multiply(wb, xa, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                read_x(xa, stage, min(q + 2, KC / 4 - 1), 0);   // behind the chunk's last step: read again, unused
+                multiply(wb, xb, 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (c + 1 < nchunks) stash(stage ^ 1);   // that stage was last read before the previous barrier
+        __syncthreads();
+    }
+    if (!active) return;
+    int dummy[TM];
+#pragma unroll
+    for (int j = 0; j < TNN; ++j)
+        if (n0 + 64 * j < N) epilogue_lanes_n<TM, ACT>(acc[j], dummy, nullptr, bias, mw, M, n0 + 64 * j, n0 + 64 * j + lane, N, Y, yw32);
+}
+
 }  // namespace bnn

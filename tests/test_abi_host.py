@@ -114,6 +114,9 @@ def test_real_weight_layers_in_a_chain(bnn):
     assert bnn.bnn_forward_workspace_bytes(arr, 3, 4096) == 2 * 4096 * 2048 * 4 + 4096 * 2048 * 4 + planes
     # fewer than 128 frames: no matrix-core Softmax layer, no planes (the first two regions: 64 x 2048 fp32 each)
     assert bnn.bnn_forward_workspace_bytes(arr, 3, 64) == 2 * 64 * 2048 * 4 + 64 * 2048 * 4
+    # a real-weight layer that is not the Softmax layer, 512 frames or more: its weights transposed (K padded to 64)
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d[:1]), 1, 4096) == 448 * 2048 * 4
+    assert bnn.bnn_forward_workspace_bytes(bnn.make_layer_array(d[:1]), 1, 511) == 0
     d[2]["w_is_real"] = 0
     # layer 2 reads 2048 real inputs and has Sign units: the third region then holds the scratch of its matrix-core
     # filter instead.  128 frames or more (the tiled product): three digit bytes per input and frame, one byte per

@@ -371,6 +371,76 @@ def test_streaming_real_weight_layer(G, bnn, oracle, M, K, N, act):
         assert np.array_equal(Y.cpu().numpy(), want)
 
 
+def _one_layer_realw_forward(G, bnn, X, W, bias, K, N, act, arm, wb=32):
+    """A one-layer network with real weights through bnn_forward; `arm` = BNN_OPT_REALW_VALU_LDS."""
+    keep = [G.to_dev(W), G.to_dev(bias)]
+    d = [dict(K=K, N=N, act=act, word_bits=wb, x_is_binary=False, w_is_real=True, Wp=G.ptr(keep[0]), scale=0, bias=G.ptr(keep[1]))]
+    arr = bnn.make_layer_array(d)
+    dX = G.to_dev(X)
+    M = dX.shape[0]
+    nbytes = bnn.bnn_forward_workspace_bytes(arr, 1, M)
+    ws = torch.zeros(max(nbytes, 256), dtype=torch.uint8, device=G.DEV)
+    out = (G.word_tensor(M, N, wb) if act == bnn.BNN_ACT_SIGN
+           else torch.full((M, N), float("nan"), dtype=torch.float32, device=G.DEV))
+    bnn.bnn_set_option(bnn.BNN_OPT_REALW_VALU_LDS, arm)
+    try:
+        assert bnn.bnn_forward(arr, 1, G.ptr(dX), M, G.ptr(out), G.ptr(ws), nbytes, G.stream()) == bnn.BNN_OK
+        torch.cuda.synchronize()
+    finally:
+        bnn.bnn_set_option(bnn.BNN_OPT_REALW_VALU_LDS, 1)
+    return G.words_to_host(out, wb) if act == bnn.BNN_ACT_SIGN else out.cpu().numpy()
+
+
+@pytest.mark.parametrize("act", ["sign", "linear", "hardtanh", "sigmoid"])
+@pytest.mark.parametrize("M,K,N", [(512, 4, 1), (513, 12, 70), (600, 440, 300), (1030, 200, 513), (577, 64, 256),
+                                   (2048, 452, 1025), (640, 2048, 257)])
+def test_real_weight_layer_in_forward_register_fmas(G, bnn, oracle, M, K, N, act):
+    """512 frames or more inside bnn_forward: the ascending-k chains of the real-weight layer (paper Sec. 3.1) from the
+    kernel whose fmas take three register operands (frames through LDS, weights from a transposed copy): the oracle's
+    chain, so identical bits, and identical to the other kernel's."""
+    X, W, bias = _rand_realw(M * 5 + K + N, M, K, N)
+    a = bnn.ACT_BY_NAME[act]
+    got = _one_layer_realw_forward(G, bnn, X, W, bias, K, N, a, 1)
+    old = _one_layer_realw_forward(G, bnn, X, W, bias, K, N, a, 0)
+    want = oracle.layer_realw(X, W, bias, act, 32)
+    assert np.array_equal(got.view(np.uint32), old.view(np.uint32))
+    if act == "sigmoid":
+        _close(got, want, act)
+    else:
+        assert np.array_equal(got, want)
+
+
+def test_real_weight_layer_in_forward_register_fmas_special_values(G, bnn, oracle):
+    """NaN, infinities, signed zeros, denormals and huge values in frames and weights: the same bits from both kernels
+    (NaN payloads included), and rows without them as the oracle has them."""
+    M, K, N = 700, 100, 330
+    X, W, bias = _rand_realw(77, M, K, N)
+    X[3, 17] = np.inf
+    X[4, 50] = np.nan
+    X[5] = 0.0
+    X[6] = -0.0
+    X[7] *= np.float32(1e-41)
+    X[8, 99] = np.float32(3e38)
+    X[9, 0] = -np.inf
+    W[10, 3] = np.nan
+    W[11] = -0.0
+    W[12] *= np.float32(1e-40)
+    W[13, 99] = np.float32(3e38)
+    for act in ("linear", "sign", "sigmoid"):
+        a = bnn.ACT_BY_NAME[act]
+        got = _one_layer_realw_forward(G, bnn, X, W, bias, K, N, a, 1)
+        old = _one_layer_realw_forward(G, bnn, X, W, bias, K, N, a, 0)
+        assert np.array_equal(got.view(np.uint32), old.view(np.uint32)), act
+        with np.errstate(all="ignore"):
+            want = oracle.layer_realw(X, W, bias, act, 32)
+        if act == "linear":
+            assert np.array_equal(np.isnan(got), np.isnan(want))
+            fin = ~np.isnan(want)
+            assert np.array_equal(got[fin], want[fin])
+        elif act == "sign":
+            assert np.array_equal(got, want)
+
+
 def test_realw_layer_with_pm1_weights_equals_binary_weight_layer(G, bnn, oracle):
     """Every weight +1 or -1 and no scale: the real-weight layer and the binary-weight layer give the same bits."""
     M, K, N = 70, 440, 300
