@@ -753,7 +753,8 @@ int run_realw_split_lsm(const float* X, const float* W, const float* bias, int64
 // ascending-k chains of realw_valu_kernel on fmas with three register operands (realw_valu_lds_kernel), from a
 // transposed copy of the weights in the workspace (kpad x N fp32, 256-byte aligned; K padded to 64).
 bool realw_valu_lds_applies(const bnn_layer_desc& d, int64_t M) {
-    return d.w_is_real && d.act != BNN_ACT_LOGSOFTMAX && M >= 512 && (d.K & 3) == 0;
+    // (the limits keep the grids of both kernels and the 32-bit byte offset inside a row of the copy in range)
+    return d.w_is_real && d.act != BNN_ACT_LOGSOFTMAX && M >= 512 && (d.K & 3) == 0 && d.K <= 65536 && d.N <= (1 << 22);
 }
 size_t realw_valu_lds_bytes(int64_t K, int64_t N) {
     return round_up((size_t)realw_lds_kpad((int)K) * (size_t)N * 4, 256);
