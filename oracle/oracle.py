@@ -239,6 +239,16 @@ def log_softmax(z: np.ndarray):
     return o32, o64
 
 
+def subtract_log_prior(logp: np.ndarray, log_prior: np.ndarray) -> np.ndarray:
+    """Scaled log-likelihoods for decoding with a hybrid system (the recipe the paper's systems follow, Sec. 3; the
+    paper's own equations end at the Softmax): by Bayes' rule log p(x | s) = log P(s | x) - log P(s) + log p(x), so the
+    log-posterior of every tied state minus the log of that state's prior, the frame's constant left out.
+    out[m][n] = logp[m][n] - log_prior[n], one fp32 subtraction."""
+    logp, log_prior = _c(logp, np.float32), _c(log_prior, np.float32)
+    assert logp.ndim == 2 and log_prior.shape == (logp.shape[1],)
+    return (logp - log_prior[None, :]).astype(np.float32)
+
+
 # ----------------------------------------------------------------------------- layers
 
 def _finish(hhat32: np.ndarray, act: str, word_bits: int):

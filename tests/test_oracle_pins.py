@@ -626,3 +626,26 @@ def test_forward_flipping_a_weight_row_flips_that_hidden_unit(oracle):
     _, k1 = oracle.forward(oracle.make_layers(W2, zero, "sign", 32, use_scale=False), X, keep=True)
     h0 = oracle.unpack_pm1(k0[0], 40, 32); h1 = oracle.unpack_pm1(k1[0], 40, 32)
     assert np.array_equal(h1[:, 5], -h0[:, 5]) and np.array_equal(np.delete(h1, 5, 1), np.delete(h0, 5, 1))
+
+
+def test_subtract_log_prior_bayes_rule_and_rounding(oracle):
+    """Two tied states, two frames with known likelihoods and priors: posterior = likelihood x prior / evidence, so
+    log-posterior minus log-prior is the log-likelihood up to one constant per frame (a wrong sign, or the prior taken
+    along the frames, breaks this).  Then the arithmetic: dyadic values exactly, random values as the correctly rounded
+    exact difference."""
+    lik = np.array([[0.2, 0.6], [0.05, 0.01]])
+    prior = np.array([0.75, 0.25])
+    post = lik * prior / (lik * prior).sum(1, keepdims=True)
+    out = oracle.subtract_log_prior(np.log(post).astype(np.float32), np.log(prior).astype(np.float32)).astype(np.float64)
+    assert np.allclose(out[:, 0] - out[:, 1], np.log(lik[:, 0] / lik[:, 1]), atol=1e-6)
+    assert np.array_equal(oracle.subtract_log_prior(np.array([[-0.5, -2.0], [0.0, -8.0]], np.float32), np.array([-1.0, -0.25], np.float32)),
+                          np.array([[0.5, -1.75], [1.0, -7.75]], np.float32))
+    rng = np.random.default_rng(3)
+    a = -rng.uniform(0.01, 300, (7, 11)).astype(np.float32)
+    b = -rng.uniform(0.5, 12, 11).astype(np.float32)
+    got = oracle.subtract_log_prior(a, b)
+    for m in range(7):
+        for n in range(11):
+            exact = Fraction(float(a[m, n])) - Fraction(float(b[n]))   # fits a double exactly: one rounding to fp32 below
+            assert got[m, n] == np.float32(float(exact))
+    assert np.array_equal(oracle.subtract_log_prior(a, np.zeros(11, np.float32)), a)
