@@ -407,6 +407,13 @@ int bnn_grad_norm_clip(float* g, int64_t count, float alpha, void* workspace, fl
  * w[i] <- Sign(w[i]) where u[i] < |w[i]|.   w in/out [count];  u [count]. */
 int bnn_semi_stochastic_binarize(float* w, const float* u, int64_t count, void* stream);
 
+/* After the output layer (Alg. 2, Softmax at l = L), for decoding with a hybrid system as the recipe of Sec. 3 does (the
+ * paper's equations end at the Softmax): scaled log-likelihoods log p(x | s) + const = log P(s | x) - log P(s).
+ *   logp in/out: DEVICE fp32 [M][N], the log-posteriors bnn_forward wrote;  log_prior: DEVICE fp32 [N], log of each
+ *   tied state's prior (the caller's, e.g. from state counts);  logp[m][n] <- logp[m][n] - log_prior[n], one fp32
+ *   subtraction.  The two buffers must not overlap (BNN_EINVAL).  M = 0 is a no-op. */
+int bnn_subtract_log_prior(float* logp, const float* log_prior, int64_t M, int64_t N, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

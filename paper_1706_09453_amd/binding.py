@@ -80,6 +80,7 @@ _SIGNATURES = {
     "bnn_update_clip": (c_int, [c_void_p, c_void_p, c_int64, c_float, c_int, c_void_p]),
     "bnn_grad_norm_clip": (c_int, [c_void_p, c_int64, c_float, c_void_p, c_void_p, c_void_p]),
     "bnn_semi_stochastic_binarize": (c_int, [c_void_p, c_void_p, c_int64, c_void_p]),
+    "bnn_subtract_log_prior": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_void_p]),
     "bnn_forward_workspace_bytes": (c_size_t, [c_void_p, c_int, c_int64]),
     "bnn_forward": (c_int, [c_void_p, c_int, c_void_p, c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
     "bnn_forward_static": (c_int, [c_void_p, c_int, c_void_p, c_int64, c_void_p, c_void_p]),
@@ -221,6 +222,10 @@ def bnn_update_clip(w: int, g: int, count: int, eta: float, clip: int, stream: i
 
 def bnn_grad_norm_clip(g: int, count: int, alpha: float, workspace: int, norm_out: int, stream: int = 0) -> int:
     return _check(_lib.bnn_grad_norm_clip(g, count, alpha, workspace, norm_out, stream or None))
+
+
+def bnn_subtract_log_prior(logp: int, log_prior: int, M: int, N: int, stream: int = 0) -> int:
+    return _check(_lib.bnn_subtract_log_prior(logp, log_prior, M, N, stream or None))
 
 
 def bnn_semi_stochastic_binarize(w: int, u: int, count: int, stream: int = 0) -> int:

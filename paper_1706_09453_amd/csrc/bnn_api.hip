@@ -1213,6 +1213,16 @@ BNN_EXPORT int bnn_grad_norm_clip(float* g, int64_t count, float alpha, void* wo
     return launch_status();
 }
 
+BNN_EXPORT int bnn_subtract_log_prior(float* logp, const float* log_prior, int64_t M, int64_t N, void* stream) {
+    if (M < 0 || N <= 0 || M > kMaxDim || N > kMaxN) return BNN_ESHAPE;
+    if (M == 0) return BNN_OK;
+    if (!logp || !log_prior) return BNN_EINVAL;
+    if (!aligned(logp, 4) || !aligned(log_prior, 4)) return BNN_EALIGN;
+    if (overlap(logp, (size_t)M * (size_t)N * 4, log_prior, (size_t)N * 4)) return BNN_EINVAL;
+    subtract_log_prior_kernel<<<elementwise_blocks(M * N), 256, 0, static_cast<hipStream_t>(stream)>>>(logp, log_prior, M, (int)N);
+    return launch_status();
+}
+
 BNN_EXPORT int bnn_semi_stochastic_binarize(float* w, const float* u, int64_t count, void* stream) {
     if (count < 0) return BNN_ESHAPE;
     if (count == 0) return BNN_OK;

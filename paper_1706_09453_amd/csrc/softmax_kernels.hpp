@@ -184,4 +184,15 @@ __global__ __launch_bounds__(256) void log_softmax_rows_i16_kernel(float* __rest
     }
 }
 
+// Scaled log-likelihoods for decoding with a hybrid system: logp[m][n] -= log_prior[n] (log-posterior minus the log of
+// the tied state's prior; one fp32 subtraction).  One thread per element, grid-stride.
+__global__ __launch_bounds__(256) void subtract_log_prior_kernel(float* __restrict__ logp, const float* __restrict__ log_prior,
+                                                                 int64_t M, int N) {
+    const int64_t total = M * (int64_t)N;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int n = (int)(e % N);
+        logp[e] = logp[e] - log_prior[n];
+    }
+}
+
 }  // namespace bnn

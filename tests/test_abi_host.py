@@ -192,6 +192,13 @@ def test_training_argument_validation(bnn):
     assert _status(bnn.bnn_grad_norm_clip, P, 16, 0.0, Q, R, 0) == E                 # alpha must be positive
     assert _status(bnn.bnn_grad_norm_clip, P, 16, 15.0, 0, R, 0) == E                # no workspace
     assert _status(bnn.bnn_grad_norm_clip, P, 16, 15.0, Q + 4, R, 0) == A
+    assert _status(bnn.bnn_subtract_log_prior, 0, P, 4, 8, 0) == E                   # null log-posteriors
+    assert _status(bnn.bnn_subtract_log_prior, P, 0, 4, 8, 0) == E                   # null priors
+    assert _status(bnn.bnn_subtract_log_prior, P, P + 64, 4, 8, 0) == E              # the priors inside the output
+    assert _status(bnn.bnn_subtract_log_prior, P, Q, 4, 0, 0) == bnn.BNN_ESHAPE
+    assert _status(bnn.bnn_subtract_log_prior, P, Q, -1, 8, 0) == bnn.BNN_ESHAPE
+    assert _status(bnn.bnn_subtract_log_prior, P + 2, Q, 4, 8, 0) == bnn.BNN_EALIGN
+    assert bnn.bnn_subtract_log_prior(0, 0, 0, 8, 0) == 0                            # no frames: nothing to do
     assert _status(bnn.bnn_semi_stochastic_binarize, P, 0, 16, 0) == E
     assert _status(bnn.bnn_semi_stochastic_binarize, P, P + 8, 16, 0) == E
 

@@ -1242,3 +1242,23 @@ def test_random_shapes_all_layer_kinds(G, bnn, oracle, M, K, N, stream_frames):
                     assert np.array_equal(g_, w_), (act, i)
     finally:
         bnn.bnn_set_option(bnn.BNN_OPT_REALX_F32_MFMA, 0)
+
+
+@pytest.mark.parametrize("M,N", [(1, 1), (3, 5), (70, 3307), (300, 3400), (4096, 3972)])
+def test_subtract_log_prior(G, bnn, oracle, M, N):
+    """Log-posteriors minus log-priors (scaled log-likelihoods for hybrid decoding): one fp32 subtraction per element,
+    identical bits; NaN and infinities pass through as the arithmetic has them."""
+    rng = np.random.default_rng(M + N)
+    z = (rng.standard_normal((M, N)) * 4).astype(np.float32)
+    logp, _ = oracle.log_softmax(z)
+    counts = rng.integers(1, 1000, N).astype(np.float64)
+    log_prior = np.log(counts / counts.sum()).astype(np.float32)
+    if M > 2:
+        logp[1, 0] = -np.inf
+        logp[2, N - 1] = np.nan
+    d = G.to_dev(logp.copy())
+    bnn.bnn_subtract_log_prior(G.ptr(d), G.ptr(G.to_dev(log_prior)), M, N, G.stream())
+    torch.cuda.synchronize()
+    with np.errstate(all="ignore"):
+        want = oracle.subtract_log_prior(logp, log_prior)
+    assert np.array_equal(d.cpu().numpy().view(np.uint32), want.view(np.uint32))
