@@ -163,8 +163,46 @@ def streaming(args, bnn, workloads, G, torch) -> int:
                 model.forward(X, out)
             torch.cuda.synchronize()
             us = (time.perf_counter() - t0) * 1e6 / steps
+            # the same pass waited for every time (what one caller sees from call to result), and as one captured graph
+            # (its launches become one: the host's share of a pass drops from about 27 us to a few)
+            t0 = time.perf_counter()
+            for _ in range(200):
+                model.forward(X, out)
+                torch.cuda.synchronize()
+            us_sync = (time.perf_counter() - t0) * 1e6 / 200
+            us_graph = us_graph_sync = None
+            try:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    model.forward(X, out)
+                torch.cuda.synchronize()
+                eager = out.clone()
+                out.fill_(float("nan"))
+                for _ in range(10):
+                    g.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(out, eager), "a replayed pass gives the eager pass's result"
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    g.replay()
+                torch.cuda.synchronize()
+                us_graph = (time.perf_counter() - t0) * 1e6 / steps
+                t0 = time.perf_counter()
+                for _ in range(200):
+                    g.replay()
+                    torch.cuda.synchronize()
+                us_graph_sync = (time.perf_counter() - t0) * 1e6 / 200
+                del g
+            except Exception as e:
+                print(f"bench.py: graph capture failed ({e})", file=sys.stderr)
+                torch.cuda.synchronize()
             print(json.dumps({"workload": cfg.name.split(" M=")[0] + f" M={M} (streaming)", "batch_frames": M,
                               "latency_us": round(us, 1), "frames_per_s": round(M / (us * 1e-6), 1),
+                              "latency_us_waited_for": round(us_sync, 1),
+                              "latency_us_graph_replay": None if us_graph is None else round(us_graph, 1),
+                              "latency_us_graph_replay_waited_for": None if us_graph_sync is None else round(us_graph_sync, 1),
                               "kernel_launches": model.n_layers + 1}), flush=True)
         del model, Ws, bs
         torch.cuda.empty_cache()
