@@ -274,7 +274,11 @@ int bnn_layer_binw_binx_arm(const void* Xp, const void* Wp, const float* scale, 
  * binary layer as fp32 if a real-weight layer reads them, or for the matrix-core filter of a binary-weight layer with
  * real inputs and Sign units (3 bytes per input and frame, 16 bytes per frame; not needed by a first layer of at most
  * 512 inputs), or for the digit planes of a binary-weight LOGSOFTMAX layer with real inputs (4 bytes per input and
- * frame, 16 per frame, from 128 frames on), whichever is larger.  0 on invalid arguments, and for a one-layer network without such a layer.
+ * frame, 16 per frame, from 128 frames on), whichever is larger; with 128 frames or more these two also hold a byte per
+ * weight (K padded to 64) and, for Sign units, a record of 32 bytes per frame and 256 outputs; a real-weight layer adds
+ * the bf16 pieces of both operands (LOGSOFTMAX, 128 frames or more: 6 bytes per element, K padded to 32) or a
+ * transposed copy of its weights (other activations, 512 frames or more: 4 bytes per weight, K padded to 64).
+ * 0 on invalid arguments, and for a one-layer network without such a layer.
  * HOST helper; layers is a HOST array.
  */
 size_t bnn_forward_workspace_bytes(const bnn_layer_desc* layers, int n_layers, int64_t M);
